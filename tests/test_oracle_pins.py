@@ -1,0 +1,370 @@
+"""Pins for the CPU oracle: everything here runs without a GPU.
+
+The oracle is checked against things it does not itself define: published
+known answers of the generator, a definition-level brute force on tiny
+inputs, special cases that reduce to library routines (stable argsort,
+torch.topk), exact invariants of Algorithm 1, the closed form in the proof
+that rTop-k is a compression operator, and the inclusion probabilities that
+Definition 3's uniform k-subset implies.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+from scipy import stats
+
+import oracle
+from tests import brute
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def bits(x):
+    return np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+
+
+# --------------------------------------------------------------------------
+# generator
+# --------------------------------------------------------------------------
+def _kat_rows():
+    rows = []
+    with open(os.path.join(GOLDEN, "philox4x32_10_kat.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            w = [int(t, 16) for t in line.split()]
+            rows.append((w[0:4], w[4:6], tuple(w[6:10])))
+    assert len(rows) == 3
+    return rows
+
+
+@pytest.mark.parametrize("ctr,key,expect", _kat_rows())
+def test_philox_known_answers(ctr, key, expect):
+    assert oracle.philox4x32_10(ctr, key) == expect
+    assert brute.philox4x32_10(ctr, key) == expect
+
+
+def test_key64_layout_matches_independent_typing():
+    # counter = (index, 0, step_lo, step_hi), key = (seed_lo, seed_hi),
+    # K = out0 << 32 | out1 -- including seeds and steps above 2^32
+    rng = np.random.default_rng(7)
+    for _ in range(200):
+        seed = int(rng.integers(0, 1 << 63)) * 2 + int(rng.integers(0, 2))
+        step = int(rng.integers(0, 1 << 63)) * 2 + int(rng.integers(0, 2))
+        index = int(rng.integers(0, 1 << 32))
+        assert oracle.key64(seed, step, index) == brute.key64(seed, step, index)
+    o = oracle.philox4x32_10((5, 0, 9, 0), (42, 0))
+    assert oracle.key64(42, 9, 5) == (o[0] << 32) | o[1]
+
+
+# --------------------------------------------------------------------------
+# brute force on tiny d: every (r, k), ties, signed zeros, denormals
+# --------------------------------------------------------------------------
+ALPHABET = np.array([0.0, -0.0, 1.0, -1.0, 1.0, 2.0, -2.0, 0.5, 1e-45, -1e-45, 3.5, -3.5],
+                    dtype=np.float32)
+
+
+@pytest.mark.parametrize("d", [1, 2, 5, 8])
+def test_encode_equals_brute_force(d):
+    rng = np.random.default_rng(100 + d)
+    n_vec = 12 if d == 8 else 20
+    for trial in range(n_vec):
+        g = ALPHABET[rng.integers(0, ALPHABET.size, d)]
+        m = ALPHABET[rng.integers(0, ALPHABET.size, d)] if trial % 2 else np.zeros(d, np.float32)
+        for r in range(1, d + 1):
+            for k in range(1, r + 1):
+                seed = int(rng.integers(0, 1 << 40))
+                step = int(rng.integers(0, 1 << 34))
+                oi, ov, om = oracle.encode(g, m, r, k, seed, step)
+                bi, bv, bm = brute.encode(g, m, r, k, seed, step)
+                assert np.array_equal(oi, bi), (g, m, r, k, seed, step)
+                assert np.array_equal(bits(ov), bits(bv))
+                assert np.array_equal(bits(om), bits(bm))
+
+
+def test_top_r_equals_brute_force_with_heavy_ties():
+    rng = np.random.default_rng(5)
+    small = np.array([0.0, -0.0, 1.0, -1.0, 2.0], dtype=np.float32)
+    for _ in range(60):
+        d = int(rng.integers(1, 10))
+        a = small[rng.integers(0, small.size, d)]
+        for r in range(1, d + 1):
+            got = oracle.top_r(a, r)
+            assert tuple(sorted(got.tolist())) == brute.top_r_set(a.tolist(), r)
+            # pi itself: non-increasing magnitude, index ascending inside ties
+            mags = [brute.mag_bits(float(a[i])) for i in got]
+            assert all(mags[j] > mags[j + 1] or (mags[j] == mags[j + 1] and got[j] < got[j + 1])
+                       for j in range(r - 1))
+
+
+# --------------------------------------------------------------------------
+# special cases that reduce to library routines
+# --------------------------------------------------------------------------
+def test_r_equals_k_is_top_k_stable_argsort():
+    rng = np.random.default_rng(11)
+    d = 5000
+    g = rng.standard_normal(d).astype(np.float32)
+    g[rng.integers(0, d, 500)] = 0.25          # ties
+    g[rng.integers(0, d, 500)] = -0.25
+    m = rng.standard_normal(d).astype(np.float32) * 0.1
+    a = g + m
+    mag = bits(a) & 0x7FFFFFFF
+    order = np.argsort(-(mag.astype(np.int64)), kind="stable")
+    for k in (1, 17, 400, 4999, 5000):
+        oi, ov, om = oracle.encode(g, m, k, k, 3, 4)
+        assert np.array_equal(oi, np.sort(order[:k]).astype(np.uint32))
+        assert np.array_equal(bits(ov), bits(a[oi]))
+
+
+def test_top_r_matches_torch_topk_on_distinct_magnitudes():
+    import torch
+    rng = np.random.default_rng(12)
+    d = 20000
+    mags = rng.permutation(d).astype(np.float32) + 1.0
+    a = mags * rng.choice([-1.0, 1.0], d).astype(np.float32)
+    for r in (1, 10, 777, d):
+        want = torch.topk(torch.from_numpy(np.abs(a)), r).indices.numpy()
+        got = oracle.top_r(a, r)
+        assert np.array_equal(got, want.astype(np.uint32))
+
+
+def test_r_equals_d_is_random_k_over_all_coordinates():
+    rng = np.random.default_rng(13)
+    d = 48
+    g = rng.standard_normal(d).astype(np.float32)
+    m = np.zeros(d, np.float32)
+    for k in (1, 7, 47, 48):
+        for seed, step in ((42, 0), (42, 1), (1 << 35, 1 << 33)):
+            oi, _, _ = oracle.encode(g, m, d, k, seed, step)
+            assert oi.tolist() == brute.random_k_subset(range(d), k, seed, step)
+
+
+# --------------------------------------------------------------------------
+# invariants of Definition 3 and Algorithm 1
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("d,r,k", [(1000, 100, 10), (4097, 41, 41), (333, 333, 5), (64, 1, 1)])
+def test_invariants(d, r, k):
+    rng = np.random.default_rng(d + r + k)
+    g = (rng.standard_normal(d) * 10.0 ** rng.uniform(-3, 0, d)).astype(np.float32)
+    g[rng.integers(0, d, d // 10)] = 0.0
+    m = (rng.standard_normal(d) * 1e-2).astype(np.float32)
+    a = g + m
+    idx, val, m2 = oracle.encode(g, m, r, k, 99, 5)
+    assert idx.size == k and np.all(np.diff(idx.astype(np.int64)) > 0)
+    top = set(oracle.top_r(a, r).tolist())
+    assert set(idx.tolist()) <= top
+    # top-r set dominates its complement
+    mag = (bits(a) & 0x7FFFFFFF).astype(np.int64)
+    inside = np.zeros(d, bool)
+    inside[list(top)] = True
+    if r < d:
+        assert mag[inside].min() >= mag[~inside].max()
+        thr = mag[inside].min()
+        tie_in = np.flatnonzero(inside & (mag == thr))
+        tie_out = np.flatnonzero(~inside & (mag == thr))
+        if tie_out.size:
+            assert tie_in.max() < tie_out.min()
+    # values pass through unmodified; memory holds exactly what was not sent
+    assert np.array_equal(bits(val), bits(a[idx]))
+    sent = np.zeros(d, bool)
+    sent[idx] = True
+    assert np.array_equal(bits(m2[~sent]), bits(a[~sent]))
+    assert np.all(bits(m2[sent]) == 0)
+    ghat = np.zeros(d, np.float32)
+    ghat[idx] = val
+    assert np.all(m2 + ghat == a)              # m^{t+1} + ghat^t = g^t + m^t
+
+
+def test_domain_of_definition_3_is_enforced():
+    g = np.ones(8, np.float32)
+    m = np.zeros(8, np.float32)
+    for r, k in ((4, 0), (4, 5), (9, 2), (0, 0)):
+        with pytest.raises(ValueError):
+            oracle.encode(g, m, r, k, 1, 1)
+
+
+def test_memory_makes_a_small_constant_gradient_get_sent():
+    # error compensation: what is not sent is carried over, so a persistent
+    # small component keeps growing in memory until it is selected.
+    rng = np.random.default_rng(21)
+    d, r, k, j = 200, 10, 5, 7
+    m = np.zeros(d, np.float32)
+    sent_at = None
+    for t in range(4000):
+        g = rng.standard_normal(d).astype(np.float32)
+        g[j] = 0.05
+        idx, val, m = oracle.encode(g, m, r, k, 1, t)
+        if j in idx.tolist():
+            sent_at = t
+            break
+    assert sent_at is not None and sent_at > 5
+    assert m[j] == 0.0
+
+
+# --------------------------------------------------------------------------
+# uniformity of U (Definition 3) and the compression-operator closed form
+# --------------------------------------------------------------------------
+def _inclusion_counts(vary, n_draws, d=256, r=64, k=16):
+    rng = np.random.default_rng(31)
+    base = rng.permutation(d).astype(np.float32) + 1.0
+    a = base * rng.choice([-1.0, 1.0], d).astype(np.float32)
+    top = np.sort(oracle.top_r(a, r))
+    pos = {int(i): p for p, i in enumerate(top)}
+    m = np.zeros(d, np.float32)
+    single = np.zeros(r, np.int64)
+    pair = np.zeros((r, r), np.int64)
+    for t in range(n_draws):
+        seed, step = (1000 + t, 3) if vary == "seed" else (77, t)
+        idx, _, _ = oracle.encode(a, m, r, k, seed, step)
+        p = np.array([pos[int(i)] for i in idx])
+        single[p] += 1
+        pair[np.ix_(p, p)] += 1
+    return single, pair
+
+
+@pytest.mark.parametrize("vary", ["seed", "step"])
+def test_each_top_r_member_is_included_with_probability_k_over_r(vary):
+    r, k, N = 64, 16, 20000
+    single, pair = _inclusion_counts(vary, N, r=r, k=k)
+    assert single.sum() == N * k
+    p = k / r
+    # for a fixed-size uniform subset the inclusion counts have covariance
+    # that shrinks the Pearson statistic by (r-1)/r; then it is ~ chi2(r-1)
+    x2 = ((r - 1) / r) * np.sum((single - N * p) ** 2) / (N * p * (1 - p))
+    lo, hi = stats.chi2.ppf([1e-5, 1 - 1e-5], r - 1)
+    assert lo < x2 < hi, x2
+    # pairs: P(i and j both in U) = k(k-1) / (r(r-1))
+    off = pair[~np.eye(r, dtype=bool)]
+    pp = k * (k - 1) / (r * (r - 1))
+    z = (off - N * pp) / np.sqrt(N * pp * (1 - pp))
+    assert np.abs(z).max() < 6.0
+    assert abs(off.mean() / N - pp) < 1e-9     # exact: every draw has k(k-1) ordered pairs
+
+
+def test_expected_squared_error_matches_closed_form():
+    # proof that rTop-k is a compression operator:
+    # E||w - rTop_k(w)||^2 = (1 - k/r) sum_{j<=r} w_j^2 + sum_{j>r} w_j^2 <= (1 - k/d)||w||^2
+    rng = np.random.default_rng(41)
+    d, r, k, N = 400, 50, 10, 6000
+    w = (rng.standard_normal(d) * 10.0 ** rng.uniform(-2, 0, d)).astype(np.float32)
+    m = np.zeros(d, np.float32)
+    w64 = w.astype(np.float64)
+    srt = np.sort(w64 ** 2)[::-1]
+    closed = (1 - k / r) * srt[:r].sum() + srt[r:].sum()
+    assert closed <= (1 - k / d) * (w64 ** 2).sum() + 1e-12
+    errs = np.empty(N)
+    mean_vec = np.zeros(d)
+    for t in range(N):
+        idx, val, _ = oracle.encode(w, m, r, k, 5000 + t, 0)
+        gh = np.zeros(d)
+        gh[idx] = val
+        errs[t] = ((w64 - gh) ** 2).sum()
+        mean_vec += gh
+    se = errs.std(ddof=1) / np.sqrt(N)
+    assert abs(errs.mean() - closed) < 5 * se, (errs.mean(), closed, se)
+    # E[rTop_k(w)] = (k/r) top_r(w)
+    top = oracle.top_r(w, r)
+    want = np.zeros(d)
+    want[top] = w64[top] * k / r
+    sd = np.sqrt((k / r) * (1 - k / r) / N) * np.abs(w64) + 1e-12
+    assert np.all(np.abs(mean_vec / N - want) < 6 * sd)
+
+
+# --------------------------------------------------------------------------
+# master: ghat = (1/n) sum_i ghat_i
+# --------------------------------------------------------------------------
+def test_aggregate_single_worker_is_a_scatter():
+    d = 50
+    idx = np.array([3, 9, 10, 49], np.uint32)
+    val = np.array([1.5, -2.0, 1e-40, 7.0], np.float32)
+    for fn in (oracle.aggregate, oracle.aggregate_f32):
+        out = fn(idx, val, 1, d)
+        want = np.zeros(d, np.float32)
+        want[idx] = val
+        assert np.array_equal(bits(out), bits(want))
+
+
+def test_aggregate_disjoint_supports_divide_by_n_not_by_senders():
+    d, n, k = 64, 4, 3
+    idx = np.arange(n * k, dtype=np.uint32)
+    val = (np.arange(n * k) + 1).astype(np.float32)
+    for fn in (oracle.aggregate, oracle.aggregate_f32):
+        out = fn(idx, val, n, d)
+        want = np.zeros(d, np.float32)
+        want[idx] = val / np.float32(n)
+        assert np.array_equal(out, want)
+        assert np.all(out[n * k:] == 0)
+
+
+def test_aggregate_identical_messages_power_of_two_n_returns_the_value():
+    d, n = 32, 8
+    one_idx = np.array([1, 5, 30], np.uint32)
+    one_val = np.array([0.1, -3.3, 1e-3], np.float32)
+    idx = np.tile(one_idx, n)
+    # binary64 accumulation of 8 binary32 values is exact, so the mean is v
+    out = oracle.aggregate(idx, np.tile(one_val, n), n, d)
+    assert np.array_equal(out[one_idx], one_val)
+    # in binary32 the partial sums 3v, 5v, ... round unless v has a short mantissa
+    short_val = np.array([0.5, -3.25, 96.0], np.float32)
+    out = oracle.aggregate_f32(idx, np.tile(short_val, n), n, d)
+    assert np.array_equal(out[one_idx], short_val)
+
+
+def test_aggregate_equals_dense_mean_and_f32_variant_is_close():
+    rng = np.random.default_rng(51)
+    d, n, k = 300, 5, 40
+    idx = np.stack([np.sort(rng.choice(d, k, replace=False)) for _ in range(n)]).astype(np.uint32)
+    val = rng.standard_normal((n, k)).astype(np.float32)
+    dense = np.zeros((n, d), np.float64)
+    for w in range(n):
+        dense[w, idx[w]] = val[w]
+    want = dense.sum(axis=0) / n                     # the formula, on dense vectors
+    abs_sum = np.abs(dense).sum(axis=0) / n
+    out64 = oracle.aggregate(idx, val, n, d)
+    out32 = oracle.aggregate_f32(idx, val, n, d)
+    assert np.array_equal(out64, want.astype(np.float32))
+    tol = 1e-6 * np.maximum(np.abs(want), abs_sum)
+    assert np.all(np.abs(out32.astype(np.float64) - want) <= tol)
+    untouched = np.setdiff1d(np.arange(d), idx.reshape(-1))
+    assert np.all(bits(out64[untouched]) == 0) and np.all(bits(out32[untouched]) == 0)
+
+
+def test_aggregate_f32_divides_by_n_with_one_correct_rounding():
+    # a coordinate sent by exactly one of n workers must come out as the
+    # correctly rounded quotient v / n (not v times a rounded reciprocal)
+    rng = np.random.default_rng(52)
+    k = 4000
+    for n in (3, 5, 7, 11):
+        d = n * k
+        idx = np.arange(d, dtype=np.uint32)
+        val = (rng.standard_normal(d) * 10.0 ** rng.uniform(-6, 3, d)).astype(np.float32)
+        want = (val.astype(np.float64) / n).astype(np.float32)
+        assert np.any(want != val * (np.float32(1.0) / np.float32(n)))
+        for fn in (oracle.aggregate, oracle.aggregate_f32):
+            assert np.array_equal(bits(fn(idx, val, n, d)), bits(want))
+
+
+def test_aggregate_rejects_out_of_range_index():
+    with pytest.raises(ValueError):
+        oracle.aggregate(np.array([4], np.uint32), np.array([1.0], np.float32), 1, 4)
+
+
+def test_encode_then_aggregate_matches_brute_force_end_to_end():
+    rng = np.random.default_rng(61)
+    d, r, k, n = 9, 5, 2, 3
+    res = [np.zeros(d, np.float32) for _ in range(n)]
+    for t in range(3):
+        msgs_i, msgs_v, dense = [], [], np.zeros(d, np.float64)
+        for w in range(n):
+            g = rng.standard_normal(d).astype(np.float32)
+            bi, bv, bm = brute.encode(g, res[w], r, k, 42 + w, t)
+            oi, ov, om = oracle.encode(g, res[w], r, k, 42 + w, t)
+            assert np.array_equal(oi, bi) and np.array_equal(bits(om), bits(bm))
+            res[w] = om
+            msgs_i.append(oi)
+            msgs_v.append(ov)
+            dense[bi] += bv.astype(np.float64)
+        out = oracle.aggregate(np.concatenate(msgs_i), np.concatenate(msgs_v), n, d)
+        assert np.array_equal(out, (dense / n).astype(np.float32))
