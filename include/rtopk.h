@@ -1,0 +1,126 @@
+/*
+ * rtopk.h -- C ABI of the MI355X (gfx950) rTop-k hot path.
+ *
+ * Two operations, both taken from the paper's problem statement (Section III,
+ * Algorithm 1): per worker, sparsify the error-compensated gradient with the
+ * rTop-k operator of Definition 3; on the master, average the n sparse
+ * messages into one dense update.
+ *
+ * Conventions for every entry point
+ *   - Pointers marked "device" are HIP device pointers valid on the current
+ *     device; pointers marked "host" are ordinary host pointers.
+ *   - The library allocates nothing, keeps no state between calls and never
+ *     synchronises the host (rtopk_encode_stats excepted). Work is enqueued
+ *     on `stream` (a hipStream_t, may be NULL for the default stream) and the
+ *     call returns at once. The caller owns all buffers, workspace included,
+ *     and must keep them alive until the stream has drained.
+ *   - Two calls may run concurrently only with distinct workspaces, residuals
+ *     and outputs.
+ *   - Return value: RTOPK_OK or a negative error code; rtopk_strerror() gives
+ *     a static description. Argument checks are made on the host before
+ *     anything is launched; a failed check launches nothing.
+ *   - Results are a pure function of the argument values and buffer contents:
+ *     they do not depend on grid size, stream or run.
+ */
+#ifndef RTOPK_H
+#define RTOPK_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RTOPK_OK 0
+#define RTOPK_EINVAL (-1)     /* null pointer, or sizes outside 1 <= k <= r <= d < 2^32, n < 1, aliasing */
+#define RTOPK_EWORKSPACE (-2) /* workspace null, misaligned (256 bytes) or too small */
+#define RTOPK_EHIP (-3)       /* a HIP call or kernel launch failed */
+
+/* Bytes of device workspace rtopk_encode needs for these sizes.
+ * bytes: host pointer, written on success. */
+int rtopk_encode_workspace_bytes(uint64_t d, uint64_t r, uint64_t k, uint64_t *bytes);
+
+/* Bytes of device workspace rtopk_aggregate needs for these sizes. */
+int rtopk_aggregate_workspace_bytes(uint64_t d, uint32_t n, uint64_t k, uint64_t *bytes);
+
+/*
+ * One node-side step of Algorithm 1 for one worker:
+ *     a <- grad + residual            (error compensation, one binary32 add)
+ *     U <- rTop-k selection on a      (Definition 3: a uniformly random
+ *                                      k-subset of the r largest-magnitude
+ *                                      coordinates, Definition 1)
+ *     message <- {(i, a_i) : i in U}
+ *     residual <- a - message         (a_i where not sent; a_i - a_i where sent)
+ *
+ * Choices the paper leaves open, fixed here so the result is unique:
+ *   magnitude order = order of the low 31 bits of the binary32 pattern; equal
+ *   magnitudes: lower index first; U = the k members of the top-r set with
+ *   the smallest (K(i), i), K(i) = first two output words (word0 << 32 |
+ *   word1) of Philox4x32-10 with counter (i, 0, step_lo, step_hi) and key
+ *   (seed_lo, seed_hi).
+ *
+ * grad       device, [d] binary32, read only
+ * residual   device, [d] binary32, in: m_t, out: m_{t+1}; must not overlap grad
+ * d, r, k    1 <= k <= r <= d < 2^32
+ * seed,step  select the random subset; a fresh `step` gives a fresh subset,
+ *            distinct `seed`s give independent workers
+ * out_idx    device, [k] uint32, the set U in strictly ascending order
+ * out_val    device, [k] binary32, out_val[j] = a[out_idx[j]]
+ * workspace  device, 256-byte aligned, >= rtopk_encode_workspace_bytes(d,r,k);
+ *            contents on entry are irrelevant, contents on return unspecified
+ * stream     hipStream_t
+ */
+int rtopk_encode(const float *grad, float *residual,
+                 uint64_t d, uint64_t r, uint64_t k,
+                 uint64_t seed, uint64_t step,
+                 uint32_t *out_idx, float *out_val,
+                 void *workspace, uint64_t workspace_bytes, void *stream);
+
+/*
+ * Master step of Algorithm 1: out = (1/n) * sum_{w<n} message_w as a dense
+ * vector. Every coordinate is divided by n, whether or not all workers sent
+ * it; coordinates nobody sent are +0. Sums are formed in binary32 starting
+ * from +0, adding workers in the order 0..n-1 (entries of one message in
+ * position order, so a repeated index is simply added again), followed by
+ * one correctly rounded binary32 division by (float)n. No floating-point
+ * atomics are used, so the result is reproducible bit for bit.
+ *
+ * idx   device, [n*k] uint32, worker-major: worker w owns [w*k, (w+1)*k);
+ *       each worker's slice must be sorted ascending (as rtopk_encode emits
+ *       it); every index must be < d (precondition, not checked)
+ * val   device, [n*k] binary32
+ * out   device, [d] binary32, fully overwritten
+ * workspace  device, 256-byte aligned, >= rtopk_aggregate_workspace_bytes
+ */
+int rtopk_aggregate(const uint32_t *idx, const float *val,
+                    uint32_t n, uint64_t k, uint64_t d,
+                    float *out,
+                    void *workspace, uint64_t workspace_bytes, void *stream);
+
+/*
+ * Diagnostics of the most recent rtopk_encode that used `workspace`.
+ * Synchronises `stream`, then copies a few counters to the host. Not part of
+ * the hot path; tests and profiling use it.
+ */
+typedef struct rtopk_encode_stats {
+    uint32_t error_flags;     /* 0 = clean; bit 0: a bounded device-side wait gave up */
+    uint32_t path;            /* 0: threshold found on a compacted superset; 1: on the full vector */
+    uint32_t threshold_bits;  /* magnitude pattern of the r-th largest |a_i| */
+    uint32_t reserved;
+    uint64_t count_greater;   /* #{i : mag(a_i) > threshold} */
+    uint64_t ties_taken;      /* r - count_greater, taken from the lowest indices */
+    uint64_t superset_size;   /* entries compacted before the exact selection (path 0) */
+    uint64_t key_bucket_size; /* candidates whose sampling key shared the deciding top digit */
+} rtopk_encode_stats_t;
+
+int rtopk_encode_stats(const void *workspace, void *stream, rtopk_encode_stats_t *host_out);
+
+const char *rtopk_strerror(int code);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int rtopk_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RTOPK_H */

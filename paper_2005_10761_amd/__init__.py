@@ -1,0 +1,14 @@
+"""MI355X-native rTop-k gradient sparsification: Python binding of ``librtopk.so``.
+
+The package is argument marshalling only. Every step of the hot path runs in
+the hand-written gfx950 kernels behind the C ABI declared in
+``include/rtopk.h``; PyTorch supplies device memory and streams and nothing
+else. There is no CPU fallback: if the compiled library is missing the import
+of :mod:`paper_2005_10761_amd.binding` symbols fails loudly at first use.
+"""
+from .binding import (RtopkError, aggregate, aggregate_workspace_bytes, encode,
+                      encode_stats, encode_workspace_bytes, library_path, load_library,
+                      strerror, version)
+
+__all__ = ["RtopkError", "aggregate", "aggregate_workspace_bytes", "encode", "encode_stats",
+           "encode_workspace_bytes", "library_path", "load_library", "strerror", "version"]

@@ -1,0 +1,149 @@
+"""ctypes binding of the C ABI in ``include/rtopk.h`` (same names, same
+argument order). Tensors are passed as raw device pointers; no arithmetic of
+the method happens here."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "librtopk.so")
+_LIB: Optional[ctypes.CDLL] = None
+
+EXPORTS = ("rtopk_encode_workspace_bytes", "rtopk_aggregate_workspace_bytes", "rtopk_encode",
+           "rtopk_aggregate", "rtopk_encode_stats", "rtopk_strerror", "rtopk_version")
+
+
+class RtopkError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} (code {code})")
+
+
+class EncodeStats(ctypes.Structure):
+    _fields_ = [("error_flags", ctypes.c_uint32), ("path", ctypes.c_uint32),
+                ("threshold_bits", ctypes.c_uint32), ("reserved", ctypes.c_uint32),
+                ("count_greater", ctypes.c_uint64), ("ties_taken", ctypes.c_uint64),
+                ("superset_size", ctypes.c_uint64), ("key_bucket_size", ctypes.c_uint64)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> ctypes.CDLL:
+    """Load ``librtopk.so``. There is no fallback: a missing library is an error."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2005_10761_amd.build` "
+            "(hipcc, gfx950). The rTop-k path has no CPU or PyTorch fallback.")
+    L = ctypes.CDLL(_LIB_PATH)
+    u64, u32, vp = ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p
+    L.rtopk_encode_workspace_bytes.argtypes = [u64, u64, u64, ctypes.POINTER(u64)]
+    L.rtopk_encode_workspace_bytes.restype = ctypes.c_int
+    L.rtopk_aggregate_workspace_bytes.argtypes = [u64, u32, u64, ctypes.POINTER(u64)]
+    L.rtopk_aggregate_workspace_bytes.restype = ctypes.c_int
+    L.rtopk_encode.argtypes = [vp, vp, u64, u64, u64, u64, u64, vp, vp, vp, u64, vp]
+    L.rtopk_encode.restype = ctypes.c_int
+    L.rtopk_aggregate.argtypes = [vp, vp, u32, u64, u64, vp, vp, u64, vp]
+    L.rtopk_aggregate.restype = ctypes.c_int
+    L.rtopk_encode_stats.argtypes = [vp, vp, ctypes.POINTER(EncodeStats)]
+    L.rtopk_encode_stats.restype = ctypes.c_int
+    L.rtopk_strerror.argtypes = [ctypes.c_int]
+    L.rtopk_strerror.restype = ctypes.c_char_p
+    L.rtopk_version.argtypes = []
+    L.rtopk_version.restype = ctypes.c_int
+    _LIB = L
+    return L
+
+
+def strerror(code: int) -> str:
+    return load_library().rtopk_strerror(int(code)).decode()
+
+
+def version() -> int:
+    return int(load_library().rtopk_version())
+
+
+def encode_workspace_bytes(d: int, r: int, k: int) -> int:
+    out = ctypes.c_uint64(0)
+    rc = load_library().rtopk_encode_workspace_bytes(d, r, k, ctypes.byref(out))
+    if rc:
+        raise RtopkError(rc, "rtopk_encode_workspace_bytes")
+    return int(out.value)
+
+
+def aggregate_workspace_bytes(d: int, n: int, k: int) -> int:
+    out = ctypes.c_uint64(0)
+    rc = load_library().rtopk_aggregate_workspace_bytes(d, n, k, ctypes.byref(out))
+    if rc:
+        raise RtopkError(rc, "rtopk_aggregate_workspace_bytes")
+    return int(out.value)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream_handle(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    h = stream.cuda_stream
+    return h if h else None
+
+
+def _need(t: torch.Tensor, dtype, name: str) -> None:
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{name} must be a contiguous {dtype} tensor on the GPU")
+
+
+def encode(grad: torch.Tensor, residual: torch.Tensor, r: int, k: int, seed: int, step: int,
+           out_idx: torch.Tensor, out_val: torch.Tensor, workspace: torch.Tensor,
+           stream=None) -> None:
+    """rtopk_encode: enqueue one node-side step of Algorithm 1. ``residual`` is
+    updated in place; ``out_idx`` (int32 storage holding uint32 values) and
+    ``out_val`` receive the message."""
+    _need(grad, torch.float32, "grad")
+    _need(residual, torch.float32, "residual")
+    _need(out_idx, torch.int32, "out_idx")
+    _need(out_val, torch.float32, "out_val")
+    d = grad.numel()
+    if residual.numel() != d or out_idx.numel() < k or out_val.numel() < k:
+        raise ValueError("residual must have d elements, out_idx/out_val at least k")
+    rc = load_library().rtopk_encode(
+        _ptr(grad), _ptr(residual), d, r, k, seed & (2**64 - 1), step & (2**64 - 1),
+        _ptr(out_idx), _ptr(out_val), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if rc:
+        raise RtopkError(rc, "rtopk_encode")
+
+
+def aggregate(idx: torch.Tensor, val: torch.Tensor, n: int, k: int, out: torch.Tensor,
+              workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    """rtopk_aggregate: enqueue the master's averaging step. ``idx``/``val`` hold
+    the n messages back to back; ``out`` (d elements) is fully overwritten."""
+    _need(idx, torch.int32, "idx")
+    _need(val, torch.float32, "val")
+    _need(out, torch.float32, "out")
+    if idx.numel() < n * k or val.numel() < n * k:
+        raise ValueError("idx/val must hold n*k entries")
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = load_library().rtopk_aggregate(_ptr(idx), _ptr(val), n, k, out.numel(), _ptr(out),
+                                        _ptr(workspace), ws_bytes, _stream_handle(stream))
+    if rc:
+        raise RtopkError(rc, "rtopk_aggregate")
+
+
+def encode_stats(workspace: torch.Tensor, stream=None) -> dict:
+    st = EncodeStats()
+    rc = load_library().rtopk_encode_stats(_ptr(workspace), _stream_handle(stream),
+                                           ctypes.byref(st))
+    if rc:
+        raise RtopkError(rc, "rtopk_encode_stats")
+    return {name: int(getattr(st, name)) for name, _ in EncodeStats._fields_}

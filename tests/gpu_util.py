@@ -1,0 +1,82 @@
+"""Helpers for the GPU parity tests: run the HIP path through the C ABI and
+hand back numpy arrays to compare with the oracle."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import paper_2005_10761_amd as rt
+
+DEV = torch.device("cuda:0")
+
+
+def bits(x):
+    return np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+
+
+class GpuWorker:
+    """Device-side state of one simulated worker: residual, message buffers,
+    workspace. ``offset`` shifts grad/residual off 16-byte alignment."""
+
+    def __init__(self, d: int, r: int, k: int, residual=None, offset: int = 0):
+        self.d, self.r, self.k, self.offset = d, r, k, offset
+        self._res_store = torch.zeros(d + offset, dtype=torch.float32, device=DEV)
+        self.residual = self._res_store[offset:]
+        if residual is not None:
+            self.residual.copy_(torch.from_numpy(np.ascontiguousarray(residual, np.float32)))
+        self._g_store = torch.empty(d + offset, dtype=torch.float32, device=DEV)
+        self.grad = self._g_store[offset:]
+        self.idx = torch.full((k,), -1, dtype=torch.int32, device=DEV)
+        self.val = torch.full((k,), float("nan"), dtype=torch.float32, device=DEV)
+        self.ws = torch.empty(rt.encode_workspace_bytes(d, r, k), dtype=torch.uint8, device=DEV)
+        # poison the workspace: the library must not depend on its contents
+        self.ws.fill_(0xA5)
+
+    def encode(self, g: np.ndarray, seed: int, step: int, check_stats: bool = True):
+        self.grad.copy_(torch.from_numpy(np.ascontiguousarray(g, np.float32)))
+        rt.encode(self.grad, self.residual, self.r, self.k, seed, step, self.idx, self.val,
+                  self.ws)
+        st = rt.encode_stats(self.ws)
+        if check_stats:
+            assert st["error_flags"] == 0, st
+        self.stats = st
+        return (self.idx.cpu().numpy().view(np.uint32).copy(),
+                self.val.cpu().numpy().copy(),
+                self.residual.cpu().numpy().copy())
+
+
+def gpu_encode_once(g, m, r, k, seed, step, offset=0):
+    w = GpuWorker(len(g), r, k, residual=m, offset=offset)
+    out = w.encode(g, seed, step)
+    return out + (w.stats,)
+
+
+def gpu_aggregate(idx: np.ndarray, val: np.ndarray, n: int, d: int) -> np.ndarray:
+    idx = np.ascontiguousarray(idx, np.uint32).reshape(-1)
+    val = np.ascontiguousarray(val, np.float32).reshape(-1)
+    k = idx.size // n
+    ti = torch.from_numpy(idx.view(np.int32)).to(DEV)
+    tv = torch.from_numpy(val).to(DEV)
+    out = torch.full((d,), float("nan"), dtype=torch.float32, device=DEV)
+    rt.aggregate(ti, tv, n, k, out)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def assert_encode_equal(got, want, what=""):
+    gi, gv, gm = got[:3]
+    wi, wv, wm = want
+    assert np.array_equal(gi, wi), f"{what}: indices differ"
+    assert np.array_equal(bits(gv), bits(wv)), f"{what}: values differ"
+    assert np.array_equal(bits(gm), bits(wm)), f"{what}: residual differs"
+
+
+def assert_aggregate_close(got, idx, val, n, d, want64):
+    """|gpu - ref| <= 1e-6 * max(|ref|, sum_w |v_w| / n): relative to the mean,
+    or to the mean of absolute contributions when those cancel."""
+    scale = np.zeros(d)
+    np.add.at(scale, np.asarray(idx).reshape(-1).astype(np.int64),
+              np.abs(np.asarray(val, np.float64).reshape(-1)) / n)
+    g = got.astype(np.float64)
+    w = want64.astype(np.float64)
+    assert np.all(np.abs(g - w) <= 1e-6 * np.maximum(np.abs(w), scale))

@@ -1,0 +1,66 @@
+"""The C-ABI library loads and exports every symbol include/rtopk.h declares;
+host-side argument checks (no kernel is launched, no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2005_10761_amd as rt
+from paper_2005_10761_amd.binding import EXPORTS
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "rtopk.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return set(re.findall(r"\b(rtopk_[a-z_0-9]+)\s*\(", text))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = rt.load_library()
+    declared = _declared_symbols()
+    assert declared == set(EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_version_and_strerror():
+    assert rt.version() >= 100
+    assert rt.strerror(0) == "ok"
+    for code in (-1, -2, -3, -99):
+        assert isinstance(rt.strerror(code), str) and rt.strerror(code)
+
+
+def test_workspace_queries_validate_definition_3_domain():
+    assert rt.encode_workspace_bytes(1 << 20, 10486, 1049) > 0
+    assert rt.encode_workspace_bytes(1, 1, 1) > 0
+    for d, r, k in ((10, 5, 0), (10, 5, 6), (10, 11, 5), (1 << 32, 5, 5), (0, 0, 0)):
+        with pytest.raises(rt.RtopkError) as e:
+            rt.encode_workspace_bytes(d, r, k)
+        assert e.value.code == -1
+    assert rt.aggregate_workspace_bytes(1000, 4, 10) >= 0
+    with pytest.raises(rt.RtopkError):
+        rt.aggregate_workspace_bytes(1000, 0, 10)
+
+
+def test_encode_rejects_bad_arguments_before_launching():
+    lib = rt.load_library()
+    u64 = ctypes.c_uint64
+    fake = ctypes.c_void_p(0x1000)          # never dereferenced: checks fail first
+    fake2 = ctypes.c_void_p(0x100000)
+    # null pointers
+    assert lib.rtopk_encode(None, fake, 8, 4, 2, 0, 0, fake, fake, fake, u64(1 << 30), None) == -1
+    # k > r
+    assert lib.rtopk_encode(fake, fake2, 8, 4, 5, 0, 0, fake, fake, fake, u64(1 << 30), None) == -1
+    # grad overlaps residual
+    assert lib.rtopk_encode(fake, fake, 8, 4, 2, 0, 0, fake, fake, fake, u64(1 << 30), None) == -1
+    # workspace too small / null / misaligned
+    assert lib.rtopk_encode(fake, fake2, 8, 4, 2, 0, 0, fake, fake, fake, u64(16), None) == -2
+    assert lib.rtopk_encode(fake, fake2, 8, 4, 2, 0, 0, fake, fake, None, u64(1 << 30), None) == -2
+    assert lib.rtopk_encode(fake, fake2, 8, 4, 2, 0, 0, fake, fake, ctypes.c_void_p(0x1010),
+                            u64(1 << 30), None) == -2
+    # aggregate
+    assert lib.rtopk_aggregate(None, fake, 2, 3, 10, fake, None, u64(0), None) == -1
+    assert lib.rtopk_aggregate(fake, fake, 0, 3, 10, fake, None, u64(0), None) == -1

@@ -1,0 +1,252 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle.
+
+Bar: indices, sent values and residual bit-exact; the aggregated average
+within 1e-6 relative of the oracle's binary64 mean (tolerance stated in
+``gpu_util.assert_aggregate_close``) and bit-exact against the oracle's
+binary32 worker-order variant.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from workloads import Workload, philox_seed_for_worker
+
+pytestmark = pytest.mark.gpu
+
+
+def _u():
+    from tests import gpu_util
+    return gpu_util
+
+
+def _check(g, m, r, k, seed, step, offset=0, what=""):
+    u = _u()
+    got = u.gpu_encode_once(g, m, r, k, seed, step, offset=offset)
+    want = oracle.encode(g, m, r, k, seed, step)
+    u.assert_encode_equal(got, want, what or f"d={len(g)} r={r} k={k}")
+    return got[3]
+
+
+# --------------------------------------------------------------------------
+# small adversarial inputs
+# --------------------------------------------------------------------------
+def test_tiny_sizes_every_r_k():
+    rng = np.random.default_rng(1)
+    alphabet = np.array([0.0, -0.0, 1.0, -1.0, 2.0, 0.5, 1e-45, -1e-45, 3.5], np.float32)
+    for d in (1, 2, 3, 5, 7):
+        g = alphabet[rng.integers(0, alphabet.size, d)]
+        m = alphabet[rng.integers(0, alphabet.size, d)]
+        for r in range(1, d + 1):
+            for k in range(1, r + 1):
+                _check(g, m, r, k, 42 + r, k)
+
+
+@pytest.mark.parametrize("d", [63, 64, 255, 257, 4095, 4096, 4097, 3 * 4096 + 17, 100_003])
+@pytest.mark.parametrize("offset", [0, 1])
+def test_random_values_ragged_sizes_and_misaligned_pointers(d, offset):
+    rng = np.random.default_rng(d)
+    g = (rng.standard_normal(d) * 10.0 ** rng.uniform(-3, 0, d)).astype(np.float32)
+    m = (rng.standard_normal(d) * 1e-2).astype(np.float32)
+    r = max(1, d // 50)
+    k = max(1, r // 7)
+    st = _check(g, m, r, k, 7, 3, offset=offset)
+    assert st["count_greater"] + st["ties_taken"] == r
+
+
+def test_degenerate_value_patterns():
+    rng = np.random.default_rng(3)
+    d = 20_000
+    cases = {
+        "all_equal": np.full(d, 0.75, np.float32),
+        "all_zero": np.zeros(d, np.float32),
+        "signed_zero_mix": np.where(rng.random(d) < 0.5, 0.0, -0.0).astype(np.float32),
+        "denormals": (rng.integers(1, 50, d) * np.float32(1e-45) *
+                      rng.choice([-1, 1], d)).astype(np.float32),
+        "two_levels": rng.choice([1.0, -1.0, 2.0], d).astype(np.float32),
+        "mostly_zero": np.where(rng.random(d) < 0.001, rng.standard_normal(d), 0.0).astype(np.float32),
+    }
+    for name, g in cases.items():
+        m = np.zeros(d, np.float32)
+        for r, k in ((200, 20), (d // 2, 1), (d, d // 3), (1, 1), (d, d), (777, 777)):
+            _check(g, m, r, k, 11, 2, what=f"{name} r={r} k={k}")
+
+
+def test_ties_straddling_the_threshold_take_lowest_indices():
+    d = 50_000
+    rng = np.random.default_rng(4)
+    g = rng.standard_normal(d).astype(np.float32) * 0.1
+    tie_pos = rng.choice(d, 3000, replace=False)
+    g[tie_pos] = np.where(rng.random(3000) < 0.5, 5.0, -5.0)     # 3000 ties on top
+    big = rng.choice(np.setdiff1d(np.arange(d), tie_pos), 100, replace=False)
+    g[big] = 9.0 + rng.random(100).astype(np.float32)
+    m = np.zeros(d, np.float32)
+    st = _check(g, m, 1100, 1100, 1, 1)          # r = k: the selection itself is visible
+    assert st["count_greater"] == 100 and st["ties_taken"] == 1000
+    _check(g, m, 1100, 300, 1, 1)
+
+
+def test_huge_tie_bucket_uses_the_full_vector_path():
+    d = 300_000
+    g = np.full(d, -2.5, np.float32)
+    g[::1000] = 3.0
+    m = np.zeros(d, np.float32)
+    st = _check(g, m, 5000, 500, 9, 9)
+    assert st["path"] == 1 and st["count_greater"] == 300 and st["ties_taken"] == 4700
+    st = _check(np.zeros(d, np.float32), m, 1000, 10, 9, 9)
+    assert st["path"] == 1
+
+
+def test_special_cases_top_k_and_random_k():
+    rng = np.random.default_rng(5)
+    d = 30_011
+    g = rng.standard_normal(d).astype(np.float32)
+    m = np.zeros(d, np.float32)
+    _check(g, m, 300, 300, 1, 0)      # r = k : top-k
+    _check(g, m, d, 300, 1, 0)        # r = d : random-k
+    _check(g, m, d, d, 1, 0)          # everything is sent
+    _check(g, m, 300, 1, 1, 0)
+
+
+def test_non_finite_values_are_ordered_by_bit_pattern():
+    d = 5000
+    rng = np.random.default_rng(6)
+    g = rng.standard_normal(d).astype(np.float32)
+    g[10] = np.inf
+    g[20] = -np.inf
+    g[30] = np.nan
+    m = np.zeros(d, np.float32)
+    u = _u()
+    gi, gv, gm, _ = u.gpu_encode_once(g, m, 50, 50, 1, 1)
+    wi, wv, wm = oracle.encode(g, m, 50, 50, 1, 1)
+    assert np.array_equal(gi, wi) and {10, 20, 30} <= set(gi.tolist())
+    assert np.array_equal(u.bits(gv), u.bits(wv))
+    sent = np.zeros(d, bool)
+    sent[gi] = True
+    assert np.array_equal(u.bits(gm[~sent]), u.bits(wm[~sent]))
+    assert np.array_equal(np.isnan(gm[sent]), np.isnan(wm[sent]))
+
+
+def test_seed_and_step_use_all_64_bits():
+    rng = np.random.default_rng(8)
+    d = 9000
+    g = rng.standard_normal(d).astype(np.float32)
+    m = np.zeros(d, np.float32)
+    seen = set()
+    for seed, step in ((1, 1), (1 + (1 << 32), 1), (1, 1 + (1 << 32)), ((1 << 64) - 1, (1 << 63) + 5)):
+        u = _u()
+        got = u.gpu_encode_once(g, m, 900, 90, seed, step)
+        u.assert_encode_equal(got, oracle.encode(g, m, 900, 90, seed, step))
+        seen.add(tuple(got[0].tolist()))
+    assert len(seen) == 4
+
+
+# --------------------------------------------------------------------------
+# multi-step error feedback, several workers, aggregate
+# --------------------------------------------------------------------------
+def _run_config(cfg, d, n_workers, steps, r=None, k=None, check_aggregate=True):
+    u = _u()
+    wl = Workload(cfg, d=d, r=r, k=k)
+    d, r, k = wl.d, wl.r, wl.k
+    gw = [u.GpuWorker(d, r, k) for _ in range(n_workers)]
+    res = [np.zeros(d, np.float32) for _ in range(n_workers)]
+    for t in range(steps):
+        msgs_i, msgs_v = [], []
+        for w in range(n_workers):
+            g = wl.gradient(w, t)
+            seed = philox_seed_for_worker(w)
+            got = gw[w].encode(g, seed, t)
+            oi, ov, res[w] = oracle.encode(g, res[w], r, k, seed, t)
+            u.assert_encode_equal(got, (oi, ov, res[w]), f"cfg{cfg} d={d} w={w} t={t}")
+            msgs_i.append(oi)
+            msgs_v.append(ov)
+        if check_aggregate:
+            ai, av = np.concatenate(msgs_i), np.concatenate(msgs_v)
+            out = u.gpu_aggregate(ai, av, n_workers, d)
+            u.assert_aggregate_close(out, ai, av, n_workers, d, oracle.aggregate(ai, av, n_workers, d))
+            assert np.array_equal(u.bits(out), u.bits(oracle.aggregate_f32(ai, av, n_workers, d)))
+    return gw
+
+
+@pytest.mark.parametrize("cfg,d,n,steps", [(1, 150_001, 1, 5), (2, 400_003, 4, 3), (3, 300_000, 4, 3),
+                                           (4, 660_340, 2, 3), (5, 500_009, 3, 2)])
+def test_scaled_down_configs_with_error_feedback(cfg, d, n, steps):
+    _run_config(cfg, d, n, steps)
+
+
+def test_stress_sweep_points_scaled_down():
+    d = 1 << 20
+    for k_num, k_den in ((1, 10000), (1, 1000), (1, 100)):
+        for ratio in (2, 5, 10):
+            k = max(1, (d * k_num + k_den - 1) // k_den)
+            _run_config(5, d, 2, 2, r=ratio * k, k=k)
+
+
+def test_same_call_twice_gives_identical_bytes():
+    u = _u()
+    wl = Workload(2, d=777_777)
+    g = wl.gradient(0, 0)
+    a = u.gpu_encode_once(g, np.zeros(wl.d, np.float32), wl.r, wl.k, 5, 6)
+    b = u.gpu_encode_once(g, np.zeros(wl.d, np.float32), wl.r, wl.k, 5, 6)
+    u.assert_encode_equal(a, b[:3])
+
+
+def test_resume_from_residual_and_step():
+    u = _u()
+    wl = Workload(3, d=250_000)
+    straight = u.GpuWorker(wl.d, wl.r, wl.k)
+    outs = [straight.encode(wl.gradient(0, t), 42, t) for t in range(5)]
+    first = u.GpuWorker(wl.d, wl.r, wl.k)
+    for t in range(2):
+        mid = first.encode(wl.gradient(0, t), 42, t)
+    resumed = u.GpuWorker(wl.d, wl.r, wl.k, residual=mid[2])
+    for t in range(2, 5):
+        got = resumed.encode(wl.gradient(0, t), 42, t)
+        u.assert_encode_equal(got, outs[t])
+
+
+# --------------------------------------------------------------------------
+# aggregate on its own
+# --------------------------------------------------------------------------
+def test_aggregate_special_cases():
+    u = _u()
+    d = 10_000
+    idx = np.array([3, 9, 4096, 9999], np.uint32)
+    val = np.array([1.5, -2.0, 1e-40, 7.0], np.float32)
+    out = u.gpu_aggregate(idx, val, 1, d)
+    want = np.zeros(d, np.float32)
+    want[idx] = val
+    assert np.array_equal(u.bits(out), u.bits(want))
+    # every worker sends the same pairs, n a power of two
+    n = 8
+    sv = np.array([0.5, -3.25, 96.0, 1.0], np.float32)
+    out = u.gpu_aggregate(np.tile(idx, n), np.tile(sv, n), n, d)
+    assert np.array_equal(out[idx], sv) and np.count_nonzero(out) == 4
+    # one sender out of n: correctly rounded v / n
+    rng = np.random.default_rng(9)
+    for n in (3, 5, 7, 16):
+        k = 1500
+        ii = np.arange(n * k, dtype=np.uint32) * 3
+        vv = rng.standard_normal(n * k).astype(np.float32)
+        out = u.gpu_aggregate(ii, vv, n, 3 * n * k + 5)
+        assert np.array_equal(u.bits(out[ii]), u.bits((vv.astype(np.float64) / n).astype(np.float32)))
+
+
+@pytest.mark.parametrize("d,n,k", [(5000, 3, 100), (4096 * 5 + 3, 16, 700), (1_000_003, 8, 10_000),
+                                   (70, 70, 5), (100_000, 130, 50)])
+def test_aggregate_random_messages(d, n, k):
+    u = _u()
+    rng = np.random.default_rng(d + n)
+    idx = np.stack([np.sort(rng.choice(d, k, replace=False)) for _ in range(n)]).astype(np.uint32)
+    val = (rng.standard_normal((n, k)) * 10.0 ** rng.uniform(-3, 1, (n, k))).astype(np.float32)
+    out = u.gpu_aggregate(idx, val, n, d)
+    u.assert_aggregate_close(out, idx, val, n, d, oracle.aggregate(idx, val, n, d))
+    assert np.array_equal(u.bits(out), u.bits(oracle.aggregate_f32(idx, val, n, d)))
+
+
+def test_aggregate_repeated_index_inside_one_message_is_added_again():
+    u = _u()
+    d, n = 9000, 2
+    idx = np.array([[5, 5, 5, 4100, 4100, 8999], [5, 6, 6, 4100, 8999, 8999]], np.uint32)
+    val = np.array([[1, 2, 3, 4, 5, 6], [7, 8, 9, 10, 11, 12]], np.float32) * np.float32(0.1)
+    out = u.gpu_aggregate(idx, val, n, d)
+    assert np.array_equal(u.bits(out), u.bits(oracle.aggregate_f32(idx, val, n, d)))
