@@ -1,0 +1,243 @@
+#!/usr/bin/env python3
+"""Benchmark of the rTop-k hot path on one MI355X.
+
+One *step* is one pass of the whole hot path over one batch of synthetic
+input: n workers each run ``rtopk_encode`` (error-compensated rTop-k
+sparsification of a fresh d-element gradient) and the master runs
+``rtopk_aggregate`` on the n messages. The workload is the ResNet-50-sized
+configuration (d = 25,557,032, r = 0.5% d, k = 0.1% d, n = 8 workers) that the
+headline metric is quoted on. All gradients of the warm-up and timed steps are
+resident in HBM before the clock starts.
+
+Prints ONE JSON line:
+  value      = gradient bytes consumed per second over whole steps
+               (n * 4d bytes per step / seconds per step), GB/s
+  roofline   = the dominant kernel (fused residual add + first histogram):
+               algorithmic bytes per launch (12 d) over its mean duration,
+               measured with HIP events on the launch stream, against the
+               8 TB/s HBM peak
+  cpu_baseline = the CPU oracle, one thread, timed on a bounded sample of the
+               same workload
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+METRIC = "rTop-k encode gradient GB/s and % of HBM peak at d=25.6M; aggregate GB/s"
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs
+# (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); filled in
+# from the summaries under profiles/ when they exist for this kernel version.
+DOMINANT_KERNEL_TRAFFIC_BYTES = None
+
+
+class HipEvents:
+    """Raw hipEvent_t pairs through the HIP runtime that torch already loaded."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so.7")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float),
+                                                 ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.events = []
+
+    def new(self) -> int:
+        ev = ctypes.c_void_p()
+        rc = self.hip.hipEventCreate(ctypes.byref(ev))
+        if rc != 0:
+            raise RuntimeError(f"hipEventCreate failed: {rc}")
+        self.events.append(ev)
+        return ev.value
+
+    def elapsed_ms(self, a: int, b: int) -> float:
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b)
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
+        return float(ms.value)
+
+    def close(self):
+        for ev in self.events:
+            self.hip.hipEventDestroy(ev)
+        self.events = []
+
+
+def cpu_baseline(wl, n_sample: int):
+    """Time the oracle as it stands on a bounded sample: n_sample encodes of
+    step 0 and one aggregate of those messages, single thread."""
+    import numpy as np
+    import oracle
+    from workloads import philox_seed_for_worker
+    oracle.lib()
+    grads = [wl.gradient(w, 0) for w in range(n_sample)]
+    zero = np.zeros(wl.d, np.float32)
+    t0 = time.perf_counter()
+    msgs = [oracle.encode(grads[w], zero, wl.r, wl.k, philox_seed_for_worker(w), 0)
+            for w in range(n_sample)]
+    t1 = time.perf_counter()
+    idx = np.concatenate([m[0] for m in msgs])
+    val = np.concatenate([m[1] for m in msgs])
+    oracle.aggregate(idx, val, n_sample, wl.d)
+    t2 = time.perf_counter()
+    total = t2 - t0
+    return {
+        "value": round(n_sample * 4 * wl.d / total / 1e9, 4),
+        "unit": "GB/s",
+        "cores": 1,
+        "kind": "oracle",
+        "sample": (f"{n_sample} of {wl.n_workers} workers at step 0: {n_sample} oracle encodes "
+                   f"({t1 - t0:.1f} s) + one aggregate of their messages ({t2 - t1:.2f} s), "
+                   f"d={wl.d}; host has {len(os.sched_getaffinity(0))} usable cores"),
+        "encode_s_per_call": round((t1 - t0) / n_sample, 3),
+        "aggregate_s_per_call": round(t2 - t1, 3),
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=3, help="workload configuration (1-5)")
+    ap.add_argument("--workers", type=int, default=None, help="override the worker count")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=2, help="oracle encodes to time")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; simulated workers share it and no "
+              "collective exists, so --gpus must be 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2005_10761_amd as rt
+    from workloads import Workload, philox_seed_for_worker
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    rt.load_library()
+    dev = torch.device("cuda:0")
+    wl = Workload(args.config)
+    d, r, k = wl.d, wl.r, wl.k
+    n = args.workers or wl.n_workers
+    K, W = args.steps, args.warmup
+    total_steps = K + W
+
+    # ---- inputs: every gradient of every step resident in HBM ------------
+    grads = [[torch.from_numpy(wl.gradient(w, t)).to(dev) for w in range(n)]
+             for t in range(total_steps)]
+    residual = [torch.zeros(d, dtype=torch.float32, device=dev) for _ in range(n)]
+    idx = torch.empty(n * k, dtype=torch.int32, device=dev)
+    val = torch.empty(n * k, dtype=torch.float32, device=dev)
+    out = torch.empty(d, dtype=torch.float32, device=dev)
+    ws = torch.empty(rt.encode_workspace_bytes(d, r, k), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def one_step(t: int, trace=None):
+        for w in range(n):
+            if trace is not None:
+                rt.trace_next_encode(rt.STAGES["fused"], *trace[w])
+            rt.encode(grads[t][w], residual[w], r, k, philox_seed_for_worker(w), t,
+                      idx[w * k:(w + 1) * k], val[w * k:(w + 1) * k], ws, stream)
+        rt.aggregate(idx, val, n, k, out, None, stream)
+
+    for t in range(W):
+        one_step(t)
+    torch.cuda.synchronize()
+
+    # ---- timed region: K steps, events on the launch stream ---------------
+    ev = HipEvents()
+    fused_pairs = [[(ev.new(), ev.new()) for _ in range(n)] for _ in range(K)]
+    phase = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True),
+              torch.cuda.Event(enable_timing=True)) for _ in range(K)]
+    torch.cuda.synchronize()
+    t_wall0 = time.perf_counter()
+    for s in range(K):
+        t = W + s
+        phase[s][0].record(stream)
+        for w in range(n):
+            rt.trace_next_encode(rt.STAGES["fused"], *fused_pairs[s][w])
+            rt.encode(grads[t][w], residual[w], r, k, philox_seed_for_worker(w), t,
+                      idx[w * k:(w + 1) * k], val[w * k:(w + 1) * k], ws, stream)
+        phase[s][1].record(stream)
+        rt.aggregate(idx, val, n, k, out, None, stream)
+        phase[s][2].record(stream)
+    torch.cuda.synchronize()
+    t_wall1 = time.perf_counter()
+
+    stats = rt.encode_stats(ws)
+    if stats["error_flags"] != 0:
+        print(f"bench.py: encode reported error flags {stats}", file=sys.stderr)
+        return 4
+
+    total_ms = phase[0][0].elapsed_time(phase[-1][2])
+    enc_ms = sum(p[0].elapsed_time(p[1]) for p in phase)
+    agg_ms = sum(p[1].elapsed_time(p[2]) for p in phase)
+    fused_ms = [ev.elapsed_ms(a, b) for row in fused_pairs for (a, b) in row]
+    ev.close()
+    ms_per_step = total_ms / K
+    enc_ms_call = enc_ms / (K * n)
+    agg_ms_call = agg_ms / K
+    fused_ms_avg = sum(fused_ms) / len(fused_ms)
+
+    value = n * 4.0 * d / (ms_per_step * 1e-3) / 1e9
+    achieved = 12.0 * d / (fused_ms_avg * 1e-3) / 1e9
+    result = {
+        "metric": METRIC,
+        "value": round(value, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": wl.config.name, "d": d, "r": r, "k": k, "workers": n,
+                   "step": f"{n} x rtopk_encode + 1 x rtopk_aggregate"},
+        "encode_gradient_GBps": round(4.0 * d / (enc_ms_call * 1e-3) / 1e9, 2),
+        "encode_ms_per_call": round(enc_ms_call, 4),
+        "encode_pct_hbm_peak_at_12d": round(100.0 * 12.0 * d / (enc_ms_call * 1e-3) / 1e9
+                                            / HBM_PEAK_GBPS, 2),
+        "aggregate_GBps": round(4.0 * d / (agg_ms_call * 1e-3) / 1e9, 2),
+        "aggregate_ms_per_call": round(agg_ms_call, 4),
+        "wall_ms_per_step": round((t_wall1 - t_wall0) * 1e3 / K, 4),
+        "last_encode": {"path": stats["path"], "superset": stats["superset_size"],
+                        "key_bucket": stats["key_bucket_size"]},
+        "roofline": {
+            "kernel": "k_fused_add_hist",
+            "bound": "hbm",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBPS, 4),
+            "traffic": DOMINANT_KERNEL_TRAFFIC_BYTES,
+            "bytes_per_launch": 12 * d,
+            "avg_launch_ms": round(fused_ms_avg, 5),
+            "launches": len(fused_ms),
+        },
+    }
+    del grads
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, max(1, min(args.cpu_sample, n)))
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

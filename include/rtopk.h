@@ -115,6 +115,23 @@ typedef struct rtopk_encode_stats {
 
 int rtopk_encode_stats(const void *workspace, void *stream, rtopk_encode_stats_t *host_out);
 
+/*
+ * Instrumentation for benchmarks: the NEXT rtopk_encode issued from the
+ * calling host thread records `ev_begin` (a hipEvent_t) on its stream right
+ * before the kernels of `stage` and `ev_end` right after them; the request is
+ * then forgotten. Stage RTOPK_STAGE_ALL brackets the whole call. The events
+ * stay owned by the caller. Passing stage 0 cancels a pending request.
+ */
+#define RTOPK_STAGE_INIT 1      /* clear control block, histograms, scan status */
+#define RTOPK_STAGE_FUSED 2     /* a = g + m, store, first histogram, pick */
+#define RTOPK_STAGE_COMPACT 3   /* superset compaction */
+#define RTOPK_STAGE_REFINE 4    /* remaining magnitude digits */
+#define RTOPK_STAGE_SELECT 5    /* top-r candidates */
+#define RTOPK_STAGE_SAMPLE 6    /* k-of-r: key histogram, collect, resolve */
+#define RTOPK_STAGE_EMIT 7      /* message + residual write-back */
+#define RTOPK_STAGE_ALL 100
+int rtopk_trace_next_encode(int stage, void *ev_begin, void *ev_end);
+
 const char *rtopk_strerror(int code);
 
 /* Library version: major * 10000 + minor * 100 + patch. */

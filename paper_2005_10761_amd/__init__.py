@@ -8,7 +8,7 @@ of :mod:`paper_2005_10761_amd.binding` symbols fails loudly at first use.
 """
 from .binding import (RtopkError, aggregate, aggregate_workspace_bytes, encode,
                       encode_stats, encode_workspace_bytes, library_path, load_library,
-                      strerror, version)
+                      strerror, trace_next_encode, version, STAGES)
 
 __all__ = ["RtopkError", "aggregate", "aggregate_workspace_bytes", "encode", "encode_stats",
-           "encode_workspace_bytes", "library_path", "load_library", "strerror", "version"]
+           "encode_workspace_bytes", "library_path", "load_library", "strerror", "trace_next_encode", "version", "STAGES"]

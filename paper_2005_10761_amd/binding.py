@@ -14,7 +14,8 @@ _LIB_PATH = os.path.join(_HERE, "librtopk.so")
 _LIB: Optional[ctypes.CDLL] = None
 
 EXPORTS = ("rtopk_encode_workspace_bytes", "rtopk_aggregate_workspace_bytes", "rtopk_encode",
-           "rtopk_aggregate", "rtopk_encode_stats", "rtopk_strerror", "rtopk_version")
+           "rtopk_aggregate", "rtopk_encode_stats", "rtopk_trace_next_encode", "rtopk_strerror",
+           "rtopk_version")
 
 
 class RtopkError(RuntimeError):
@@ -55,6 +56,8 @@ def load_library() -> ctypes.CDLL:
     L.rtopk_aggregate.restype = ctypes.c_int
     L.rtopk_encode_stats.argtypes = [vp, vp, ctypes.POINTER(EncodeStats)]
     L.rtopk_encode_stats.restype = ctypes.c_int
+    L.rtopk_trace_next_encode.argtypes = [ctypes.c_int, vp, vp]
+    L.rtopk_trace_next_encode.restype = ctypes.c_int
     L.rtopk_strerror.argtypes = [ctypes.c_int]
     L.rtopk_strerror.restype = ctypes.c_char_p
     L.rtopk_version.argtypes = []
@@ -138,6 +141,18 @@ def aggregate(idx: torch.Tensor, val: torch.Tensor, n: int, k: int, out: torch.T
                                         _ptr(workspace), ws_bytes, _stream_handle(stream))
     if rc:
         raise RtopkError(rc, "rtopk_aggregate")
+
+
+STAGES = {"init": 1, "fused": 2, "compact": 3, "refine": 4, "select": 5, "sample": 6,
+          "emit": 7, "all": 100}
+
+
+def trace_next_encode(stage: int, ev_begin: int, ev_end: int) -> None:
+    """rtopk_trace_next_encode: raw hipEvent_t handles, recorded around ``stage``
+    of the next encode issued from this thread."""
+    rc = load_library().rtopk_trace_next_encode(stage, ev_begin, ev_end)
+    if rc:
+        raise RtopkError(rc, "rtopk_trace_next_encode")
 
 
 def encode_stats(workspace: torch.Tensor, stream=None) -> dict:

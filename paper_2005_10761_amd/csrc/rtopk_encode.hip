@@ -680,6 +680,39 @@ extern "C" int rtopk_encode_workspace_bytes(uint64_t d, uint64_t r, uint64_t k, 
     return RTOPK_OK;
 }
 
+namespace {
+struct TraceRequest {
+    int stage = 0;
+    hipEvent_t begin = nullptr, end = nullptr;
+};
+thread_local TraceRequest g_trace;
+
+// records the requested pair of events around one stage of the pipeline
+struct StageScope {
+    const TraceRequest &tr;
+    hipStream_t stream;
+    bool on;
+    StageScope(const TraceRequest &t, int stage, hipStream_t s)
+        : tr(t), stream(s), on(t.stage == stage)
+    {
+        if (on) (void)hipEventRecord(tr.begin, stream);
+    }
+    ~StageScope()
+    {
+        if (on) (void)hipEventRecord(tr.end, stream);
+    }
+};
+}  // namespace
+
+extern "C" int rtopk_trace_next_encode(int stage, void *ev_begin, void *ev_end)
+{
+    if (stage != 0 && (!ev_begin || !ev_end)) return RTOPK_EINVAL;
+    g_trace.stage = stage;
+    g_trace.begin = (hipEvent_t)ev_begin;
+    g_trace.end = (hipEvent_t)ev_end;
+    return RTOPK_OK;
+}
+
 #define RTOPK_LAUNCH_CHECK()                              \
     do {                                                  \
         if (hipGetLastError() != hipSuccess) return RTOPK_EHIP; \
@@ -719,13 +752,18 @@ extern "C" int rtopk_encode(const float *grad, float *residual, uint64_t d, uint
     auto clamp_grid = [](u64 want, u64 lo, u64 hi) {
         return (unsigned)(want < lo ? lo : (want > hi ? hi : want));
     };
+    const TraceRequest trace = g_trace;
+    g_trace = TraceRequest{};
+    StageScope whole(trace, RTOPK_STAGE_ALL, stream);
 
     {
+        StageScope sc(trace, RTOPK_STAGE_INIT, stream);
         const u64 words = L.zero_bytes / 4;
         k_init<<<clamp_grid((words + 255) / 256, 1, 1024), 256, 0, stream>>>((u32 *)ws, words);
         RTOPK_LAUNCH_CHECK();
     }
     {
+        StageScope sc(trace, RTOPK_STAGE_FUSED, stream);
         const u64 per_block = (u64)kFusedThreads * (vec4 ? 16 : 4);
         const unsigned grid = clamp_grid((d + per_block - 1) / per_block, 1, 512);
         if (vec4)
@@ -737,6 +775,7 @@ extern "C" int rtopk_encode(const float *grad, float *residual, uint64_t d, uint
         RTOPK_LAUNCH_CHECK();
     }
     {
+        StageScope sc(trace, RTOPK_STAGE_COMPACT, stream);
         const bool rvec4 = ((uintptr_t)residual & 15u) == 0;
         if (rvec4)
             k_compact_superset<true><<<L.tiles_full, kTileThreads, 0, stream>>>(
@@ -747,6 +786,7 @@ extern "C" int rtopk_encode(const float *grad, float *residual, uint64_t d, uint
         RTOPK_LAUNCH_CHECK();
     }
     {
+        StageScope sc(trace, RTOPK_STAGE_REFINE, stream);
         const unsigned grid = clamp_grid((L.cap_s + 2047) / 2048, 1, 512);
         k_hist_pass<2><<<grid, kHistThreads, 0, stream>>>(residual, d, s_val, ctl, hist2);
         RTOPK_LAUNCH_CHECK();
@@ -754,21 +794,26 @@ extern "C" int rtopk_encode(const float *grad, float *residual, uint64_t d, uint
         RTOPK_LAUNCH_CHECK();
     }
     {
+        StageScope sc(trace, RTOPK_STAGE_SELECT, stream);
         const unsigned grid = clamp_grid((L.cap_s + kTileElems - 1) / kTileElems, 1, 1024);
         k_select_top_r<<<grid, kTileThreads, 0, stream>>>(residual, d, s_idx, s_val, ctl, st_gt,
                                                          st_eq, cand_idx, cand_val, r);
         RTOPK_LAUNCH_CHECK();
     }
     {
+        StageScope sc(trace, RTOPK_STAGE_SAMPLE, stream);
         const unsigned grid = clamp_grid((r + 2047) / 2048, 1, 512);
         k_key_hist<<<grid, kHistThreads, 0, stream>>>(cand_idx, r, k, ps, ctl, histk);
         RTOPK_LAUNCH_CHECK();
         k_key_collect<<<grid, kHistThreads, 0, stream>>>(cand_idx, r, ps, ctl, m_key, m_idx);
         RTOPK_LAUNCH_CHECK();
     }
-    k_emit<<<L.tiles_cand, kTileThreads, 0, stream>>>(cand_idx, cand_val, r, k, ps, ctl, st_emit,
-                                                      out_idx, out_val, residual);
-    RTOPK_LAUNCH_CHECK();
+    {
+        StageScope sc(trace, RTOPK_STAGE_EMIT, stream);
+        k_emit<<<L.tiles_cand, kTileThreads, 0, stream>>>(cand_idx, cand_val, r, k, ps, ctl,
+                                                          st_emit, out_idx, out_val, residual);
+        RTOPK_LAUNCH_CHECK();
+    }
     return RTOPK_OK;
 }
 
