@@ -217,7 +217,8 @@ def main() -> int:
         "aggregate_ms_per_call": round(agg_ms_call, 4),
         "wall_ms_per_step": round((t_wall1 - t_wall0) * 1e3 / K, 4),
         "last_encode": {"path": stats["path"], "superset": stats["superset_size"],
-                        "key_bucket": stats["key_bucket_size"]},
+                        "boundary_list": stats["boundary_list_size"],
+                        "key_list": stats["key_list_size"]},
         "roofline": {
             "kernel": "k_fused_add_hist",
             "bound": "hbm",

@@ -103,14 +103,16 @@ int rtopk_aggregate(const uint32_t *idx, const float *val,
  * the hot path; tests and profiling use it.
  */
 typedef struct rtopk_encode_stats {
-    uint32_t error_flags;     /* 0 = clean; bit 0: a bounded device-side wait gave up */
-    uint32_t path;            /* 0: threshold found on a compacted superset; 1: on the full vector */
-    uint32_t threshold_bits;  /* magnitude pattern of the r-th largest |a_i| */
-    uint32_t reserved;
-    uint64_t count_greater;   /* #{i : mag(a_i) > threshold} */
-    uint64_t ties_taken;      /* r - count_greater, taken from the lowest indices */
-    uint64_t superset_size;   /* entries compacted before the exact selection (path 0) */
-    uint64_t key_bucket_size; /* candidates whose sampling key shared the deciding top digit */
+    uint32_t error_flags;        /* 0 = clean; bit 1: a selection found no element of the requested
+                                    rank; bit 2: the winners did not add up to k (results invalid) */
+    uint32_t path;               /* 0: both cut points came from the short lists; 1: at least one
+                                    came from the slow selection over the whole candidate buffer */
+    uint32_t threshold_bits;     /* magnitude pattern of the r-th largest |a_i| */
+    uint32_t boundary_list_size; /* candidates that shared the deciding histogram bin */
+    uint64_t count_greater;      /* #{i : mag(a_i) > threshold} */
+    uint64_t ties_taken;         /* r - count_greater, taken from the lowest indices */
+    uint64_t superset_size;      /* entries compacted before the exact selection */
+    uint64_t key_list_size;      /* members whose sampling key fell inside the a-priori window */
 } rtopk_encode_stats_t;
 
 int rtopk_encode_stats(const void *workspace, void *stream, rtopk_encode_stats_t *host_out);
@@ -122,13 +124,12 @@ int rtopk_encode_stats(const void *workspace, void *stream, rtopk_encode_stats_t
  * then forgotten. Stage RTOPK_STAGE_ALL brackets the whole call. The events
  * stay owned by the caller. Passing stage 0 cancels a pending request.
  */
-#define RTOPK_STAGE_INIT 1      /* clear control block, histograms, scan status */
-#define RTOPK_STAGE_FUSED 2     /* a = g + m, store, first histogram, pick */
-#define RTOPK_STAGE_COMPACT 3   /* superset compaction */
-#define RTOPK_STAGE_REFINE 4    /* remaining magnitude digits */
-#define RTOPK_STAGE_SELECT 5    /* top-r candidates */
-#define RTOPK_STAGE_SAMPLE 6    /* k-of-r: key histogram, collect, resolve */
-#define RTOPK_STAGE_EMIT 7      /* message + residual write-back */
+#define RTOPK_STAGE_INIT 1      /* clear control block and histograms */
+#define RTOPK_STAGE_FUSED 2     /* a = g + m, store, first histogram */
+#define RTOPK_STAGE_SCAN 3      /* candidate compaction + second histogram */
+#define RTOPK_STAGE_CLASSIFY 4  /* certain members, key window, short lists */
+#define RTOPK_STAGE_FINALIZE 5  /* exact cut points, output offsets */
+#define RTOPK_STAGE_EMIT 6      /* message + residual write-back */
 #define RTOPK_STAGE_ALL 100
 int rtopk_trace_next_encode(int stage, void *ev_begin, void *ev_end);
 

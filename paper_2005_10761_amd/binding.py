@@ -26,9 +26,9 @@ class RtopkError(RuntimeError):
 
 class EncodeStats(ctypes.Structure):
     _fields_ = [("error_flags", ctypes.c_uint32), ("path", ctypes.c_uint32),
-                ("threshold_bits", ctypes.c_uint32), ("reserved", ctypes.c_uint32),
+                ("threshold_bits", ctypes.c_uint32), ("boundary_list_size", ctypes.c_uint32),
                 ("count_greater", ctypes.c_uint64), ("ties_taken", ctypes.c_uint64),
-                ("superset_size", ctypes.c_uint64), ("key_bucket_size", ctypes.c_uint64)]
+                ("superset_size", ctypes.c_uint64), ("key_list_size", ctypes.c_uint64)]
 
 
 def library_path() -> str:
@@ -143,8 +143,8 @@ def aggregate(idx: torch.Tensor, val: torch.Tensor, n: int, k: int, out: torch.T
         raise RtopkError(rc, "rtopk_aggregate")
 
 
-STAGES = {"init": 1, "fused": 2, "compact": 3, "refine": 4, "select": 5, "sample": 6,
-          "emit": 7, "all": 100}
+STAGES = {"init": 1, "fused": 2, "scan": 3, "classify": 4, "finalize": 5, "emit": 6,
+          "all": 100}
 
 
 def trace_next_encode(stage: int, ev_begin: int, ev_end: int) -> None:
