@@ -220,7 +220,7 @@ def main() -> int:
                         "boundary_list": stats["boundary_list_size"],
                         "key_list": stats["key_list_size"]},
         "roofline": {
-            "kernel": "k_fused_add_hist",
+            "kernel": "k_fused",
             "bound": "hbm",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBPS,

@@ -105,8 +105,9 @@ int rtopk_aggregate(const uint32_t *idx, const float *val,
 typedef struct rtopk_encode_stats {
     uint32_t error_flags;        /* 0 = clean; bit 1: a selection found no element of the requested
                                     rank; bit 2: the winners did not add up to k (results invalid) */
-    uint32_t path;               /* 0: both cut points came from the short lists; 1: at least one
-                                    came from the slow selection over the whole candidate buffer */
+    uint32_t path;               /* 0: both cut points came from the short lists; bit 0: at least one
+                                    came from the slow selection over all candidates; bit 1: the
+                                    sampled estimate failed and the vector itself was walked */
     uint32_t threshold_bits;     /* magnitude pattern of the r-th largest |a_i| */
     uint32_t boundary_list_size; /* candidates that shared the deciding histogram bin */
     uint64_t count_greater;      /* #{i : mag(a_i) > threshold} */
@@ -124,12 +125,11 @@ int rtopk_encode_stats(const void *workspace, void *stream, rtopk_encode_stats_t
  * then forgotten. Stage RTOPK_STAGE_ALL brackets the whole call. The events
  * stay owned by the caller. Passing stage 0 cancels a pending request.
  */
-#define RTOPK_STAGE_INIT 1      /* clear control block and histograms */
-#define RTOPK_STAGE_FUSED 2     /* a = g + m, store, first histogram */
-#define RTOPK_STAGE_SCAN 3      /* candidate compaction + second histogram */
-#define RTOPK_STAGE_CLASSIFY 4  /* certain members, key window, short lists */
-#define RTOPK_STAGE_FINALIZE 5  /* exact cut points, output offsets */
-#define RTOPK_STAGE_EMIT 6      /* message + residual write-back */
+#define RTOPK_STAGE_PREPARE 1   /* sample a = g + m, estimate the threshold range, clear counters */
+#define RTOPK_STAGE_FUSED 2     /* a = g + m, store, candidates + histogram */
+#define RTOPK_STAGE_CLASSIFY 3  /* certain members, key window, short lists */
+#define RTOPK_STAGE_FINALIZE 4  /* exact cut points, output offsets */
+#define RTOPK_STAGE_EMIT 5      /* message + residual write-back */
 #define RTOPK_STAGE_ALL 100
 int rtopk_trace_next_encode(int stage, void *ev_begin, void *ev_end);
 

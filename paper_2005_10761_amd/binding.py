@@ -143,8 +143,7 @@ def aggregate(idx: torch.Tensor, val: torch.Tensor, n: int, k: int, out: torch.T
         raise RtopkError(rc, "rtopk_aggregate")
 
 
-STAGES = {"init": 1, "fused": 2, "scan": 3, "classify": 4, "finalize": 5, "emit": 6,
-          "all": 100}
+STAGES = {"prepare": 1, "fused": 2, "classify": 3, "finalize": 4, "emit": 5, "all": 100}
 
 
 def trace_next_encode(stage: int, ev_begin: int, ev_end: int) -> None:

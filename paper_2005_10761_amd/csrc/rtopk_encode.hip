@@ -1,77 +1,131 @@
 // rtopk_encode: one node-side step of Algorithm 1 (error compensation, the
-// rTop-k operator of Definition 3, residual write-back) as a chain of gfx950
-// kernels. All cross-kernel state lives in the caller's workspace.
+// rTop-k operator of Definition 3, residual write-back) as a chain of six
+// gfx950 kernels that stream the gradient and the residual exactly once
+// (12d bytes). All cross-kernel state lives in the caller's workspace.
 //
-// The vector is cut into W contiguous chunks, one per wavefront, and every
-// chunk owns a slice of the candidate buffer S as long as the chunk itself.
-// A wavefront that streams its chunk appends the entries it keeps to its own
-// slice in index order and finally stores how many it kept. S is therefore
-// ordered by index without any cross-workgroup scan, ticket or fence, and a
-// slice can never overflow. Later kernels walk S chunk by chunk.
+// The vector is cut into W short contiguous chunks, and every chunk owns a
+// slice of the candidate buffer S as long as the chunk itself. The wavefront
+// that streams a chunk appends the entries it keeps to the chunk's slice in
+// index order and finally stores how many it kept. S is therefore ordered by
+// index without any cross-workgroup scan, ticket or fence, and a slice can
+// never overflow. Later kernels walk S chunk by chunk; each of their
+// wavefronts takes every U-th chunk, so that a region of the vector that is
+// dense in candidates is shared by all wavefronts.
 //
 // Pipeline:
-//   init       zero the control block and the two global histograms
-//   fused      a = g + m, stored into the residual buffer; histogram of the
-//              top 12 magnitude bits (12d bytes, the dominant kernel)
-//   scan       every workgroup picks the bucket b1 that holds the r-th largest
-//              magnitude; entries in bucket b1 or above -> S; 4096-bin
-//              histogram of the next 12 bits of the bucket-b1 entries (4d)
-//   classify   every workgroup picks the deciding level-2 bin. Entries of S
-//              above it are certain members of the top-r set: their Philox
-//              key is compared with an a-priori window [K_lo, K_hi] around
-//              the k-th smallest of r uniform keys - below: certain winner
-//              (counted per unit), inside: copied to the short list M.
-//              Entries inside the deciding bin are copied to the short list B
+//   sample     a = g + m at 16384 jittered, stratified locations (4 elements
+//              each); clears the control block and the global histogram
+//   estimate   one workgroup: from the sample's order statistics, a lower
+//              bound t_lo that the r-th largest magnitude exceeds and an upper
+//              bound t_hi that it stays below, both with ~6 sigma of margin;
+//              [t_lo, t_hi] becomes the finely binned part of the histogram
+//   fused      a = g + m, stored into the residual buffer (12d bytes, the
+//              dominant kernel); entries with magnitude >= t_lo -> S, and
+//              into a 4096-bin histogram: 2048 linear bins over the fine
+//              range, 2048 coarse bins (top 11 magnitude bits) above it
+//   classify   every workgroup picks the histogram bin that holds the r-th
+//              largest magnitude. Entries of S above that bin are certain
+//              members of the top-r set: their Philox key is compared with an
+//              a-priori window [K_lo, K_hi] around the k-th smallest of r
+//              uniform keys - below: certain winner (counted per chunk),
+//              inside: copied to the short list M. Entries inside the
+//              deciding bin are copied to the short list B
 //   finalize   one workgroup: exact r-th largest (magnitude, lower index
 //              first) inside B -> (T, I*); members of B join the key lists;
 //              exact (k - #certain)-th smallest (key, index) in M -> (K*, J*);
-//              prefix sum of the winners per unit. Whenever a short list
+//              prefix sum of the winners per chunk. Whenever a short list
 //              overflowed or the key window missed, the same quantities are
 //              found by radix selection over all of S instead (slow, exact)
 //   emit       entries of S that are members and winners -> the message in
-//              index order, starting at the unit's prefix; residual at the
+//              index order, starting at the chunk's prefix; residual at the
 //              sent positions <- a - a
+// If the sample misleads the estimate so far that S holds fewer than r
+// entries, the histogram shows it; classify then raises a flag and finalize
+// and emit walk the vector a itself instead of S (slow, exact).
 //
 // What the hardware punishes shaped this: a device-scope fence inside a
 // kernel costs tens of microseconds once a few hundred workgroups execute
 // one, and atomics on a single address retire at about one per 12 ns. So no
 // kernel here uses a fence, a ticket or a "last workgroup out" protocol;
 // workgroups never wait for each other; global atomics only go to histogram
-// bins; small decisions are recomputed by every workgroup that needs them.
+// bins and per-chunk counters; small decisions are recomputed by every
+// workgroup that needs them.
 #include "rtopk_common.h"
 #include "../../include/rtopk.h"
 
 #include <math.h>
+#include <mutex>
+#include <type_traits>
+#include <vector>
 
 namespace rtopk {
 
-constexpr int kShift1 = 19;                   // level 1: top 12 of the 31 magnitude bits
-constexpr int kBins1 = 1 << 12;
-constexpr int kBins2 = 1 << 12;               // level 2: next 12 bits of the picked bucket
-constexpr int kShift2 = kShift1 - 12;
+constexpr u32 kMaxFineBins = 2048;            // linear bins over [t_lo, fine_hi]: 64 .. 2048, by r
+constexpr u32 kCoarseShift = 23;              // coarse bins above them: the 8 exponent bits
+constexpr u32 kCoarseBins = 256;
+constexpr u32 kMaxBins = kMaxFineBins + kCoarseBins;
+constexpr u32 kMaxFusedBlocks = 1024;         // rows of per-workgroup histograms
+constexpr u32 kHistRows = 8;                  // rows left after the first reduction step
+
+constexpr u32 kSampleLoc = 16384;             // sampled locations, 4 consecutive elements each
+constexpr u32 kSampleThreads = 256;
+constexpr u32 kEstThreads = 1024;
+constexpr u32 kNoSample = 0xFFFFFFFFu;
 
 constexpr u32 kChunkQuantum = 256;            // one wavefront iteration: 64 lanes x 4 elements
-constexpr u32 kTargetChunks = 8192;
-constexpr u32 kMaxUnits = 4096;               // a unit = the chunks one wavefront of classify/emit walks
-constexpr u32 kWalkThreads = 256;             // classify / emit / scan workgroups: 4 wavefronts
+constexpr u32 kChunkAlign = 4 * kChunkQuantum; // chunks are whole groups of four iterations
+constexpr u32 kTargetChunks = 32768;          // short chunks, dealt round-robin to the wavefronts
+constexpr u32 kMaxUnits = 4096;               // wavefronts of classify / emit
+constexpr u32 kUnitChunks = kTargetChunks / kMaxUnits;   // chunks one of them walks, at most
+constexpr u32 kWalkThreads = 256;             // fused / classify / emit workgroups: 4 wavefronts
 constexpr u32 kWalkWaves = kWalkThreads / kWave;
 constexpr u32 kMaxWalkBlocks = kMaxUnits / kWalkWaves;
 constexpr u32 kListCap = 512;                 // short-list slots per classify workgroup
 constexpr int kFinThreads = 1024;
-constexpr u32 kStageB = 512, kStageM = 2560;  // short lists that fit are selected in LDS
+constexpr u32 kFinWaves = kFinThreads / kWave;
+constexpr u32 kSlabs = kTargetChunks / (4 * kFinThreads);  // 16-byte groups of chunk counters per thread
+constexpr u32 kStageB = 2048, kStageM = 2304; // short lists that fit are selected in LDS
 
 constexpr u32 kErrSelect = 2u;                // a selection found no element of the requested rank
 constexpr u32 kErrCount = 4u;                 // the winners did not add up to k
 
+// Histogram geometry chosen by the estimate kernel.
+struct Bins {
+    u32 t_lo;           // candidates are the entries with magnitude pattern >= t_lo
+    u32 fine_hi;        // last pattern of the linear bins
+    u32 shift;          // log2 of the patterns per linear bin
+    u32 nfine;          // number of linear bins
+};
+
+__device__ __forceinline__ u32 bin_of(const Bins &b, u32 m)
+{
+    return m <= b.fine_hi ? (m - b.t_lo) >> b.shift : b.nfine + (m >> kCoarseShift);
+}
+
+__device__ __forceinline__ void bin_range(const Bins &b, u32 bin, u32 *lo, u32 *hi)
+{
+    if (bin < b.nfine) {
+        *lo = b.t_lo + (bin << b.shift);
+        const u32 h = *lo + ((1u << b.shift) - 1u);
+        *hi = h < b.fine_hi ? h : b.fine_hi;
+    } else {
+        const u32 c = bin - b.nfine;
+        const u32 l = c << kCoarseShift;
+        *lo = l > b.fine_hi ? l : b.fine_hi + 1u;
+        *hi = l | ((1u << kCoarseShift) - 1u);
+    }
+}
+
 struct EncodeCtl {
     u32 err;
-    u32 path;           // 0: short lists; 1: some quantity came from selection over all of S
-    // written by workgroup 0 of k_scan
-    u32 h_lo;           // lowest magnitude pattern covered by the level-2 histogram
-    u32 h_shift;        // log2 of the patterns per level-2 bin
-    u64 c_above;        // entries above the level-2 range
+    u32 path;           // 0: short lists; 1: some quantity came from selection over all candidates
+    // written by k_estimate
+    Bins bins;
+    u32 n_samples;
     // written by workgroup 0 of k_classify
-    u32 bd_lo, bd_hi;   // pattern range of the deciding level-2 bin
+    u32 dense;          // S holds fewer than r entries: walk the vector itself
+    u32 bd_lo, bd_hi;   // pattern range of the deciding bin
+    u32 bd_bits;        // bit width of bd_hi - bd_lo
     u64 c_def;          // entries above bd_hi
     u32 overflow;       // a short-list region of some classify workgroup was full
     u32 pad0;
@@ -79,27 +133,29 @@ struct EncodeCtl {
     u32 T, I_star;      // last member of the top-r set in (magnitude desc, index asc) order
     u64 K_star;         // last winner in (key asc, index asc) order
     u32 J_star;
-    u32 n_b, n_m, pad1;
-    u64 superset, count_greater, ties;
+    u32 n_b, n_m;
+    u32 W;              // number of chunks, for the host-side statistics
+    u64 count_greater, ties;
 };
 
 // Geometry and sampling window: a pure function of (d, r, k), computed on the host.
 struct Geom {
     u64 d, r, k;
-    u32 C;              // elements per chunk (multiple of 256)
+    u32 C;              // elements per chunk (multiple of 1024)
     u32 W;              // chunks
-    u32 SU;             // chunks per unit
-    u32 U;              // units
+    u32 U;              // wavefronts of classify / emit; wavefront u walks chunks u, u + U, ...
     u32 G3;             // classify / emit workgroups
+    u32 L;              // sampled locations
+    u32 nfine;          // linear histogram bins
     u32 take_all;       // k == r: every member is sent, keys are never looked at
-    u64 K_lo, K_hi;     // key window
     u32 k_nlz;          // leading zeros of K_hi - K_lo
     u32 pad;
+    u64 K_lo, K_hi;     // key window
 };
 
 struct EncodeLayout {
-    u64 ctl, hist1, hist2, zero_bytes;
-    u64 seg_count, win_sure, unit_base, n_m, n_b;
+    u64 ctl, zero_bytes, partials, hist;
+    u64 samples, seg_count, win_cnt, chunk_base, blk_sure, n_m, n_b;
     u64 m_key, m_idx, b_mag, b_idx;
     u64 dm_key, dm_idx, db_key, db_idx;
     u64 s_idx, s_val;
@@ -111,12 +167,18 @@ static Geom make_geom(u64 d, u64 r, u64 k)
     Geom g{};
     g.d = d; g.r = r; g.k = k;
     u64 per = (d + kTargetChunks - 1) / kTargetChunks;
-    per = (per + kChunkQuantum - 1) / kChunkQuantum * kChunkQuantum;
+    per = (per + kChunkAlign - 1) / kChunkAlign * kChunkAlign;
     g.C = (u32)per;
     g.W = (u32)((d + per - 1) / per);
-    g.SU = (g.W + kMaxUnits - 1) / kMaxUnits;
-    g.U = (g.W + g.SU - 1) / g.SU;
+    g.U = g.W < kMaxUnits ? g.W : kMaxUnits;
     g.G3 = (g.U + kWalkWaves - 1) / kWalkWaves;
+    const u64 loc = (d + 3) / 4;
+    g.L = (u32)(loc < kSampleLoc ? loc : kSampleLoc);
+    // Every workgroup of the streaming kernel stores its whole histogram: few
+    // bins when r is small (the list B of the deciding bin then holds a few
+    // hundred entries anyway), more when r is large.
+    g.nfine = 256;
+    while (g.nfine < kMaxFineBins && (u64)g.nfine * 256 < r) g.nfine *= 2;
     g.take_all = (k == r) ? 1u : 0u;
     // The number of members with key below x * 2^64 is Binomial(r, x). The
     // window keeps 7 standard deviations plus a constant (for small k, where
@@ -140,12 +202,14 @@ static EncodeLayout make_layout(const Geom &g)
     u64 o = 0;
     auto take = [&](u64 bytes) { u64 at = o; o = align_up(o + bytes, 256); return at; };
     L.ctl = take(sizeof(EncodeCtl));
-    L.hist1 = take(kBins1 * 4);
-    L.hist2 = take(kBins2 * 4);
     L.zero_bytes = o;
-    L.seg_count = take((u64)g.W * 4);
-    L.win_sure = take((u64)g.U * 4);
-    L.unit_base = take((u64)g.U * 4);
+    L.partials = take((u64)kMaxFusedBlocks * kMaxBins * 4);
+    L.hist = take((u64)kHistRows * kMaxBins * 4);
+    L.samples = take((u64)kSampleLoc * 16);
+    L.seg_count = take((u64)kTargetChunks * 4);      // fixed size: its offset depends on nothing
+    L.win_cnt = take((u64)kTargetChunks * 4);
+    L.chunk_base = take((u64)kTargetChunks * 4);
+    L.blk_sure = take((u64)g.G3 * 4);
     L.n_m = take((u64)g.G3 * 4);
     L.n_b = take((u64)g.G3 * 4);
     const u64 slots = (u64)g.G3 * kListCap;
@@ -168,26 +232,37 @@ __device__ __forceinline__ u32 mag_of(u32 bits) { return bits & 0x7FFFFFFFu; }
 __device__ __forceinline__ u32 popc64(u64 m) { return (u32)__popcll((unsigned long long)m); }
 
 // ---------------------------------------------------------------------------
-// workgroup-wide sums of one u64 per thread (thread order)
+// workgroup-wide sums of one value per thread (thread order); the second
+// level is a wavefront scan, not a serial loop: LDS round trips are slow
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ u64 block_exclusive_sum(u64 v, u64 *lds /* >= waves + 1 words */)
+template <class T>
+__device__ __forceinline__ T wave_inclusive(T v)
 {
-    const u32 lane = lane_id(), wave = threadIdx.x / kWave, nw = blockDim.x / kWave;
-    u64 inc = v;
+    const u32 lane = lane_id();
 #pragma unroll
     for (int off = 1; off < kWave; off <<= 1) {
-        const u64 t = __shfl_up(inc, off, kWave);
-        if (lane >= (u32)off) inc += t;
+        const T t = __shfl_up(v, off, kWave);
+        if (lane >= (u32)off) v += t;
     }
+    return v;
+}
+
+// exclusive prefix of v over the workgroup; the grand total is left in lds[waves]
+template <class T>
+__device__ __forceinline__ T block_exclusive_sum(T v, T *lds /* >= waves + 1 words */)
+{
+    const u32 lane = lane_id(), wave = threadIdx.x / kWave, nw = blockDim.x / kWave;
+    const T inc = wave_inclusive(v);
     if (lane == kWave - 1) lds[wave] = inc;
     __syncthreads();
-    if (threadIdx.x == 0) {
-        u64 run = 0;
-        for (u32 w = 0; w < nw; ++w) { const u64 t = lds[w]; lds[w] = run; run += t; }
-        lds[nw] = run;
+    if (wave == 0) {
+        const T x = lane < nw ? lds[lane] : (T)0;
+        const T xi = wave_inclusive(x);
+        if (lane < nw) lds[lane] = xi - x;
+        if (lane == nw - 1) lds[nw] = xi;
     }
     __syncthreads();
-    const u64 res = lds[wave] + inc - v;
+    const T res = lds[wave] + inc - v;
     __syncthreads();
     return res;
 }
@@ -198,156 +273,161 @@ __device__ __forceinline__ u64 block_sum(u64 v, u64 *lds /* >= waves + 1 words *
     v = wave_sum_u64(v);
     if (lane_id() == 0) lds[threadIdx.x / kWave] = v;
     __syncthreads();
-    u64 total = 0;
-    for (u32 w = 0; w < nw; ++w) total += lds[w];
+    const u64 x = lane_id() < nw ? lds[lane_id()] : 0ull;
+    const u64 total = wave_sum_u64(x);
     __syncthreads();
     return total;
 }
 
-// Whole workgroup: walking the bins from the top, find the bin b with
-// #(bins above b) < need <= #(bins >= b). Stores b and the population above
-// it; the caller synchronises before reading them.
-__device__ __forceinline__ void block_pick_desc(const u32 *hist, int nbins, u64 need,
-                                                u32 *out_bin, u64 *out_before, u64 *lds)
+// Whole workgroup: walking NBINS = PER * blockDim.x bins (in LDS) from the
+// top, find the bin b with #(bins above b) < need <= #(bins >= b). Stores b
+// and the population above it; stores nothing when all bins together hold
+// fewer than `need`. The caller presets the outputs and synchronises before
+// reading them.
+template <int PER>
+__device__ __forceinline__ void block_pick_desc(const u32 *hist, u32 need, u32 *out_bin,
+                                                u32 *out_before, u32 *lds)
 {
-    const int per = (nbins + (int)blockDim.x - 1) / (int)blockDim.x;
-    const int first = (int)threadIdx.x * per;      // position in walking order
-    u64 mine = 0;
-    for (int q = 0; q < per; ++q) {
-        const int pos = first + q;
-        if (pos < nbins) mine += hist[nbins - 1 - pos];
-    }
-    const u64 before = block_exclusive_sum(mine, lds);
+    const int nbins = PER * (int)blockDim.x;
+    const int first = (int)threadIdx.x * PER;      // position in walking order
+    u32 c[PER];
+    u32 mine = 0;
+#pragma unroll
+    for (int q = 0; q < PER; ++q) { c[q] = hist[nbins - 1 - (first + q)]; mine += c[q]; }
+    const u32 before = block_exclusive_sum(mine, lds);
     if (before < need && need <= before + mine) {
-        u64 run = before;
-        for (int q = 0; q < per; ++q) {
-            const int pos = first + q;
-            if (pos >= nbins) break;
-            const int bin = nbins - 1 - pos;
-            const u64 h = hist[bin];
-            if (run + h >= need) { *out_bin = (u32)bin; *out_before = run; break; }
-            run += h;
+        u32 run = before;
+        bool done = false;
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            if (!done && run + c[q] >= need) {
+                *out_bin = (u32)(nbins - 1 - (first + q));
+                *out_before = run;
+                done = true;
+            }
+            run += c[q];
         }
     }
 }
 
 // ---------------------------------------------------------------------------
-// init: clear what the later kernels accumulate into
+// sample: magnitudes of a = g + m at g.L locations, one per stratum of the
+// vector, at a hashed offset inside the stratum, four consecutive elements
+// each. Also clears what later kernels accumulate into.
 // ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) k_init(u32 *zero_base, u32 words)
+__device__ __forceinline__ u64 stratum_start(const Geom &g, u32 j)
 {
-    for (u32 i = blockIdx.x * blockDim.x + threadIdx.x; i < words; i += gridDim.x * blockDim.x)
-        zero_base[i] = 0u;
+    // strata of (almost) equal length; only monotonicity and the two ends matter
+    if (j >= g.L) return g.d;
+    const u64 x = (u64)((double)g.d * (double)j / (double)g.L);
+    return x < g.d ? x : g.d;
+}
+
+__global__ void __launch_bounds__(kSampleThreads)
+k_sample(const float *__restrict__ grad, const float *__restrict__ residual, Geom g,
+         u32 *__restrict__ zero_base, u32 zero_words, u32 *__restrict__ samples)
+{
+    const u32 j = blockIdx.x * kSampleThreads + threadIdx.x;
+    for (u32 i = j; i < zero_words; i += gridDim.x * kSampleThreads) zero_base[i] = 0u;
+    if (j >= kSampleLoc) return;
+    u32 out[4] = {kNoSample, kNoSample, kNoSample, kNoSample};
+    if (j < g.L) {
+        const u64 start = stratum_start(g, j), end = stratum_start(g, j + 1);
+        const u64 len = end - start;
+        u64 p = start;
+        if (len > 4) {
+            u32 hsh = (j + 1u) * 0x9E3779B1u;
+            hsh ^= hsh >> 15; hsh *= 0x85EBCA77u; hsh ^= hsh >> 13;
+            // offset in [0, len - 4], scaled from the hash instead of a remainder
+            p += (u64)(((u64)hsh * (u64)(len - 3)) >> 32);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const u64 i = p + e;
+            if (i < end) out[e] = mag_of(__float_as_uint(grad[i] + residual[i]));
+        }
+    }
+    reinterpret_cast<uint4 *>(samples)[j] = make_uint4(out[0], out[1], out[2], out[3]);
 }
 
 // ---------------------------------------------------------------------------
-// fused residual add + level-1 histogram (12d bytes of HBM traffic)
+// estimate: order statistics of the sample -> histogram geometry.
+// With n samples and p = r/d, the number of samples among the true top r is
+// about Binomial(n, p); clusters of four that rise and fall together double
+// the standard deviation at worst. t_lo is the lower edge of the 12-bit
+// pattern bucket that holds the sample of rank np + 6 sd + 8 (so that at
+// least r entries lie at or above t_lo), t_hi the upper edge of the bucket
+// that holds the sample of rank np - 6 sd - 8 (fewer than r entries lie
+// above it).
 // ---------------------------------------------------------------------------
-constexpr int kFusedThreads = 1024;
+__global__ void __launch_bounds__(kEstThreads)
+k_estimate(const u32 *__restrict__ samples, Geom g, EncodeCtl *ctl)
+{
+    __shared__ u32 h[4096];
+    __shared__ u32 scan_lds[kEstThreads / kWave + 1];
+    __shared__ u64 sum_lds[kEstThreads / kWave + 1];
+    __shared__ u32 bin_s[2], before_s[2];
+    const u32 tid = threadIdx.x;
+    constexpr u32 kVecs = kSampleLoc / kEstThreads;       // 16-byte sample groups per thread
+    const uint4 *s4 = reinterpret_cast<const uint4 *>(samples);
+    uint4 v[kVecs];
+#pragma unroll
+    for (u32 q = 0; q < kVecs; ++q) v[q] = s4[q * kEstThreads + tid];
+    for (u32 b = tid; b < 4096u; b += kEstThreads) h[b] = 0u;
+    if (tid < 2u) { bin_s[tid] = 0u; before_s[tid] = 0u; }
+    __syncthreads();
+    u32 nvalid = 0, nzero = 0;
+    auto count1 = [&](u32 m) {
+        if (m == kNoSample) return;
+        ++nvalid;
+        if (m == 0u) ++nzero;                     // exact zeros come in long runs: count them aside
+        else atomicAdd(&h[m >> 19], 1u);
+    };
+#pragma unroll
+    for (u32 q = 0; q < kVecs; ++q) { count1(v[q].x); count1(v[q].y); count1(v[q].z); count1(v[q].w); }
+    nzero = (u32)wave_sum_u64(nzero);
+    if (lane_id() == 0 && nzero) atomicAdd(&h[0], nzero);
+    const u32 n = (u32)block_sum(nvalid, sum_lds);
+
+    const float p = (float)((double)g.r / (double)g.d);
+    const float np = (float)n * p;
+    const float sd = 2.0f * sqrtf(np * (1.0f - p));
+    const float lo_rank = ceilf(np + 6.0f * sd + 8.0f), hi_rank = floorf(np - 6.0f * sd - 8.0f);
+    const bool lo_all = lo_rank > (float)n;       // too few samples below the top: keep everything
+    const u32 s_lo = lo_all ? n : (u32)lo_rank;
+    const u32 s_hi = hi_rank < 1.0f ? 1u : (u32)hi_rank;
+    __syncthreads();
+    block_pick_desc<4>(h, s_lo, &bin_s[0], &before_s[0], scan_lds);
+    block_pick_desc<4>(h, s_hi, &bin_s[1], &before_s[1], scan_lds);
+    __syncthreads();
+    if (tid == 0) {
+        const u32 t_lo = lo_all ? 0u : (bin_s[0] << 19);
+        u32 t_hi = (bin_s[1] << 19) | 0x7FFFFu;
+        if (t_hi < t_lo) t_hi = t_lo;
+        u32 shift = 0;
+        while (((t_hi - t_lo) >> shift) >= g.nfine) ++shift;
+        const u64 top = (u64)t_lo + ((u64)g.nfine << shift) - 1ull;
+        ctl->bins.t_lo = t_lo;
+        ctl->bins.fine_hi = top > 0x7FFFFFFFull ? 0x7FFFFFFFu : (u32)top;
+        ctl->bins.shift = shift;
+        ctl->bins.nfine = g.nfine;
+        ctl->n_samples = n;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// One wavefront iteration of the streaming kernel covers 256 consecutive
+// elements starting at `base`. Layout of the four elements a lane holds:
+// kVec4 -> base + 4*lane + e (16-byte accesses); otherwise base + 64*e + lane
+// (coalesced 4-byte accesses, any alignment). Kept entries are appended to
+// the chunk's slice of S in index order.
+// ---------------------------------------------------------------------------
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-template <bool kVec4>
-__global__ void __launch_bounds__(kFusedThreads)
-k_fused_add_hist(const float *__restrict__ grad, float *__restrict__ residual, u64 d, u32 *hist1)
-{
-    __shared__ u32 h[kBins1];
-    for (int b = threadIdx.x; b < kBins1; b += kFusedThreads) h[b] = 0u;
-    __syncthreads();
-
-    if (kVec4) {
-        const u64 nvec = d / 4;
-        const f32x4 *g4 = reinterpret_cast<const f32x4 *>(grad);
-        f32x4 *m4 = reinterpret_cast<f32x4 *>(residual);
-        const u64 stride = (u64)gridDim.x * kFusedThreads;
-        u64 v = (u64)blockIdx.x * kFusedThreads + threadIdx.x;
-        auto body = [&](const f32x4 &g, const f32x4 &m, u64 at) {
-            const f32x4 a = g + m;
-            m4[at] = a;
-            const u32 d0 = mag_of(__float_as_uint(a.x)) >> kShift1,
-                      d1 = mag_of(__float_as_uint(a.y)) >> kShift1,
-                      d2 = mag_of(__float_as_uint(a.z)) >> kShift1,
-                      d3 = mag_of(__float_as_uint(a.w)) >> kShift1;
-            // runs of equal digits (zero rows, constant blocks): one add per wave
-            const u32 lead = __builtin_amdgcn_readfirstlane(d0);
-            const bool same = (d0 == lead) & (d1 == lead) & (d2 == lead) & (d3 == lead);
-            const u64 active = __ballot(true);
-            if (__ballot(same) == active) {
-                if (lane_id() == (u32)(__ffsll((unsigned long long)active) - 1))
-                    atomicAdd(&h[lead], 4u * popc64(active));
-            } else {
-                atomicAdd(&h[d0], 1u); atomicAdd(&h[d1], 1u);
-                atomicAdd(&h[d2], 1u); atomicAdd(&h[d3], 1u);
-            }
-        };
-        for (; v + 3 * stride < nvec; v += 4 * stride) {
-            f32x4 g[4], m[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                g[u] = __builtin_nontemporal_load(&g4[v + u * stride]);
-                m[u] = m4[v + u * stride];
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) body(g[u], m[u], v + u * stride);
-        }
-        for (; v < nvec; v += stride) {
-            const f32x4 g = __builtin_nontemporal_load(&g4[v]);
-            const f32x4 m = m4[v];
-            body(g, m, v);
-        }
-        if (blockIdx.x == 0 && threadIdx.x < (d & 3)) {
-            const u64 i = nvec * 4 + threadIdx.x;
-            const float a = grad[i] + residual[i];
-            residual[i] = a;
-            atomicAdd(&h[mag_of(__float_as_uint(a)) >> kShift1], 1u);
-        }
-    } else {
-        const u64 stride = (u64)gridDim.x * kFusedThreads;
-        for (u64 i = (u64)blockIdx.x * kFusedThreads + threadIdx.x; i < d; i += stride) {
-            const float a = grad[i] + residual[i];
-            residual[i] = a;
-            atomicAdd(&h[mag_of(__float_as_uint(a)) >> kShift1], 1u);
-        }
-    }
-    __syncthreads();
-    for (int b = threadIdx.x; b < kBins1; b += kFusedThreads) {
-        const u32 c = h[b];
-        if (c) atomicAdd(&hist1[b], c);
-    }
-}
-
-// ---------------------------------------------------------------------------
-// One wavefront iteration of a chunk scan: 256 consecutive elements starting
-// at `base`, of which those below `end` exist. Layout of the four elements a
-// lane holds: kVec4 -> base + 4*lane + e (one 16-byte load); otherwise
-// base + 64*e + lane (four coalesced 4-byte loads, any alignment).
-// Kept entries are appended to the wavefront's slice in index order.
-// ---------------------------------------------------------------------------
 template <bool kVec4>
 __device__ __forceinline__ u64 elem_index(u64 base, int e)
 {
     return kVec4 ? base + 4ull * lane_id() + (u64)e : base + 64ull * (u64)e + lane_id();
-}
-
-template <bool kVec4>
-__device__ __forceinline__ void load_row(const float *__restrict__ a, u64 base, u64 end,
-                                         u32 (&bits)[4], bool (&valid)[4])
-{
-    if (kVec4) {
-        const u64 i0 = base + 4ull * lane_id();
-        if (i0 + 3 < end) {
-            const float4 v = *reinterpret_cast<const float4 *>(a + i0);
-            bits[0] = __float_as_uint(v.x); bits[1] = __float_as_uint(v.y);
-            bits[2] = __float_as_uint(v.z); bits[3] = __float_as_uint(v.w);
-            valid[0] = valid[1] = valid[2] = valid[3] = true;
-            return;
-        }
-    }
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const u64 i = elem_index<kVec4>(base, e);
-        valid[e] = i < end;
-        bits[e] = valid[e] ? __float_as_uint(a[i]) : 0u;
-    }
 }
 
 template <bool kVec4>
@@ -382,130 +462,328 @@ __device__ __forceinline__ void append_hits(const u32 (&bits)[4], const bool (&h
 }
 
 // ---------------------------------------------------------------------------
-// scan: entries whose level-1 digit is at or above the picked bucket -> S;
-// level-2 histogram of the entries inside the bucket. Reads a once (4d).
+// fused: a = g + m -> residual buffer; candidates -> S and the histogram.
+// Reads g and m once, writes a once: 12d bytes of HBM traffic. The grid is
+// sized to what the device holds at once; wavefront v takes chunks v,
+// v + #wavefronts, ... so that neighbouring wavefronts stream neighbouring
+// 4 KB pieces of each array.
 // ---------------------------------------------------------------------------
-template <bool kVec4>
-__global__ void __launch_bounds__(kWalkThreads)
-k_scan(const float *__restrict__ a, Geom g, EncodeCtl *ctl, const u32 *__restrict__ hist1,
-       u32 *hist2, u32 *__restrict__ seg_count, u32 *__restrict__ s_idx,
-       u32 *__restrict__ s_val)
-{
-    __shared__ u32 h2[kBins2];
-    __shared__ u64 scan_lds[kWalkWaves + 1];
-    __shared__ u32 bin_s;
-    __shared__ u64 before_s;
-    for (int b = threadIdx.x; b < kBins2; b += kWalkThreads) h2[b] = 0u;
-    block_pick_desc(hist1, kBins1, g.r, &bin_s, &before_s, scan_lds);
-    __syncthreads();
-    const u32 t_lo = bin_s << kShift1;
-    const u32 h_hi = t_lo | ((1u << kShift1) - 1u);
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        ctl->h_lo = t_lo;
-        ctl->h_shift = kShift2;
-        ctl->c_above = before_s;
-    }
+constexpr u32 kFusedThreads = 512;
+constexpr u32 kFusedWaves = kFusedThreads / kWave;
 
-    const u32 w = blockIdx.x * kWalkWaves + threadIdx.x / kWave;
-    if (w < g.W) {
+template <bool kVec4>
+__global__ void __launch_bounds__(kFusedThreads)
+k_fused(const float *__restrict__ grad, float *__restrict__ residual, Geom g,
+        const EncodeCtl *__restrict__ ctl, u32 *__restrict__ partials,
+        u32 *__restrict__ seg_count, u32 *__restrict__ s_idx, u32 *__restrict__ s_val)
+{
+    __shared__ u32 h[kMaxBins];
+    const Bins bins = ctl->bins;
+    const u32 nbins = bins.nfine + kCoarseBins;
+    for (u32 b = threadIdx.x; b < nbins; b += kFusedThreads) h[b] = 0u;
+    __syncthreads();
+
+    const u32 wave_stride = gridDim.x * kFusedWaves;
+    for (u32 w = blockIdx.x * kFusedWaves + threadIdx.x / kWave; w < g.W; w += wave_stride) {
         const u64 c0 = (u64)w * g.C;
         const u64 c1 = c0 + g.C < g.d ? c0 + g.C : g.d;
         u32 *my_idx = s_idx + c0, *my_val = s_val + c0;
         u32 run = 0;
-        auto process = [&](const u32 (&bits)[4], const bool (&valid)[4], u64 base) {
+        auto keep = [&](const u32 (&bits)[4], const bool (&valid)[4], u64 base) {
             bool hit[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const u32 m = mag_of(bits[e]);
-                hit[e] = valid[e] && m >= t_lo;
-                if (hit[e] && m <= h_hi) atomicAdd(&h2[(m - t_lo) >> kShift2], 1u);
+                hit[e] = valid[e] && m >= bins.t_lo;
+                if (hit[e]) atomicAdd(&h[bin_of(bins, m)], 1u);
             }
             append_hits<kVec4>(bits, hit, base, run, my_idx, my_val);
         };
+        const bool all_valid[4] = {true, true, true, true};
+        // NR full iterations at a time, all loads issued before the first use
+        auto full_rows = [&](auto nr_c, u64 base) {
+            constexpr int NR = decltype(nr_c)::value;
+            u32 bits[NR][4];
+            if (kVec4) {
+                const f32x4 *g4 = reinterpret_cast<const f32x4 *>(grad + base) + lane_id();
+                f32x4 *m4 = reinterpret_cast<f32x4 *>(residual + base) + lane_id();
+                f32x4 gv[NR], mv[NR];
+#pragma unroll
+                for (int u = 0; u < NR; ++u) {
+                    gv[u] = __builtin_nontemporal_load(g4 + u * kWave);
+                    mv[u] = m4[u * kWave];
+                }
+#pragma unroll
+                for (int u = 0; u < NR; ++u) {
+                    const f32x4 a = gv[u] + mv[u];
+                    m4[u * kWave] = a;
+                    bits[u][0] = __float_as_uint(a.x); bits[u][1] = __float_as_uint(a.y);
+                    bits[u][2] = __float_as_uint(a.z); bits[u][3] = __float_as_uint(a.w);
+                }
+            } else {
+                const float *gp = grad + base + lane_id();
+                float *mp = residual + base + lane_id();
+                float gv[4 * NR], mv[4 * NR];
+#pragma unroll
+                for (int q = 0; q < 4 * NR; ++q) {
+                    gv[q] = __builtin_nontemporal_load(gp + q * kWave);
+                    mv[q] = mp[q * kWave];
+                }
+#pragma unroll
+                for (int q = 0; q < 4 * NR; ++q) {
+                    const float a = gv[q] + mv[q];
+                    mp[q * kWave] = a;
+                    bits[q / 4][q % 4] = __float_as_uint(a);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < NR; ++u) keep(bits[u], all_valid, base + u * kChunkQuantum);
+        };
         u64 base = c0;
-        for (; base + 4 * kChunkQuantum <= c1; base += 4 * kChunkQuantum) {
-            u32 bits[4][4];
-            bool valid[4][4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-                load_row<kVec4>(a, base + u * kChunkQuantum, c1, bits[u], valid[u]);
-#pragma unroll
-            for (int u = 0; u < 4; ++u) process(bits[u], valid[u], base + u * kChunkQuantum);
-        }
-        for (; base < c1; base += kChunkQuantum) {
+        for (; base + 4 * kChunkQuantum <= c1; base += 4 * kChunkQuantum)
+            full_rows(std::integral_constant<int, 4>{}, base);
+        for (; base + kChunkQuantum <= c1; base += kChunkQuantum)
+            full_rows(std::integral_constant<int, 1>{}, base);
+        if (base < c1) {
             u32 bits[4];
             bool valid[4];
-            load_row<kVec4>(a, base, c1, bits, valid);
-            process(bits, valid, base);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const u64 i = elem_index<kVec4>(base, e);
+                valid[e] = i < c1;
+                bits[e] = 0u;
+                if (valid[e]) {
+                    const float a = grad[i] + residual[i];
+                    residual[i] = a;
+                    bits[e] = __float_as_uint(a);
+                }
+            }
+            keep(bits, valid, base);
         }
         if (lane_id() == 0) seg_count[w] = run;
     }
     __syncthreads();
-    for (int b = threadIdx.x; b < kBins2; b += kWalkThreads) {
-        const u32 c = h2[b];
-        if (c) atomicAdd(&hist2[b], c);
+    // The workgroup's histogram goes out as one dense row with plain stores:
+    // device-wide atomics here, however few, slow the whole stream down.
+    u32 *row = partials + (u64)blockIdx.x * nbins;
+    for (u32 b = threadIdx.x; b < nbins; b += kFusedThreads) row[b] = h[b];
+}
+
+// ---------------------------------------------------------------------------
+// The candidates as later kernels see them: chunk s holds count(s) entries
+// (index, binary32 pattern), in index order. Normally that is the slice of S
+// the fused kernel filled; in dense mode it is the chunk of a itself.
+// ---------------------------------------------------------------------------
+struct Candidates {
+    const u32 *__restrict__ seg_count;
+    const u32 *__restrict__ s_idx;
+    const u32 *__restrict__ s_val;
+    const float *__restrict__ a;
+    u64 d;
+    u32 C;
+    bool dense;
+
+    __device__ __forceinline__ u32 count(u32 s) const
+    {
+        if (!dense) return seg_count[s];
+        const u64 c0 = (u64)s * C;
+        return (u32)(c0 + C < d ? C : d - c0);
+    }
+    __device__ __forceinline__ void entry(u32 s, u32 j, u32 *idx, u32 *bits) const
+    {
+        const u64 at = (u64)s * C + j;
+        if (!dense) { *idx = s_idx[at]; *bits = s_val[at]; }
+        else { *idx = (u32)at; *bits = __float_as_uint(a[at]); }
+    }
+};
+
+// One wavefront walks chunks u, u + U, u + 2U, ... as one flat sequence: lane
+// i first fetches the size of the i-th of them (there are at most
+// kUnitChunks), a prefix sum turns flat positions into (chunk, entry) pairs,
+// and every iteration of the walk hands 64 consecutive positions to the 64
+// lanes; the entries of one chunk stay in index order. f(valid, i, chunk,
+// entry, first, p0) is called by all lanes in every iteration, so it may use
+// wave-wide operations; i is the ordinal of the chunk among the wavefront's
+// chunks, first the flat position of the chunk's first entry and p0 the flat
+// position lane 0 holds.
+struct UnitWalk {
+    u32 u, stride, excl, inc, total;
+
+    __device__ __forceinline__ UnitWalk(const Candidates &cand, const Geom &g, u32 unit)
+    {
+        static_assert(kUnitChunks <= kWave, "one lane per chunk");
+        const u32 lane = lane_id();
+        u = unit;
+        stride = g.U;
+        const u32 s = unit + lane * g.U;
+        const u32 cnt = (unit < g.U && lane < kUnitChunks && s < g.W) ? cand.count(s) : 0u;
+        inc = wave_inclusive(cnt);
+        excl = inc - cnt;
+        total = __shfl(inc, kWave - 1, kWave);
+    }
+
+    template <class F>
+    __device__ __forceinline__ void for_each(F &&f) const
+    {
+        const u32 lane = lane_id();
+        for (u32 p0 = 0; p0 < total; p0 += kWave) {
+            const u32 p = p0 + lane;
+            // number of chunks that end at or before position p = ordinal of p's chunk
+            u32 c = 0;
+#pragma unroll
+            for (u32 step = kUnitChunks / 2; step > 0; step >>= 1) {
+                const u32 end_of = __shfl(inc, c + step - 1, kWave);
+                if (end_of <= p) c += step;
+            }
+            c &= kUnitChunks - 1;
+            const u32 first = __shfl(excl, c, kWave);
+            f(p < total, c, u + c * stride, p - first, first, p0);
+        }
+    }
+};
+
+// ---------------------------------------------------------------------------
+// reduce: the rows the streaming workgroups stored -> kHistRows rows.
+// Workgroup (x, y): bins 256x .. 256x+255 of rows y, y + kHistRows, ...
+// ---------------------------------------------------------------------------
+constexpr u32 kReduceThreads = 256;
+
+__global__ void __launch_bounds__(kReduceThreads)
+k_reduce(const u32 *__restrict__ partials, u32 n_rows, const EncodeCtl *__restrict__ ctl,
+         u32 *__restrict__ hist)
+{
+    const u32 nbins = ctl->bins.nfine + kCoarseBins;
+    const u32 bin = blockIdx.x * kReduceThreads + threadIdx.x;
+    if (bin >= nbins) return;
+    u32 sum = 0;
+#pragma unroll 8
+    for (u32 row = blockIdx.y; row < n_rows; row += kHistRows) sum += partials[(u64)row * nbins + bin];
+    hist[blockIdx.y * nbins + bin] = sum;
+}
+
+// ---------------------------------------------------------------------------
+// pick: one workgroup adds the remaining rows up, walks the histogram from
+// the top and finds the bin that holds the r-th largest magnitude.
+// ---------------------------------------------------------------------------
+constexpr u32 kPickThreads = 1024;
+constexpr u32 kPickPer = (kMaxBins + kPickThreads - 1) / kPickThreads;
+
+__global__ void __launch_bounds__(kPickThreads)
+k_pick(const u32 *__restrict__ hist, Geom g, EncodeCtl *ctl)
+{
+    __shared__ u32 scan_lds[kPickThreads / kWave + 1];
+    __shared__ u32 bin_s;
+    __shared__ u32 before_s;
+    const Bins bins = ctl->bins;
+    const u32 nbins = bins.nfine + kCoarseBins;
+    // thread t owns the bins at walking positions kPickPer*t .. (bin nbins-1 comes first)
+    const u32 first = threadIdx.x * kPickPer;
+    u32 c[kPickPer];
+    u32 mine = 0;
+#pragma unroll
+    for (u32 q = 0; q < kPickPer; ++q) {
+        const u32 pos = first + q;
+        c[q] = 0u;
+        if (pos < nbins) {
+#pragma unroll
+            for (u32 row = 0; row < kHistRows; ++row) c[q] += hist[row * nbins + (nbins - 1u - pos)];
+        }
+        mine += c[q];
+    }
+    if (threadIdx.x == 0) { bin_s = kMaxBins; before_s = 0u; }
+    const u32 before = block_exclusive_sum(mine, scan_lds);   // candidates number less than 2^32
+    const u64 need = g.r;
+    if ((u64)before < need && need <= (u64)before + mine) {
+        u32 run = before;
+        bool done = false;
+#pragma unroll
+        for (u32 q = 0; q < kPickPer; ++q) {
+            if (!done && (u64)run + c[q] >= need) {
+                bin_s = nbins - 1u - (first + q);
+                before_s = run;
+                done = true;
+            }
+            run += c[q];
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const bool dense = bin_s == kMaxBins;     // the histogram holds fewer than r entries
+        u32 bd_lo = 0, bd_hi = 0;
+        if (!dense) bin_range(bins, bin_s, &bd_lo, &bd_hi);
+        ctl->dense = dense ? 1u : 0u;
+        ctl->bd_lo = bd_lo;
+        ctl->bd_hi = bd_hi;
+        ctl->bd_bits = bd_hi > bd_lo ? 32u - (u32)__clz(bd_hi - bd_lo) : 1u;
+        ctl->c_def = before_s;
     }
 }
 
 // ---------------------------------------------------------------------------
 // classify: walk S; certain members are keyed against the window, entries
-// of the deciding level-2 bin go to the short list B.
+// of the deciding bin go to the short list B.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(kWalkThreads)
-k_classify(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ hist2,
-           const u32 *__restrict__ seg_count, const u32 *__restrict__ s_idx,
-           const u32 *__restrict__ s_val, u32 *__restrict__ win_sure, u32 *__restrict__ n_m,
+k_classify(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ seg_count,
+           const u32 *__restrict__ s_idx, const u32 *__restrict__ s_val,
+           u32 *__restrict__ win_cnt, u32 *__restrict__ blk_sure, u32 *__restrict__ n_m,
            u32 *__restrict__ n_b, u64 *__restrict__ m_key, u32 *__restrict__ m_idx,
            u32 *__restrict__ b_mag, u32 *__restrict__ b_idx)
 {
-    __shared__ u64 scan_lds[kWalkWaves + 1];
-    __shared__ u32 bin_s, cnt_m, cnt_b;
-    __shared__ u64 before_s;
-    if (threadIdx.x == 0) { cnt_m = 0u; cnt_b = 0u; }
-    const u64 c_above = ctl->c_above;
-    const u32 h_lo = ctl->h_lo, h_shift = ctl->h_shift;
-    block_pick_desc(hist2, kBins2, g.r - c_above, &bin_s, &before_s, scan_lds);
-    __syncthreads();
-    const u32 bd_lo = h_lo + (bin_s << h_shift);
-    const u32 bd_hi = bd_lo + ((1u << h_shift) - 1u);
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        ctl->bd_lo = bd_lo;
-        ctl->bd_hi = bd_hi;
-        ctl->c_def = c_above + before_s;
+    __shared__ u32 cnt_m, cnt_b, cnt_sure;
+    __shared__ u32 per_chunk[kWalkWaves][kUnitChunks];
+    const u32 wave = threadIdx.x / kWave, lane = lane_id();
+    const u32 u = blockIdx.x * kWalkWaves + wave;
+    const bool dense = ctl->dense != 0u;
+    const u32 bd_lo = ctl->bd_lo, bd_hi = ctl->bd_hi;
+    if (dense) {
+        if (threadIdx.x == 0) { blk_sure[blockIdx.x] = 0u; n_m[blockIdx.x] = 0u; n_b[blockIdx.x] = 0u; }
+        return;
     }
+    const Candidates cand{seg_count, s_idx, s_val, nullptr, g.d, g.C, false};
+    const UnitWalk walk(cand, g, u);
+    if (threadIdx.x == 0) { cnt_m = 0u; cnt_b = 0u; cnt_sure = 0u; }
+    if (lane < kUnitChunks) per_chunk[wave][lane] = 0u;
+    __syncthreads();
 
-    const u32 u = blockIdx.x * kWalkWaves + threadIdx.x / kWave;
-    const u32 lane = lane_id();
     const u64 slot0 = (u64)blockIdx.x * kListCap;
-    if (u < g.U) {
-        u32 sure = 0;
-        const u32 s_end = (u + 1) * g.SU < g.W ? (u + 1) * g.SU : g.W;
-        for (u32 s = u * g.SU; s < s_end; ++s) {
-            const u32 n = seg_count[s];
-            const u64 at = (u64)s * g.C;
-            for (u32 j = lane; j < n; j += kWave) {
-                const u32 idx = s_idx[at + j];
-                const u32 m = mag_of(s_val[at + j]);
-                if (m > bd_hi) {
-                    if (g.take_all) { ++sure; continue; }
-                    const u64 key = sample_key(idx, seed);
-                    if (key < g.K_lo) {
-                        ++sure;
-                    } else if (key <= g.K_hi) {
-                        const u32 p = atomicAdd(&cnt_m, 1u);
-                        if (p < kListCap) { m_key[slot0 + p] = key; m_idx[slot0 + p] = idx; }
-                    }
-                } else if (m >= bd_lo) {
-                    const u32 p = atomicAdd(&cnt_b, 1u);
-                    if (p < kListCap) { b_mag[slot0 + p] = m; b_idx[slot0 + p] = idx; }
+    walk.for_each([&](bool valid, u32 i, u32 s, u32 j, u32, u32) {
+        if (!valid) return;
+        u32 idx, bits;
+        cand.entry(s, j, &idx, &bits);
+        const u32 m = mag_of(bits);
+        if (m > bd_hi) {
+            bool sure = g.take_all != 0u;
+            if (!sure) {
+                const u64 key = sample_key(idx, seed);
+                if (key < g.K_lo) {
+                    sure = true;
+                } else if (key <= g.K_hi) {
+                    const u32 p = atomicAdd(&cnt_m, 1u);
+                    if (p < kListCap) { m_key[slot0 + p] = key; m_idx[slot0 + p] = idx; }
                 }
             }
+            if (sure) atomicAdd(&per_chunk[wave][i], 1u);
+        } else if (m >= bd_lo) {
+            const u32 p = atomicAdd(&cnt_b, 1u);
+            if (p < kListCap) { b_mag[slot0 + p] = m; b_idx[slot0 + p] = idx; }
         }
-        sure = (u32)wave_sum_u64(sure);
-        if (lane == 0) win_sure[u] = sure;
+    });
+    __builtin_amdgcn_wave_barrier();
+    // certain winners of each of the wavefront's chunks
+    u32 mine = 0;
+    if (u < g.U && lane < kUnitChunks) {
+        const u32 s = u + lane * g.U;
+        if (s < g.W) {
+            mine = per_chunk[wave][lane];
+            win_cnt[s] = mine;
+        }
     }
+    mine = (u32)wave_sum_u64(mine);
+    if (lane == 0 && mine) atomicAdd(&cnt_sure, mine);
     __syncthreads();
     if (threadIdx.x == 0) {
+        blk_sure[blockIdx.x] = cnt_sure;
         n_m[blockIdx.x] = cnt_m < kListCap ? cnt_m : kListCap;
         n_b[blockIdx.x] = cnt_b < kListCap ? cnt_b : kListCap;
         if (cnt_m > kListCap || cnt_b > kListCap) ctl->overflow = 1u;
@@ -519,7 +797,9 @@ k_classify(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ hist
 // workgroup in a way that does not change between calls). Returns the
 // rank-th smallest string (rank is 1-based). Bytes before first_byte are
 // known to be zero in every string. *ok is cleared when fewer than `rank`
-// strings exist.
+// strings exist. One barrier per byte: the 256-bin histogram rotates through
+// three buffers (the next one is cleared while the current one is filled)
+// and every wavefront repeats the walk over the bins for itself.
 // ---------------------------------------------------------------------------
 struct Pair96 {
     u64 hi;
@@ -542,52 +822,50 @@ __device__ __forceinline__ bool pair_matches(u64 hi, u32 lo, u64 phi, u32 plo, i
 
 template <class ForEach>
 __device__ __forceinline__ Pair96 block_select96(ForEach &&for_each, u64 rank, int first_byte,
-                                                 u32 *h /* 256 */, u64 *scratch /* 4 */, bool *ok)
+                                                 u32 (*h)[256] /* 3 buffers */,
+                                                 u64 *scratch /* 2 */, bool *ok)
 {
     u64 phi = 0;
     u32 plo = 0;
     u64 need = rank;
     int j = first_byte;
+    const u32 lane = lane_id();
     *ok = true;
+    for (u32 b = threadIdx.x; b < 256u; b += blockDim.x) h[0][b] = 0u;
+    __syncthreads();
+    u32 cur = 0;
     for (; j < 12; ++j) {
-        for (u32 b = threadIdx.x; b < 256u; b += blockDim.x) h[b] = 0u;
-        if (threadIdx.x == 0) { scratch[0] = 0; scratch[1] = 0; scratch[2] = 0; }
-        __syncthreads();
+        const u32 nxt = cur == 2u ? 0u : cur + 1u;
+        for (u32 b = threadIdx.x; b < 256u; b += blockDim.x) h[nxt][b] = 0u;
         for_each([&](u64 hi, u32 lo) {
-            if (pair_matches(hi, lo, phi, plo, j)) atomicAdd(&h[pair_byte(hi, lo, j)], 1u);
+            if (pair_matches(hi, lo, phi, plo, j)) atomicAdd(&h[cur][pair_byte(hi, lo, j)], 1u);
         });
         __syncthreads();
-        if (threadIdx.x < (u32)kWave) {
-            const u32 lane = threadIdx.x;
-            u64 c[4], mine = 0;
+        // every wavefront: lane l owns bins 4l .. 4l+3
+        u32 c[4];
+        u64 mine = 0;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) { c[q] = h[4 * lane + q]; mine += c[q]; }
-            u64 inc = mine;
+        for (int q = 0; q < 4; ++q) { c[q] = h[cur][4 * lane + q]; mine += c[q]; }
+        const u64 inc = wave_inclusive(mine);
+        u64 run = inc - mine;
+        const u64 owner = __ballot(run < need && need <= inc);
+        if (owner == 0ull) { *ok = false; return Pair96{0, 0}; }
+        u32 bin = 0, in_bin = 0;
+        u64 before = 0;
 #pragma unroll
-            for (int off = 1; off < kWave; off <<= 1) {
-                const u64 t = __shfl_up(inc, off, kWave);
-                if (lane >= (u32)off) inc += t;
-            }
-            u64 run = inc - mine;
-            if (run < need && need <= inc) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    if (run < need && need <= run + c[q]) {
-                        scratch[0] = 4 * lane + q; scratch[1] = run; scratch[2] = c[q];
-                    }
-                    run += c[q];
-                }
-            }
+        for (int q = 0; q < 4; ++q) {
+            if (run < need && need <= run + c[q]) { bin = 4 * lane + q; before = run; in_bin = c[q]; }
+            run += c[q];
         }
-        __syncthreads();
-        const u32 bin = (u32)scratch[0];
-        const u64 in_bin = scratch[2];
-        need -= scratch[1];
-        __syncthreads();
-        if (in_bin == 0) { *ok = false; return Pair96{0, 0}; }
+        const int src = __ffsll((unsigned long long)owner) - 1;
+        bin = __shfl(bin, src, kWave);
+        in_bin = __shfl(in_bin, src, kWave);
+        before = __shfl(before, src, kWave);
+        need -= before;
         if (j < 8) phi |= (u64)bin << (56 - 8 * j);
         else plo |= bin << (24 - 8 * (j - 8));
-        if (in_bin == 1) { ++j; break; }
+        cur = nxt;
+        if (in_bin == 1u) { ++j; break; }
     }
     if (j < 12) {
         // exactly one string starts with the resolved bytes: fetch the rest of it
@@ -597,8 +875,8 @@ __device__ __forceinline__ Pair96 block_select96(ForEach &&for_each, u64 rank, i
         __syncthreads();
         phi = scratch[0];
         plo = (u32)scratch[1];
-        __syncthreads();
     }
+    __syncthreads();
     return Pair96{phi, plo};
 }
 
@@ -620,22 +898,23 @@ __device__ __forceinline__ u32 region_of(const u32 *off, u32 n, u32 p)
 
 // ---------------------------------------------------------------------------
 // finalize: one workgroup turns the short lists into the two cut points and
-// the per-unit output offsets.
+// the output offset of every chunk.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(kFinThreads)
-k_finalize(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ seg_count,
-           const u32 *__restrict__ s_idx, const u32 *__restrict__ s_val,
-           const u32 *__restrict__ win_sure, const u32 *__restrict__ n_m,
-           const u32 *__restrict__ n_b, const u64 *__restrict__ m_key,
-           const u32 *__restrict__ m_idx, const u32 *__restrict__ b_mag,
-           const u32 *__restrict__ b_idx, u64 *dm_key, u32 *dm_idx, u64 *db_key, u32 *db_idx,
-           u32 *__restrict__ unit_base)
+k_finalize(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__ a,
+           const u32 *__restrict__ seg_count, const u32 *__restrict__ s_idx,
+           const u32 *__restrict__ s_val, u32 *win_cnt, const u32 *__restrict__ blk_sure,
+           const u32 *__restrict__ n_m, const u32 *__restrict__ n_b,
+           const u64 *__restrict__ m_key, const u32 *__restrict__ m_idx,
+           const u32 *__restrict__ b_mag, const u32 *__restrict__ b_idx, u64 *dm_key,
+           u32 *dm_idx, u64 *db_key, u32 *db_idx, u32 *__restrict__ chunk_base)
 {
-    __shared__ u32 off_m[kMaxWalkBlocks + 1], off_b[kMaxWalkBlocks + 1];
-    __shared__ u32 unit_cnt[kMaxUnits];
-    __shared__ u32 h[256];
-    __shared__ u64 scan_lds[kFinThreads / kWave + 1];
-    __shared__ u64 scratch[4];
+    static_assert(kMaxWalkBlocks <= (u32)kFinThreads, "one thread per classify workgroup");
+    __shared__ u32 off_m[kFinThreads + 1], off_b[kFinThreads + 1];
+    __shared__ u32 h[3][256];
+    __shared__ u32 scan32[kSlabs * kFinWaves + 1];
+    __shared__ u64 scan64[kFinWaves + 1];
+    __shared__ u64 scratch[2];
     __shared__ u64 st_b_key[kStageB];
     __shared__ u32 st_b_idx[kStageB];
     __shared__ u64 st_m_key[kStageM];
@@ -644,74 +923,75 @@ k_finalize(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ seg_
     __shared__ unsigned long long gt_extra;
 
     const u32 tid = threadIdx.x;
-    const u32 nwaves = kFinThreads / kWave, wave = tid / kWave, lane = lane_id();
-    auto unit_of = [&](u32 idx) { return (idx / g.C) / g.SU; };
-    // every entry of S, split wavefront by chunk
+    const u32 wave = tid / kWave, lane = lane_id();
+    const bool dense = ctl->dense != 0u;
+    const Candidates cand{seg_count, s_idx, s_val, a, g.d, g.C, dense};
+    // every candidate, split wavefront by chunk; f(index, pattern, chunk)
     auto each_s = [&](auto &&f) {
-        for (u32 s = wave; s < g.W; s += nwaves) {
-            const u32 n = seg_count[s];
-            const u64 at = (u64)s * g.C;
-            for (u32 j = lane; j < n; j += kWave) f(s_idx[at + j], s_val[at + j]);
+        for (u32 s = wave; s < g.W; s += kFinWaves) {
+            const u32 n = cand.count(s);
+            for (u32 j = lane; j < n; j += kWave) {
+                u32 idx, bits;
+                cand.entry(s, j, &idx, &bits);
+                f(idx, bits, s);
+            }
         }
     };
 
-    u64 my_sure = 0, my_super = 0;
-    for (u32 u = tid; u < kMaxUnits; u += kFinThreads) {
-        const u32 c = u < g.U ? win_sure[u] : 0u;
-        unit_cnt[u] = c;
-        my_sure += c;
-    }
-    for (u32 s = tid; s < g.W; s += kFinThreads) my_super += seg_count[s];
+    // ---- everything the short-list path needs, fetched in one round ------
+    const bool in_grid = tid < g.G3;
+    const u32 vm = in_grid ? n_m[tid] : 0u, vb = in_grid ? n_b[tid] : 0u;
+    const u32 vs = in_grid ? blk_sure[tid] : 0u;
+    const u32 bd_hi = ctl->bd_hi, bd_bits = ctl->bd_bits;
+    const u64 c_def = ctl->c_def;
+    const bool overflow = ctl->overflow != 0u;
     if (tid == 0) { extra_m = 0u; sure_extra = 0u; gt_extra = 0ull; }
-    const u32 vm = tid < g.G3 ? n_m[tid] : 0u, vb = tid < g.G3 ? n_b[tid] : 0u;
-    const u32 em = (u32)block_exclusive_sum(vm, scan_lds);
-    const u32 eb = (u32)block_exclusive_sum(vb, scan_lds);
+    const u32 em = block_exclusive_sum(vm, scan32);
+    const u32 n_m0 = scan32[kFinWaves];
+    const u32 eb = block_exclusive_sum(vb, scan32);
+    const u32 n_bd = scan32[kFinWaves];
     off_m[tid] = em;
     off_b[tid] = eb;
     if (tid == kFinThreads - 1) { off_m[kFinThreads] = em + vm; off_b[kFinThreads] = eb + vb; }
-    const u64 sure_walk = block_sum(my_sure, scan_lds);
-    const u64 superset = block_sum(my_super, scan_lds);
-    __syncthreads();
-    const u32 n_m0 = off_m[kFinThreads], n_bd = off_b[kFinThreads];
+    const u64 sure_walk = block_sum(vs, scan64);
 
-    const u32 bd_hi = ctl->bd_hi, h_shift = ctl->h_shift;
-    const u64 c_def = ctl->c_def;
     const u64 need2 = g.r - c_def;
     u32 err = 0, path = 0;
     bool have_t = false, have_k = false, ok = true;
     u32 T = 0, I_star = 0, J_star = 0xFFFFFFFFu, n_mm = 0;
     u64 K_star = ~0ull, count_greater = 0;
 
-    if (ctl->overflow == 0u && need2 >= 1 && need2 <= n_bd) {
-        // ---- exact threshold inside the deciding bin --------------------
+    if (!dense && !overflow && c_def < g.r && need2 <= n_bd) {
+        // ---- gather both short lists (one round of loads) ----------------
         const bool b_lds = n_bd <= kStageB;
         u64 *bk = b_lds ? st_b_key : db_key;
         u32 *bi = b_lds ? st_b_idx : db_idx;
+        const bool m_lds = n_m0 + n_bd <= kStageM;
+        u64 *mk = m_lds ? st_m_key : dm_key;
+        u32 *mi = m_lds ? st_m_idx : dm_idx;
         for (u32 p = tid; p < n_bd; p += kFinThreads) {
             const u32 b = region_of(off_b, g.G3, p);
             const u64 at = (u64)b * kListCap + (p - off_b[b]);
             bk[p] = (u64)(bd_hi - b_mag[at]);
             bi[p] = b_idx[at];
         }
+        for (u32 p = tid; p < n_m0; p += kFinThreads) {
+            const u32 b = region_of(off_m, g.G3, p);
+            const u64 at = (u64)b * kListCap + (p - off_m[b]);
+            mk[p] = (m_key[at] - g.K_lo) << g.k_nlz;
+            mi[p] = m_idx[at];
+        }
         __syncthreads();
+        // ---- exact threshold inside the deciding bin --------------------
         auto each_b = [&](auto &&f) {
             for (u32 p = tid; p < n_bd; p += kFinThreads) f(bk[p], bi[p]);
         };
-        const Pair96 tb = block_select96(each_b, need2, (64 - (int)h_shift) / 8, h, scratch, &ok);
+        const Pair96 tb = block_select96(each_b, need2, (64 - (int)bd_bits) / 8, h, scratch, &ok);
         if (ok) {
             have_t = true;
             T = bd_hi - (u32)tb.hi;
             I_star = tb.lo;
-            // ---- key lists: walked members + members of the deciding bin
-            const bool m_lds = n_m0 + n_bd <= kStageM;
-            u64 *mk = m_lds ? st_m_key : dm_key;
-            u32 *mi = m_lds ? st_m_idx : dm_idx;
-            for (u32 p = tid; p < n_m0; p += kFinThreads) {
-                const u32 b = region_of(off_m, g.G3, p);
-                const u64 at = (u64)b * kListCap + (p - off_m[b]);
-                mk[p] = (m_key[at] - g.K_lo) << g.k_nlz;
-                mi[p] = m_idx[at];
-            }
+            // ---- members of the deciding bin join the key lists ----------
             u32 my_gt = 0;
             for (u32 p = tid; p < n_bd; p += kFinThreads) {
                 const u64 hi = bk[p];
@@ -729,7 +1009,7 @@ k_finalize(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ seg_
                         mi[n_m0 + q] = idx;
                     }
                 }
-                if (sure) { atomicAdd(&unit_cnt[unit_of(idx)], 1u); atomicAdd(&sure_extra, 1u); }
+                if (sure) { atomicAdd(&win_cnt[idx / g.C], 1u); atomicAdd(&sure_extra, 1u); }
             }
             if (my_gt) atomicAdd(&gt_extra, (unsigned long long)my_gt);
             __syncthreads();
@@ -748,38 +1028,38 @@ k_finalize(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ seg_
                     K_star = (kb.hi >> g.k_nlz) + g.K_lo;
                     J_star = kb.lo;
                     for (u32 p = tid; p < n_mm; p += kFinThreads)
-                        if (pair_le(mk[p], mi[p], kb)) atomicAdd(&unit_cnt[unit_of(mi[p])], 1u);
+                        if (pair_le(mk[p], mi[p], kb)) atomicAdd(&win_cnt[mi[p] / g.C], 1u);
                 }
             }
         }
     }
 
     if (!have_t) {
-        // ---- exact threshold by selection over all of S -----------------
+        // ---- exact threshold by selection over all candidates -----------
         path = 1;
         auto each_mag = [&](auto &&f) {
-            each_s([&](u32 idx, u32 bits) { f((u64)(0x7FFFFFFFu - mag_of(bits)), idx); });
+            each_s([&](u32 idx, u32 bits, u32) { f((u64)(0x7FFFFFFFu - mag_of(bits)), idx); });
         };
         const Pair96 tb = block_select96(each_mag, g.r, 4, h, scratch, &ok);
         if (!ok) err |= kErrSelect;
         T = 0x7FFFFFFFu - (u32)tb.hi;
         I_star = tb.lo;
         u64 my_gt = 0;
-        each_s([&](u32, u32 bits) { if (mag_of(bits) > T) ++my_gt; });
-        count_greater = block_sum(my_gt, scan_lds);
+        each_s([&](u32, u32 bits, u32) { if (mag_of(bits) > T) ++my_gt; });
+        count_greater = block_sum(my_gt, scan64);
     }
     auto is_member = [&](u32 idx, u32 bits) {
         const u32 m = mag_of(bits);
         return m > T || (m == T && idx <= I_star);
     };
     if (!have_k) {
-        // ---- exact key cut and per-unit winners by selection over S -----
+        // ---- exact key cut and winners per chunk by selection over all candidates
         path = 1;
         __syncthreads();
-        for (u32 u = tid; u < kMaxUnits; u += kFinThreads) unit_cnt[u] = 0u;
+        for (u32 s = tid; s < g.W; s += kFinThreads) win_cnt[s] = 0u;
         if (!g.take_all) {
             auto each_key = [&](auto &&f) {
-                each_s([&](u32 idx, u32 bits) {
+                each_s([&](u32 idx, u32 bits, u32) {
                     if (is_member(idx, bits)) f(sample_key(idx, seed), idx);
                 });
             };
@@ -793,27 +1073,61 @@ k_finalize(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ seg_
         }
         __syncthreads();
         const Pair96 kcut{K_star, J_star};
-        each_s([&](u32 idx, u32 bits) {
+        each_s([&](u32 idx, u32 bits, u32 s) {
             if (is_member(idx, bits) &&
                 (g.take_all || pair_le(sample_key(idx, seed), idx, kcut)))
-                atomicAdd(&unit_cnt[unit_of(idx)], 1u);
+                atomicAdd(&win_cnt[s], 1u);
         });
     }
     __syncthreads();
 
-    // ---- output offset of every unit ------------------------------------
-    constexpr u32 per = kMaxUnits / kFinThreads;
-    u32 c[per];
-    u64 mine = 0;
+    // ---- output offset of every chunk: thread t holds the counters of chunks
+    //      4*(1024*q + t) .. +3, q < kSlabs; prefix sums run slab after slab.
+    //      This is the workgroup's first read of the counters, after the
+    //      barrier that follows its atomics on them.
+    u32 c[kSlabs][4], s4[kSlabs], inc[kSlabs];
 #pragma unroll
-    for (u32 q = 0; q < per; ++q) { c[q] = unit_cnt[tid * per + q]; mine += c[q]; }
-    u64 run = block_exclusive_sum(mine, scan_lds);
-    const u64 total = scan_lds[kFinThreads / kWave];
+    for (u32 q = 0; q < kSlabs; ++q) {
+        const u32 s = 4u * (q * kFinThreads + tid);
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (s < g.W) v = reinterpret_cast<const uint4 *>(win_cnt)[q * kFinThreads + tid];
+        c[q][0] = v.x;
+        c[q][1] = s + 1 < g.W ? v.y : 0u;
+        c[q][2] = s + 2 < g.W ? v.z : 0u;
+        c[q][3] = s + 3 < g.W ? v.w : 0u;
+        s4[q] = c[q][0] + c[q][1] + c[q][2] + c[q][3];
+    }
 #pragma unroll
-    for (u32 q = 0; q < per; ++q) {
-        const u32 u = tid * per + q;
-        if (u < g.U) unit_base[u] = (u32)run;
-        run += c[q];
+    for (u32 q = 0; q < kSlabs; ++q) inc[q] = wave_inclusive(s4[q]);
+    if (lane == kWave - 1) {
+#pragma unroll
+        for (u32 q = 0; q < kSlabs; ++q) scan32[q * kFinWaves + wave] = inc[q];
+    }
+    __syncthreads();
+    {
+        constexpr u32 n = kSlabs * kFinWaves;          // 128 partial sums, two per lane of wave 0
+        static_assert(n == 2 * kWave, "two partial sums per lane");
+        if (wave == 0) {
+            const u32 a0 = scan32[2 * lane], a1 = scan32[2 * lane + 1];
+            const u32 xi = wave_inclusive(a0 + a1);
+            scan32[2 * lane] = xi - (a0 + a1);
+            scan32[2 * lane + 1] = xi - a1;
+            if (lane == kWave - 1) scan32[n] = xi;
+        }
+    }
+    __syncthreads();
+    const u64 total = scan32[kSlabs * kFinWaves];
+#pragma unroll
+    for (u32 q = 0; q < kSlabs; ++q) {
+        const u32 s = 4u * (q * kFinThreads + tid);
+        if (s < g.W) {
+            uint4 o;
+            o.x = scan32[q * kFinWaves + wave] + inc[q] - s4[q];
+            o.y = o.x + c[q][0];
+            o.z = o.y + c[q][1];
+            o.w = o.z + c[q][2];
+            reinterpret_cast<uint4 *>(chunk_base)[q * kFinThreads + tid] = o;
+        }
     }
     if (total != g.k) err |= kErrCount;
     if (tid == 0) {
@@ -825,7 +1139,7 @@ k_finalize(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ seg_
         ctl->J_star = J_star;
         ctl->n_b = n_bd;
         ctl->n_m = n_mm;
-        ctl->superset = superset;
+        ctl->W = g.W;
         ctl->count_greater = count_greater;
         ctl->ties = g.r - count_greater;
     }
@@ -834,48 +1148,54 @@ k_finalize(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ seg_
 // ---------------------------------------------------------------------------
 // emit: members of the top-r set whose (key, index) is at or below the cut
 // -> the message in index order; residual at the sent positions <- a - a.
+// A winner's place is the output offset of its chunk plus the number of
+// winners before it in the chunk; the latter is kept as the difference of two
+// running totals over the wavefront's flat walk.
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(kWalkThreads)
 k_emit(Geom g, PhiloxSeed seed, const EncodeCtl *__restrict__ ctl,
        const u32 *__restrict__ seg_count, const u32 *__restrict__ s_idx,
-       const u32 *__restrict__ s_val, const u32 *__restrict__ unit_base,
-       u32 *__restrict__ out_idx, float *__restrict__ out_val, float *__restrict__ residual)
+       const u32 *__restrict__ s_val, const u32 *__restrict__ chunk_base,
+       u32 *__restrict__ out_idx, float *__restrict__ out_val, float *residual)
 {
     const u32 u = blockIdx.x * kWalkWaves + threadIdx.x / kWave;
     if (u >= g.U) return;
     const u32 lane = lane_id();
+    const Candidates cand{seg_count, s_idx, s_val, residual, g.d, g.C, ctl->dense != 0u};
+    const UnitWalk walk(cand, g, u);
+    const u32 my_chunk = u + lane * g.U;
+    const u32 my_base = (lane < kUnitChunks && my_chunk < g.W) ? chunk_base[my_chunk] : 0u;
     const u32 T = ctl->T, I_star = ctl->I_star;
     const Pair96 kcut{ctl->K_star, ctl->J_star};
     const u64 below = lanes_below();
-    u64 run = unit_base[u];
-    const u32 s_end = (u + 1) * g.SU < g.W ? (u + 1) * g.SU : g.W;
-    for (u32 s = u * g.SU; s < s_end; ++s) {
-        const u32 n = seg_count[s];
-        const u64 at = (u64)s * g.C;
-        for (u32 j0 = 0; j0 < n; j0 += kWave) {
-            const u32 j = j0 + lane;
-            bool win = false;
-            u32 idx = 0, bits = 0;
-            if (j < n) {
-                idx = s_idx[at + j];
-                bits = s_val[at + j];
-                const u32 m = mag_of(bits);
-                win = m > T || (m == T && idx <= I_star);
-                if (win && !g.take_all) win = pair_le(sample_key(idx, seed), idx, kcut);
-            }
-            const u64 mask = __ballot(win);
-            if (win) {
-                const u64 pos = run + popc64(mask & below);
-                if (pos < g.k) {
-                    const float v = __uint_as_float(bits);
-                    out_idx[pos] = idx;
-                    out_val[pos] = v;
-                    residual[idx] = v - v;
-                }
-            }
-            run += popc64(mask);
+    u32 run = 0;          // winners at flat positions before this iteration
+    u32 carry = 0;        // winners before the first entry of the chunk that runs into this iteration
+    walk.for_each([&](bool valid, u32 i, u32 s, u32 j, u32 first, u32 p0) {
+        bool win = false;
+        u32 idx = 0, bits = 0;
+        if (valid) {
+            cand.entry(s, j, &idx, &bits);
+            const u32 m = mag_of(bits);
+            win = m > T || (m == T && idx <= I_star);
+            if (win && !g.take_all) win = pair_le(sample_key(idx, seed), idx, kcut);
         }
-    }
+        const u64 mask = __ballot(win);
+        // winners before the first entry of this lane's chunk
+        const u32 at_start =
+            first >= p0 ? run + popc64(mask & ((1ull << (first - p0)) - 1ull)) : carry;
+        const u32 base_c = __shfl(my_base, i, kWave);
+        if (win) {
+            const u64 pos = (u64)base_c + (run + popc64(mask & below) - at_start);
+            if (pos < g.k) {
+                const float v = __uint_as_float(bits);
+                out_idx[pos] = idx;
+                out_val[pos] = v;
+                residual[idx] = v - v;
+            }
+        }
+        carry = __shfl(at_start, kWave - 1, kWave);
+        run += popc64(mask);
+    });
 }
 
 }  // namespace rtopk
@@ -923,6 +1243,35 @@ struct StageScope {
         if (on) (void)hipEventRecord(tr.end, stream);
     }
 };
+
+// Workgroups of the streaming kernel the current device holds at once (a
+// property of the device and the compiled kernel, looked up once per device).
+constexpr int kMaxDevices = 64;
+std::mutex g_resident_mutex;
+unsigned g_resident[kMaxDevices][2];
+
+int resident_fused_blocks(bool vec4, unsigned *out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return RTOPK_EHIP;
+    std::lock_guard<std::mutex> lock(g_resident_mutex);
+    unsigned &slot = g_resident[dev][vec4 ? 1 : 0];
+    if (slot == 0) {
+        int per_cu = 0, cus = 0;
+        const hipError_t e1 =
+            vec4 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_fused<true>,
+                                                                (int)kFusedThreads, 0)
+                 : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_fused<false>,
+                                                                (int)kFusedThreads, 0);
+        const hipError_t e2 =
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e1 != hipSuccess || e2 != hipSuccess || per_cu < 1 || cus < 1) return RTOPK_EHIP;
+        slot = (unsigned)per_cu * (unsigned)cus;
+        if (slot > kMaxFusedBlocks) slot = kMaxFusedBlocks;
+    }
+    *out = slot;
+    return RTOPK_OK;
+}
 }  // namespace
 
 extern "C" int rtopk_trace_next_encode(int stage, void *ev_begin, void *ev_end)
@@ -959,9 +1308,10 @@ extern "C" int rtopk_encode(const float *grad, float *residual, uint64_t d, uint
     hipStream_t stream = (hipStream_t)stream_v;
     char *ws = (char *)workspace;
     EncodeCtl *ctl = (EncodeCtl *)(ws + L.ctl);
-    u32 *hist1 = (u32 *)(ws + L.hist1), *hist2 = (u32 *)(ws + L.hist2);
-    u32 *seg_count = (u32 *)(ws + L.seg_count), *win_sure = (u32 *)(ws + L.win_sure);
-    u32 *unit_base = (u32 *)(ws + L.unit_base);
+    u32 *hist = (u32 *)(ws + L.hist), *samples = (u32 *)(ws + L.samples);
+    u32 *partials = (u32 *)(ws + L.partials);
+    u32 *seg_count = (u32 *)(ws + L.seg_count), *win_cnt = (u32 *)(ws + L.win_cnt);
+    u32 *chunk_base = (u32 *)(ws + L.chunk_base), *blk_sure = (u32 *)(ws + L.blk_sure);
     u32 *n_m = (u32 *)(ws + L.n_m), *n_b = (u32 *)(ws + L.n_b);
     u64 *m_key = (u64 *)(ws + L.m_key), *dm_key = (u64 *)(ws + L.dm_key);
     u64 *db_key = (u64 *)(ws + L.db_key);
@@ -972,57 +1322,57 @@ extern "C" int rtopk_encode(const float *grad, float *residual, uint64_t d, uint
 
     const PhiloxSeed ps{(u32)seed, (u32)(seed >> 32), (u32)step, (u32)(step >> 32)};
     const bool vec4 = (((uintptr_t)grad | (uintptr_t)residual) & 15u) == 0;
-    const bool rvec4 = ((uintptr_t)residual & 15u) == 0;
+    unsigned resident = 0;
+    const int rc2 = resident_fused_blocks(vec4, &resident);
+    if (rc2) return rc2;
 
     const TraceRequest trace = g_trace;
     g_trace = TraceRequest{};
     StageScope whole(trace, RTOPK_STAGE_ALL, stream);
 
     {
-        StageScope sc(trace, RTOPK_STAGE_INIT, stream);
-        const u32 words = (u32)(L.zero_bytes / 4);
-        k_init<<<(words + 255) / 256, 256, 0, stream>>>((u32 *)ws, words);
+        StageScope sc(trace, RTOPK_STAGE_PREPARE, stream);
+        k_sample<<<kSampleLoc / kSampleThreads, kSampleThreads, 0, stream>>>(
+            grad, residual, g, (u32 *)ws, (u32)(L.zero_bytes / 4), samples);
+        RTOPK_LAUNCH_CHECK();
+        k_estimate<<<1, kEstThreads, 0, stream>>>(samples, g, ctl);
         RTOPK_LAUNCH_CHECK();
     }
     {
         StageScope sc(trace, RTOPK_STAGE_FUSED, stream);
-        const u64 per_block = (u64)kFusedThreads * (vec4 ? 16 : 4);
-        u64 want = (d + per_block - 1) / per_block;
-        const unsigned grid = (unsigned)(want < 1 ? 1 : (want > 512 ? 512 : want));
+        unsigned grid = (g.W + kFusedWaves - 1) / kFusedWaves;
+        if (grid > resident) grid = resident;
         if (vec4)
-            k_fused_add_hist<true><<<grid, kFusedThreads, 0, stream>>>(grad, residual, d, hist1);
+            k_fused<true><<<grid, kFusedThreads, 0, stream>>>(grad, residual, g, ctl, partials,
+                                                              seg_count, s_idx, s_val);
         else
-            k_fused_add_hist<false><<<grid, kFusedThreads, 0, stream>>>(grad, residual, d, hist1);
+            k_fused<false><<<grid, kFusedThreads, 0, stream>>>(grad, residual, g, ctl, partials,
+                                                               seg_count, s_idx, s_val);
         RTOPK_LAUNCH_CHECK();
-    }
-    {
-        StageScope sc(trace, RTOPK_STAGE_SCAN, stream);
-        const unsigned grid = (g.W + kWalkWaves - 1) / kWalkWaves;
-        if (rvec4)
-            k_scan<true><<<grid, kWalkThreads, 0, stream>>>(residual, g, ctl, hist1, hist2,
-                                                            seg_count, s_idx, s_val);
-        else
-            k_scan<false><<<grid, kWalkThreads, 0, stream>>>(residual, g, ctl, hist1, hist2,
-                                                             seg_count, s_idx, s_val);
+        const dim3 rgrid((g.nfine + kCoarseBins + kReduceThreads - 1) / kReduceThreads, kHistRows);
+        k_reduce<<<rgrid, kReduceThreads, 0, stream>>>(partials, grid, ctl, hist);
         RTOPK_LAUNCH_CHECK();
     }
     {
         StageScope sc(trace, RTOPK_STAGE_CLASSIFY, stream);
-        k_classify<<<g.G3, kWalkThreads, 0, stream>>>(g, ps, ctl, hist2, seg_count, s_idx, s_val,
-                                                      win_sure, n_m, n_b, m_key, m_idx, b_mag,
-                                                      b_idx);
+        k_pick<<<1, kPickThreads, 0, stream>>>(hist, g, ctl);
+        RTOPK_LAUNCH_CHECK();
+        k_classify<<<g.G3, kWalkThreads, 0, stream>>>(g, ps, ctl, seg_count, s_idx, s_val,
+                                                      win_cnt, blk_sure, n_m, n_b, m_key, m_idx,
+                                                      b_mag, b_idx);
         RTOPK_LAUNCH_CHECK();
     }
     {
         StageScope sc(trace, RTOPK_STAGE_FINALIZE, stream);
-        k_finalize<<<1, kFinThreads, 0, stream>>>(g, ps, ctl, seg_count, s_idx, s_val, win_sure,
-                                                  n_m, n_b, m_key, m_idx, b_mag, b_idx, dm_key,
-                                                  dm_idx, db_key, db_idx, unit_base);
+        k_finalize<<<1, kFinThreads, 0, stream>>>(g, ps, ctl, residual, seg_count, s_idx, s_val,
+                                                  win_cnt, blk_sure, n_m, n_b, m_key, m_idx,
+                                                  b_mag, b_idx, dm_key, dm_idx, db_key, db_idx,
+                                                  chunk_base);
         RTOPK_LAUNCH_CHECK();
     }
     {
         StageScope sc(trace, RTOPK_STAGE_EMIT, stream);
-        k_emit<<<g.G3, kWalkThreads, 0, stream>>>(g, ps, ctl, seg_count, s_idx, s_val, unit_base,
+        k_emit<<<g.G3, kWalkThreads, 0, stream>>>(g, ps, ctl, seg_count, s_idx, s_val, chunk_base,
                                                   out_idx, out_val, residual);
         RTOPK_LAUNCH_CHECK();
     }
@@ -1038,13 +1388,23 @@ extern "C" int rtopk_encode_stats(const void *workspace, void *stream_v,
     EncodeCtl c;
     if (hipMemcpy(&c, workspace, sizeof c, hipMemcpyDeviceToHost) != hipSuccess)
         return RTOPK_EHIP;
+    // candidates kept by the streaming kernel: the chunk sizes, added up here
+    uint64_t superset = 0;
+    if (c.W > 0 && c.W <= kTargetChunks) {
+        const EncodeLayout L = make_layout(Geom{});   // the offset of seg_count is fixed
+        std::vector<u32> counts(c.W);
+        if (hipMemcpy(counts.data(), (const char *)workspace + L.seg_count, (size_t)c.W * 4,
+                      hipMemcpyDeviceToHost) != hipSuccess)
+            return RTOPK_EHIP;
+        for (u32 x : counts) superset += x;
+    }
     host_out->error_flags = c.err;
-    host_out->path = c.path;
+    host_out->path = c.path | (c.dense ? 2u : 0u);
     host_out->threshold_bits = c.T;
     host_out->boundary_list_size = c.n_b;
     host_out->count_greater = c.count_greater;
     host_out->ties_taken = c.ties;
-    host_out->superset_size = c.superset;
+    host_out->superset_size = superset;
     host_out->key_list_size = c.n_m;
     return RTOPK_OK;
 }
