@@ -9,6 +9,11 @@ configuration (d = 25,557,032, r = 0.5% d, k = 0.1% d, n = 8 workers) that the
 headline metric is quoted on. All gradients of the warm-up and timed steps are
 resident in HBM before the clock starts.
 
+By default everything runs on one stream, one kernel at a time. The n workers
+of a step are independent (Algorithm 1 runs them on n nodes), so with
+``--streams S`` their encodes are dealt to S HIP streams, each with its own
+workspace; the kernel durations measured then include whatever ran beside them.
+
 Prints ONE JSON line:
   value      = gradient bytes consumed per second over whole steps
                (n * 4d bytes per step / seconds per step), GB/s
@@ -111,6 +116,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=3, help="workload configuration (1-5)")
     ap.add_argument("--workers", type=int, default=None, help="override the worker count")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="HIP streams the simulated workers are dealt to (each with its own "
+                         "workspace); 1 = strictly one kernel at a time")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=2, help="oracle encodes to time")
     args = ap.parse_args()
@@ -133,6 +141,7 @@ def main() -> int:
     d, r, k = wl.d, wl.r, wl.k
     n = args.workers or wl.n_workers
     K, W = args.steps, args.warmup
+    S = max(1, min(args.streams, n))
     total_steps = K + W
 
     # ---- inputs: every gradient of every step resident in HBM ------------
@@ -142,56 +151,67 @@ def main() -> int:
     idx = torch.empty(n * k, dtype=torch.int32, device=dev)
     val = torch.empty(n * k, dtype=torch.float32, device=dev)
     out = torch.empty(d, dtype=torch.float32, device=dev)
-    ws = torch.empty(rt.encode_workspace_bytes(d, r, k), dtype=torch.uint8, device=dev)
-    stream = torch.cuda.current_stream()
+    ws_bytes = rt.encode_workspace_bytes(d, r, k)
+    ws = [torch.empty(ws_bytes, dtype=torch.uint8, device=dev) for _ in range(S)]
+    streams = [torch.cuda.Stream(device=dev) for _ in range(S)]     # default priority
+    joined = [torch.cuda.Event() for _ in range(S)]
+    released = torch.cuda.Event()
+    torch.cuda.synchronize()
 
-    def one_step(t: int, trace=None):
+    def one_step(t: int, trace=None, phase=None):
+        """n encodes dealt round-robin to the streams, then the master's
+        average on stream 0 once every stream has finished its encodes; the
+        next step's encodes start after the average (it reads the messages
+        they overwrite)."""
+        for s in range(1, S):
+            streams[s].wait_event(released)
+        if phase is not None:
+            phase[0].record(streams[0])
         for w in range(n):
+            s = w % S
             if trace is not None:
                 rt.trace_next_encode(rt.STAGES["fused"], *trace[w])
             rt.encode(grads[t][w], residual[w], r, k, philox_seed_for_worker(w), t,
-                      idx[w * k:(w + 1) * k], val[w * k:(w + 1) * k], ws, stream)
-        rt.aggregate(idx, val, n, k, out, None, stream)
+                      idx[w * k:(w + 1) * k], val[w * k:(w + 1) * k], ws[s], streams[s])
+        for s in range(1, S):
+            joined[s].record(streams[s])
+            streams[0].wait_event(joined[s])
+        if phase is not None:
+            phase[1].record(streams[0])
+        rt.aggregate(idx, val, n, k, out, None, streams[0])
+        if phase is not None:
+            phase[2].record(streams[0])
+        released.record(streams[0])
 
+    released.record(streams[0])
     for t in range(W):
         one_step(t)
     torch.cuda.synchronize()
 
-    # ---- timed region: K steps, events on the launch stream ---------------
+    # ---- timed region: K steps, events on the launch streams ---------------
     ev = HipEvents()
     fused_pairs = [[(ev.new(), ev.new()) for _ in range(n)] for _ in range(K)]
-    phase = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True),
-              torch.cuda.Event(enable_timing=True)) for _ in range(K)]
+    phase = [tuple(torch.cuda.Event(enable_timing=True) for _ in range(3)) for _ in range(K)]
     torch.cuda.synchronize()
     t_wall0 = time.perf_counter()
-    for s in range(K):
-        t = W + s
-        phase[s][0].record(stream)
-        for w in range(n):
-            rt.trace_next_encode(rt.STAGES["fused"], *fused_pairs[s][w])
-            rt.encode(grads[t][w], residual[w], r, k, philox_seed_for_worker(w), t,
-                      idx[w * k:(w + 1) * k], val[w * k:(w + 1) * k], ws, stream)
-        phase[s][1].record(stream)
-        rt.aggregate(idx, val, n, k, out, None, stream)
-        phase[s][2].record(stream)
+    for s_ in range(K):
+        one_step(W + s_, trace=fused_pairs[s_], phase=phase[s_])
     torch.cuda.synchronize()
     t_wall1 = time.perf_counter()
-
-    stats = rt.encode_stats(ws)
-    if stats["error_flags"] != 0:
-        print(f"bench.py: encode reported error flags {stats}", file=sys.stderr)
-        return 4
-
     total_ms = phase[0][0].elapsed_time(phase[-1][2])
-    enc_ms = sum(p[0].elapsed_time(p[1]) for p in phase)
-    agg_ms = sum(p[1].elapsed_time(p[2]) for p in phase)
+    enc_ms_call = sum(p[0].elapsed_time(p[1]) for p in phase) / (K * n)
+    agg_ms_call = sum(p[1].elapsed_time(p[2]) for p in phase) / K
     fused_ms = [ev.elapsed_ms(a, b) for row in fused_pairs for (a, b) in row]
     ev.close()
-    ms_per_step = total_ms / K
-    enc_ms_call = enc_ms / (K * n)
-    agg_ms_call = agg_ms / K
-    fused_ms_avg = sum(fused_ms) / len(fused_ms)
 
+    for s in range(S):
+        stats = rt.encode_stats(ws[s])
+        if stats["error_flags"] != 0:
+            print(f"bench.py: encode reported error flags {stats}", file=sys.stderr)
+            return 4
+
+    ms_per_step = total_ms / K
+    fused_ms_avg = sum(fused_ms) / len(fused_ms)
     value = n * 4.0 * d / (ms_per_step * 1e-3) / 1e9
     achieved = 12.0 * d / (fused_ms_avg * 1e-3) / 1e9
     result = {
@@ -208,7 +228,8 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": wl.config.name, "d": d, "r": r, "k": k, "workers": n,
-                   "step": f"{n} x rtopk_encode + 1 x rtopk_aggregate"},
+                   "streams": S,
+                   "step": f"{n} x rtopk_encode on {S} stream(s) + 1 x rtopk_aggregate"},
         "encode_gradient_GBps": round(4.0 * d / (enc_ms_call * 1e-3) / 1e9, 2),
         "encode_ms_per_call": round(enc_ms_call, 4),
         "encode_pct_hbm_peak_at_12d": round(100.0 * 12.0 * d / (enc_ms_call * 1e-3) / 1e9

@@ -45,23 +45,38 @@ __device__ __forceinline__ u32 lane_id() { return threadIdx.x & (kWave - 1); }
 
 __device__ __forceinline__ u64 lanes_below() { return (1ull << lane_id()) - 1ull; }
 
-// inclusive prefix sum over the 64 lanes of a wave
-__device__ __forceinline__ u32 wave_inclusive_sum(u32 v)
+// Data-parallel-primitive move: every lane reads `v` from the lane the DPP
+// control selects inside its row of 16 (or, for the two row broadcasts, from
+// the last lane of the previous row / of the first half); lanes the row and
+// bank masks leave out, or whose source does not exist, get 0.
+template <int kCtrl, int kRowMask, int kBankMask>
+__device__ __forceinline__ u32 dpp_or_zero(u32 v)
 {
-    const u32 lane = lane_id();
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        const u32 t = __shfl_up(v, off, kWave);
-        if (lane >= (u32)off) v += t;
-    }
-    return v;
+    return (u32)__builtin_amdgcn_update_dpp(0, (int)v, kCtrl, kRowMask, kBankMask, false);
 }
 
-__device__ __forceinline__ u64 wave_sum_u64(u64 v)
+// Inclusive prefix sum over the 64 lanes of a wavefront in seven DPP adds
+// (a few cycles each; a shuffle goes through the LDS crossbar and costs a
+// hundred): a 4-wide window with row_shr 1..3, widened to the row of 16 with
+// row_shr 4 and 8 on the upper banks, then the row totals handed on with
+// row_bcast 15 (to rows 1 and 3) and row_bcast 31 (to rows 2 and 3).
+__device__ __forceinline__ u32 wave_inclusive_sum(u32 v)
 {
-#pragma unroll
-    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
-    return v;
+    u32 x = v;
+    x += dpp_or_zero<0x111, 0xF, 0xF>(v);
+    x += dpp_or_zero<0x112, 0xF, 0xF>(v);
+    x += dpp_or_zero<0x113, 0xF, 0xF>(v);
+    x += dpp_or_zero<0x114, 0xF, 0xE>(x);
+    x += dpp_or_zero<0x118, 0xF, 0xC>(x);
+    x += dpp_or_zero<0x142, 0xA, 0xF>(x);
+    x += dpp_or_zero<0x143, 0xC, 0xF>(x);
+    return x;
+}
+
+// sum over the wavefront, in every lane
+__device__ __forceinline__ u32 wave_sum(u32 v)
+{
+    return (u32)__builtin_amdgcn_readlane((int)wave_inclusive_sum(v), kWave - 1);
 }
 
 __host__ __device__ constexpr u64 align_up(u64 x, u64 a) { return (x + a - 1) / a * a; }

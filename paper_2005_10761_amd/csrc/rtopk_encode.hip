@@ -65,7 +65,7 @@ constexpr u32 kCoarseShift = 23;              // coarse bins above them: the 8 e
 constexpr u32 kCoarseBins = 256;
 constexpr u32 kMaxBins = kMaxFineBins + kCoarseBins;
 constexpr u32 kMaxFusedBlocks = 1024;         // rows of per-workgroup histograms
-constexpr u32 kHistRows = 8;                  // rows left after the first reduction step
+constexpr u32 kHistRows = 32;                 // rows left after the first reduction step
 
 constexpr u32 kSampleLoc = 16384;             // sampled locations, 4 consecutive elements each
 constexpr u32 kSampleThreads = 256;
@@ -231,62 +231,60 @@ static EncodeLayout make_layout(const Geom &g)
 __device__ __forceinline__ u32 mag_of(u32 bits) { return bits & 0x7FFFFFFFu; }
 __device__ __forceinline__ u32 popc64(u64 m) { return (u32)__popcll((unsigned long long)m); }
 
+// Workgroup barrier that orders LDS accesses only: global loads, stores and
+// atomics a thread has in flight stay in flight (__syncthreads would wait for
+// all of them to complete first).
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // ---------------------------------------------------------------------------
 // workgroup-wide sums of one value per thread (thread order); the second
 // level is a wavefront scan, not a serial loop: LDS round trips are slow
 // ---------------------------------------------------------------------------
-template <class T>
-__device__ __forceinline__ T wave_inclusive(T v)
-{
-    const u32 lane = lane_id();
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        const T t = __shfl_up(v, off, kWave);
-        if (lane >= (u32)off) v += t;
-    }
-    return v;
-}
-
 // exclusive prefix of v over the workgroup; the grand total is left in lds[waves]
-template <class T>
-__device__ __forceinline__ T block_exclusive_sum(T v, T *lds /* >= waves + 1 words */)
+__device__ __forceinline__ u32 block_exclusive_sum(u32 v, u32 *lds /* >= waves + 1 words */)
 {
     const u32 lane = lane_id(), wave = threadIdx.x / kWave, nw = blockDim.x / kWave;
-    const T inc = wave_inclusive(v);
+    const u32 inc = wave_inclusive_sum(v);
     if (lane == kWave - 1) lds[wave] = inc;
-    __syncthreads();
+    lds_barrier();
     if (wave == 0) {
-        const T x = lane < nw ? lds[lane] : (T)0;
-        const T xi = wave_inclusive(x);
+        const u32 x = lane < nw ? lds[lane] : 0u;
+        const u32 xi = wave_inclusive_sum(x);
         if (lane < nw) lds[lane] = xi - x;
         if (lane == nw - 1) lds[nw] = xi;
     }
-    __syncthreads();
-    const T res = lds[wave] + inc - v;
-    __syncthreads();
+    lds_barrier();
+    const u32 res = lds[wave] + inc - v;
+    lds_barrier();
     return res;
 }
 
-__device__ __forceinline__ u64 block_sum(u64 v, u64 *lds /* >= waves + 1 words */)
+// sum of v over the workgroup, in every thread (the sum must fit 32 bits)
+__device__ __forceinline__ u32 block_sum(u32 v, u32 *lds /* >= waves words */)
 {
     const u32 nw = blockDim.x / kWave;
-    v = wave_sum_u64(v);
+    v = wave_sum(v);
     if (lane_id() == 0) lds[threadIdx.x / kWave] = v;
-    __syncthreads();
-    const u64 x = lane_id() < nw ? lds[lane_id()] : 0ull;
-    const u64 total = wave_sum_u64(x);
-    __syncthreads();
+    lds_barrier();
+    const u32 total = wave_sum(lane_id() < nw ? lds[lane_id()] : 0u);
+    lds_barrier();
     return total;
 }
 
 // Whole workgroup: walking NBINS = PER * blockDim.x bins (in LDS) from the
-// top, find the bin b with #(bins above b) < need <= #(bins >= b). Stores b
-// and the population above it; stores nothing when all bins together hold
-// fewer than `need`. The caller presets the outputs and synchronises before
-// reading them.
-template <int PER>
-__device__ __forceinline__ void block_pick_desc(const u32 *hist, u32 need, u32 *out_bin,
-                                                u32 *out_before, u32 *lds)
+// top, find for each of NRANKS ranks the bin b with #(bins above b) < need <=
+// #(bins >= b). Stores b and the population above it; stores nothing for a
+// rank that all bins together do not reach. The caller presets the outputs
+// and synchronises before reading them.
+template <int PER, int NRANKS>
+__device__ __forceinline__ void block_pick_desc(const u32 *hist, const u32 (&need)[NRANKS],
+                                                u32 *out_bin /* NRANKS */,
+                                                u32 *out_before /* NRANKS */, u32 *lds)
 {
     const int nbins = PER * (int)blockDim.x;
     const int first = (int)threadIdx.x * PER;      // position in walking order
@@ -295,17 +293,20 @@ __device__ __forceinline__ void block_pick_desc(const u32 *hist, u32 need, u32 *
 #pragma unroll
     for (int q = 0; q < PER; ++q) { c[q] = hist[nbins - 1 - (first + q)]; mine += c[q]; }
     const u32 before = block_exclusive_sum(mine, lds);
-    if (before < need && need <= before + mine) {
-        u32 run = before;
-        bool done = false;
 #pragma unroll
-        for (int q = 0; q < PER; ++q) {
-            if (!done && run + c[q] >= need) {
-                *out_bin = (u32)(nbins - 1 - (first + q));
-                *out_before = run;
-                done = true;
+    for (int k = 0; k < NRANKS; ++k) {
+        if (before < need[k] && need[k] <= before + mine) {
+            u32 run = before;
+            bool done = false;
+#pragma unroll
+            for (int q = 0; q < PER; ++q) {
+                if (!done && run + c[q] >= need[k]) {
+                    out_bin[k] = (u32)(nbins - 1 - (first + q));
+                    out_before[k] = run;
+                    done = true;
+                }
+                run += c[q];
             }
-            run += c[q];
         }
     }
 }
@@ -365,8 +366,7 @@ k_estimate(const u32 *__restrict__ samples, Geom g, EncodeCtl *ctl)
 {
     __shared__ u32 h[4096];
     __shared__ u32 scan_lds[kEstThreads / kWave + 1];
-    __shared__ u64 sum_lds[kEstThreads / kWave + 1];
-    __shared__ u32 bin_s[2], before_s[2];
+    __shared__ u32 bin_s[3], before_s[3];
     const u32 tid = threadIdx.x;
     constexpr u32 kVecs = kSampleLoc / kEstThreads;       // 16-byte sample groups per thread
     const uint4 *s4 = reinterpret_cast<const uint4 *>(samples);
@@ -374,20 +374,16 @@ k_estimate(const u32 *__restrict__ samples, Geom g, EncodeCtl *ctl)
 #pragma unroll
     for (u32 q = 0; q < kVecs; ++q) v[q] = s4[q * kEstThreads + tid];
     for (u32 b = tid; b < 4096u; b += kEstThreads) h[b] = 0u;
-    if (tid < 2u) { bin_s[tid] = 0u; before_s[tid] = 0u; }
-    __syncthreads();
-    u32 nvalid = 0, nzero = 0;
-    auto count1 = [&](u32 m) {
+    if (tid < 3u) { bin_s[tid] = 0u; before_s[tid] = 0u; }
+    u32 nvalid = 0, tmax = 0;
+    auto look = [&](u32 m) {
         if (m == kNoSample) return;
         ++nvalid;
-        if (m == 0u) ++nzero;                     // exact zeros come in long runs: count them aside
-        else atomicAdd(&h[m >> 19], 1u);
+        tmax = m > tmax ? m : tmax;
     };
 #pragma unroll
-    for (u32 q = 0; q < kVecs; ++q) { count1(v[q].x); count1(v[q].y); count1(v[q].z); count1(v[q].w); }
-    nzero = (u32)wave_sum_u64(nzero);
-    if (lane_id() == 0 && nzero) atomicAdd(&h[0], nzero);
-    const u32 n = (u32)block_sum(nvalid, sum_lds);
+    for (u32 q = 0; q < kVecs; ++q) { look(v[q].x); look(v[q].y); look(v[q].z); look(v[q].w); }
+    const u32 n = block_sum(nvalid, scan_lds);            // also orders the clearing of h
 
     const float p = (float)((double)g.r / (double)g.d);
     const float np = (float)n * p;
@@ -396,9 +392,34 @@ k_estimate(const u32 *__restrict__ samples, Geom g, EncodeCtl *ctl)
     const bool lo_all = lo_rank > (float)n;       // too few samples below the top: keep everything
     const u32 s_lo = lo_all ? n : (u32)lo_rank;
     const u32 s_hi = hi_rank < 1.0f ? 1u : (u32)hi_rank;
+
+    // Only the top s_lo samples matter. At most s_lo - 1 threads hold a sample
+    // above the s_lo-th largest one, so the s_lo-th largest of the per-thread
+    // maxima is not above it: buckets below that maximum's bucket need no count.
+    u32 cut_bucket = 0;
+    if (s_lo < kEstThreads) {
+        if (nvalid) atomicAdd(&h[tmax >> 19], 1u);
+        __syncthreads();
+        const u32 want_cut[1] = {s_lo};
+        block_pick_desc<4, 1>(h, want_cut, &bin_s[2], &before_s[2], scan_lds);
+        __syncthreads();
+        cut_bucket = bin_s[2];                     // stays 0 when fewer than s_lo threads hold samples
+        for (u32 b = tid; b < 4096u; b += kEstThreads) h[b] = 0u;
+        __syncthreads();
+    }
+    u32 nzero = 0;
+    auto count = [&](u32 m) {
+        if (m == kNoSample || (m >> 19) < cut_bucket) return;
+        if (m == 0u) ++nzero;                     // exact zeros come in long runs: count them aside
+        else atomicAdd(&h[m >> 19], 1u);
+    };
+#pragma unroll
+    for (u32 q = 0; q < kVecs; ++q) { count(v[q].x); count(v[q].y); count(v[q].z); count(v[q].w); }
+    nzero = wave_sum(nzero);
+    if (lane_id() == 0 && nzero) atomicAdd(&h[0], nzero);
     __syncthreads();
-    block_pick_desc<4>(h, s_lo, &bin_s[0], &before_s[0], scan_lds);
-    block_pick_desc<4>(h, s_hi, &bin_s[1], &before_s[1], scan_lds);
+    const u32 want[2] = {s_lo, s_hi};
+    block_pick_desc<4, 2>(h, want, &bin_s[0], &before_s[0], scan_lds);
     __syncthreads();
     if (tid == 0) {
         const u32 t_lo = lo_all ? 0u : (bin_s[0] << 19);
@@ -617,7 +638,7 @@ struct UnitWalk {
         stride = g.U;
         const u32 s = unit + lane * g.U;
         const u32 cnt = (unit < g.U && lane < kUnitChunks && s < g.W) ? cand.count(s) : 0u;
-        inc = wave_inclusive(cnt);
+        inc = wave_inclusive_sum(cnt);
         excl = inc - cnt;
         total = __shfl(inc, kWave - 1, kWave);
     }
@@ -746,7 +767,9 @@ k_classify(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ seg_
     if (lane < kUnitChunks) per_chunk[wave][lane] = 0u;
     __syncthreads();
 
-    const u64 slot0 = (u64)blockIdx.x * kListCap;
+    // entry p of this workgroup's short lists lives at [p][workgroup]: the
+    // finalize kernel reads entry p of all workgroups with one coalesced load
+    auto slot = [&](u32 p) { return (u64)p * g.G3 + blockIdx.x; };
     walk.for_each([&](bool valid, u32 i, u32 s, u32 j, u32, u32) {
         if (!valid) return;
         u32 idx, bits;
@@ -760,13 +783,13 @@ k_classify(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ seg_
                     sure = true;
                 } else if (key <= g.K_hi) {
                     const u32 p = atomicAdd(&cnt_m, 1u);
-                    if (p < kListCap) { m_key[slot0 + p] = key; m_idx[slot0 + p] = idx; }
+                    if (p < kListCap) { m_key[slot(p)] = key; m_idx[slot(p)] = idx; }
                 }
             }
             if (sure) atomicAdd(&per_chunk[wave][i], 1u);
         } else if (m >= bd_lo) {
             const u32 p = atomicAdd(&cnt_b, 1u);
-            if (p < kListCap) { b_mag[slot0 + p] = m; b_idx[slot0 + p] = idx; }
+            if (p < kListCap) { b_mag[slot(p)] = m; b_idx[slot(p)] = idx; }
         }
     });
     __builtin_amdgcn_wave_barrier();
@@ -779,7 +802,7 @@ k_classify(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ seg_
             win_cnt[s] = mine;
         }
     }
-    mine = (u32)wave_sum_u64(mine);
+    mine = wave_sum(mine);
     if (lane == 0 && mine) atomicAdd(&cnt_sure, mine);
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -799,7 +822,9 @@ k_classify(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ seg_
 // known to be zero in every string. *ok is cleared when fewer than `rank`
 // strings exist. One barrier per byte: the 256-bin histogram rotates through
 // three buffers (the next one is cleared while the current one is filled)
-// and every wavefront repeats the walk over the bins for itself.
+// and every wavefront repeats the walk over the bins for itself. The barriers
+// order LDS only; for_each may read global memory but must not depend on
+// global writes made by other threads since the last full barrier.
 // ---------------------------------------------------------------------------
 struct Pair96 {
     u64 hi;
@@ -832,7 +857,7 @@ __device__ __forceinline__ Pair96 block_select96(ForEach &&for_each, u64 rank, i
     const u32 lane = lane_id();
     *ok = true;
     for (u32 b = threadIdx.x; b < 256u; b += blockDim.x) h[0][b] = 0u;
-    __syncthreads();
+    lds_barrier();
     u32 cur = 0;
     for (; j < 12; ++j) {
         const u32 nxt = cur == 2u ? 0u : cur + 1u;
@@ -840,27 +865,27 @@ __device__ __forceinline__ Pair96 block_select96(ForEach &&for_each, u64 rank, i
         for_each([&](u64 hi, u32 lo) {
             if (pair_matches(hi, lo, phi, plo, j)) atomicAdd(&h[cur][pair_byte(hi, lo, j)], 1u);
         });
-        __syncthreads();
+        lds_barrier();
         // every wavefront: lane l owns bins 4l .. 4l+3
+        // (the strings number fewer than 2^32, so 32-bit counts do)
         u32 c[4];
-        u64 mine = 0;
+        u32 mine = 0;
 #pragma unroll
         for (int q = 0; q < 4; ++q) { c[q] = h[cur][4 * lane + q]; mine += c[q]; }
-        const u64 inc = wave_inclusive(mine);
-        u64 run = inc - mine;
-        const u64 owner = __ballot(run < need && need <= inc);
+        const u32 inc = wave_inclusive_sum(mine);
+        u32 run = inc - mine;
+        const u64 owner = __ballot((u64)run < need && need <= (u64)inc);
         if (owner == 0ull) { *ok = false; return Pair96{0, 0}; }
-        u32 bin = 0, in_bin = 0;
-        u64 before = 0;
+        u32 bin = 0, in_bin = 0, before = 0;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            if (run < need && need <= run + c[q]) { bin = 4 * lane + q; before = run; in_bin = c[q]; }
+            if ((u64)run < need && need <= (u64)run + c[q]) { bin = 4 * lane + q; before = run; in_bin = c[q]; }
             run += c[q];
         }
         const int src = __ffsll((unsigned long long)owner) - 1;
-        bin = __shfl(bin, src, kWave);
-        in_bin = __shfl(in_bin, src, kWave);
-        before = __shfl(before, src, kWave);
+        bin = (u32)__builtin_amdgcn_readlane((int)bin, src);
+        in_bin = (u32)__builtin_amdgcn_readlane((int)in_bin, src);
+        before = (u32)__builtin_amdgcn_readlane((int)before, src);
         need -= before;
         if (j < 8) phi |= (u64)bin << (56 - 8 * j);
         else plo |= bin << (24 - 8 * (j - 8));
@@ -872,28 +897,17 @@ __device__ __forceinline__ Pair96 block_select96(ForEach &&for_each, u64 rank, i
         for_each([&](u64 hi, u32 lo) {
             if (pair_matches(hi, lo, phi, plo, j)) { scratch[0] = hi; scratch[1] = lo; }
         });
-        __syncthreads();
+        lds_barrier();
         phi = scratch[0];
         plo = (u32)scratch[1];
     }
-    __syncthreads();
+    lds_barrier();
     return Pair96{phi, plo};
 }
 
 __device__ __forceinline__ bool pair_le(u64 hi, u32 lo, const Pair96 &p)
 {
     return hi < p.hi || (hi == p.hi && lo <= p.lo);
-}
-
-// position p of a concatenation of regions -> region index (off[] ascending, off[n] = total)
-__device__ __forceinline__ u32 region_of(const u32 *off, u32 n, u32 p)
-{
-    u32 lo = 0, hi = n;           // answer in [lo, hi): largest b with off[b] <= p
-    while (hi - lo > 1) {
-        const u32 mid = (lo + hi) >> 1;
-        if (off[mid] <= p) lo = mid; else hi = mid;
-    }
-    return lo;
 }
 
 // ---------------------------------------------------------------------------
@@ -910,10 +924,8 @@ k_finalize(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__ a,
            u32 *dm_idx, u64 *db_key, u32 *db_idx, u32 *__restrict__ chunk_base)
 {
     static_assert(kMaxWalkBlocks <= (u32)kFinThreads, "one thread per classify workgroup");
-    __shared__ u32 off_m[kFinThreads + 1], off_b[kFinThreads + 1];
     __shared__ u32 h[3][256];
     __shared__ u32 scan32[kSlabs * kFinWaves + 1];
-    __shared__ u64 scan64[kFinWaves + 1];
     __shared__ u64 scratch[2];
     __shared__ u64 st_b_key[kStageB];
     __shared__ u32 st_b_idx[kStageB];
@@ -950,10 +962,7 @@ k_finalize(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__ a,
     const u32 n_m0 = scan32[kFinWaves];
     const u32 eb = block_exclusive_sum(vb, scan32);
     const u32 n_bd = scan32[kFinWaves];
-    off_m[tid] = em;
-    off_b[tid] = eb;
-    if (tid == kFinThreads - 1) { off_m[kFinThreads] = em + vm; off_b[kFinThreads] = eb + vb; }
-    const u64 sure_walk = block_sum(vs, scan64);
+    const u64 sure_walk = block_sum(vs, scan32);
 
     const u64 need2 = g.r - c_def;
     u32 err = 0, path = 0;
@@ -962,26 +971,32 @@ k_finalize(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__ a,
     u64 K_star = ~0ull, count_greater = 0;
 
     if (!dense && !overflow && c_def < g.r && need2 <= n_bd) {
-        // ---- gather both short lists (one round of loads) ----------------
+        // ---- both short lists, each thread copying the entries of its own
+        //      classify workgroup (a handful), all loads in one round --------
         const bool b_lds = n_bd <= kStageB;
         u64 *bk = b_lds ? st_b_key : db_key;
         u32 *bi = b_lds ? st_b_idx : db_idx;
         const bool m_lds = n_m0 + n_bd <= kStageM;
         u64 *mk = m_lds ? st_m_key : dm_key;
         u32 *mi = m_lds ? st_m_idx : dm_idx;
+        // Entry j of classify workgroup t lives at [j][t]. First every thread
+        // notes where the entries of its workgroup are (no memory latency in
+        // that loop), then the entries are fetched position by position, all
+        // loads of a thread in flight together.
+        for (u32 j = 0; j < vb; ++j) bi[eb + j] = j * g.G3 + tid;
+        for (u32 j = 0; j < vm; ++j) mi[em + j] = j * g.G3 + tid;
+        if (b_lds && m_lds) lds_barrier(); else __syncthreads();
         for (u32 p = tid; p < n_bd; p += kFinThreads) {
-            const u32 b = region_of(off_b, g.G3, p);
-            const u64 at = (u64)b * kListCap + (p - off_b[b]);
+            const u32 at = bi[p];
             bk[p] = (u64)(bd_hi - b_mag[at]);
             bi[p] = b_idx[at];
         }
         for (u32 p = tid; p < n_m0; p += kFinThreads) {
-            const u32 b = region_of(off_m, g.G3, p);
-            const u64 at = (u64)b * kListCap + (p - off_m[b]);
+            const u32 at = mi[p];
             mk[p] = (m_key[at] - g.K_lo) << g.k_nlz;
             mi[p] = m_idx[at];
         }
-        __syncthreads();
+        if (b_lds && m_lds) lds_barrier(); else __syncthreads();
         // ---- exact threshold inside the deciding bin --------------------
         auto each_b = [&](auto &&f) {
             for (u32 p = tid; p < n_bd; p += kFinThreads) f(bk[p], bi[p]);
@@ -991,7 +1006,8 @@ k_finalize(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__ a,
             have_t = true;
             T = bd_hi - (u32)tb.hi;
             I_star = tb.lo;
-            // ---- members of the deciding bin join the key lists ----------
+            // ---- members of the deciding bin join the key lists; the atomics
+            //      on the chunk counters are left in flight --------------------
             u32 my_gt = 0;
             for (u32 p = tid; p < n_bd; p += kFinThreads) {
                 const u64 hi = bk[p];
@@ -1012,7 +1028,7 @@ k_finalize(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__ a,
                 if (sure) { atomicAdd(&win_cnt[idx / g.C], 1u); atomicAdd(&sure_extra, 1u); }
             }
             if (my_gt) atomicAdd(&gt_extra, (unsigned long long)my_gt);
-            __syncthreads();
+            if (m_lds) lds_barrier(); else __syncthreads();
             count_greater = c_def + gt_extra;
             n_mm = n_m0 + extra_m;
             const u64 c_klo = sure_walk + sure_extra;
@@ -1044,9 +1060,9 @@ k_finalize(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__ a,
         if (!ok) err |= kErrSelect;
         T = 0x7FFFFFFFu - (u32)tb.hi;
         I_star = tb.lo;
-        u64 my_gt = 0;
+        u32 my_gt = 0;
         each_s([&](u32, u32 bits, u32) { if (mag_of(bits) > T) ++my_gt; });
-        count_greater = block_sum(my_gt, scan64);
+        count_greater = block_sum(my_gt, scan32);
     }
     auto is_member = [&](u32 idx, u32 bits) {
         const u32 m = mag_of(bits);
@@ -1098,7 +1114,7 @@ k_finalize(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__ a,
         s4[q] = c[q][0] + c[q][1] + c[q][2] + c[q][3];
     }
 #pragma unroll
-    for (u32 q = 0; q < kSlabs; ++q) inc[q] = wave_inclusive(s4[q]);
+    for (u32 q = 0; q < kSlabs; ++q) inc[q] = wave_inclusive_sum(s4[q]);
     if (lane == kWave - 1) {
 #pragma unroll
         for (u32 q = 0; q < kSlabs; ++q) scan32[q * kFinWaves + wave] = inc[q];
@@ -1109,7 +1125,7 @@ k_finalize(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__ a,
         static_assert(n == 2 * kWave, "two partial sums per lane");
         if (wave == 0) {
             const u32 a0 = scan32[2 * lane], a1 = scan32[2 * lane + 1];
-            const u32 xi = wave_inclusive(a0 + a1);
+            const u32 xi = wave_inclusive_sum(a0 + a1);
             scan32[2 * lane] = xi - (a0 + a1);
             scan32[2 * lane + 1] = xi - a1;
             if (lane == kWave - 1) scan32[n] = xi;
@@ -1244,32 +1260,35 @@ struct StageScope {
     }
 };
 
-// Workgroups of the streaming kernel the current device holds at once (a
-// property of the device and the compiled kernel, looked up once per device).
+// Workgroups of the streaming kernel: as many as the device holds at once, at
+// most three per compute unit (all start together and share the chunks
+// evenly, so none waits for a slot). A property of the device and of the
+// compiled kernel, looked up at the first call on the device.
 constexpr int kMaxDevices = 64;
-std::mutex g_resident_mutex;
-unsigned g_resident[kMaxDevices][2];
+constexpr int kFusedBlocksPerCU = 3;
+std::mutex g_device_mutex;
+unsigned g_fused_grid[kMaxDevices];
 
-int resident_fused_blocks(bool vec4, unsigned *out)
+int fused_grid_limit(unsigned *out)
 {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return RTOPK_EHIP;
-    std::lock_guard<std::mutex> lock(g_resident_mutex);
-    unsigned &slot = g_resident[dev][vec4 ? 1 : 0];
-    if (slot == 0) {
-        int per_cu = 0, cus = 0;
-        const hipError_t e1 =
-            vec4 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_fused<true>,
-                                                                (int)kFusedThreads, 0)
-                 : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_fused<false>,
-                                                                (int)kFusedThreads, 0);
-        const hipError_t e2 =
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e1 != hipSuccess || e2 != hipSuccess || per_cu < 1 || cus < 1) return RTOPK_EHIP;
-        slot = (unsigned)per_cu * (unsigned)cus;
-        if (slot > kMaxFusedBlocks) slot = kMaxFusedBlocks;
+    std::lock_guard<std::mutex> lock(g_device_mutex);
+    if (g_fused_grid[dev] == 0) {
+        int cus = 0, fit_t = 0, fit_f = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&fit_t, k_fused<true>,
+                                                         (int)kFusedThreads, 0) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&fit_f, k_fused<false>,
+                                                         (int)kFusedThreads, 0) != hipSuccess)
+            return RTOPK_EHIP;
+        int per_cu = fit_t < fit_f ? fit_t : fit_f;
+        per_cu = per_cu < kFusedBlocksPerCU ? per_cu : kFusedBlocksPerCU;
+        if (cus < 1 || per_cu < 1) return RTOPK_EHIP;
+        const unsigned grid = (unsigned)cus * (unsigned)per_cu;
+        g_fused_grid[dev] = grid > kMaxFusedBlocks ? kMaxFusedBlocks : grid;
     }
-    *out = slot;
+    *out = g_fused_grid[dev];
     return RTOPK_OK;
 }
 }  // namespace
@@ -1322,8 +1341,8 @@ extern "C" int rtopk_encode(const float *grad, float *residual, uint64_t d, uint
 
     const PhiloxSeed ps{(u32)seed, (u32)(seed >> 32), (u32)step, (u32)(step >> 32)};
     const bool vec4 = (((uintptr_t)grad | (uintptr_t)residual) & 15u) == 0;
-    unsigned resident = 0;
-    const int rc2 = resident_fused_blocks(vec4, &resident);
+    unsigned grid_limit = 0;
+    const int rc2 = fused_grid_limit(&grid_limit);
     if (rc2) return rc2;
 
     const TraceRequest trace = g_trace;
@@ -1339,16 +1358,19 @@ extern "C" int rtopk_encode(const float *grad, float *residual, uint64_t d, uint
         RTOPK_LAUNCH_CHECK();
     }
     {
-        StageScope sc(trace, RTOPK_STAGE_FUSED, stream);
         unsigned grid = (g.W + kFusedWaves - 1) / kFusedWaves;
-        if (grid > resident) grid = resident;
-        if (vec4)
-            k_fused<true><<<grid, kFusedThreads, 0, stream>>>(grad, residual, g, ctl, partials,
-                                                              seg_count, s_idx, s_val);
-        else
-            k_fused<false><<<grid, kFusedThreads, 0, stream>>>(grad, residual, g, ctl, partials,
-                                                               seg_count, s_idx, s_val);
-        RTOPK_LAUNCH_CHECK();
+        if (grid > grid_limit) grid = grid_limit;
+        {
+            StageScope sc(trace, RTOPK_STAGE_FUSED, stream);
+            if (vec4)
+                k_fused<true><<<grid, kFusedThreads, 0, stream>>>(grad, residual, g, ctl, partials,
+                                                                  seg_count, s_idx, s_val);
+            else
+                k_fused<false><<<grid, kFusedThreads, 0, stream>>>(grad, residual, g, ctl,
+                                                                   partials, seg_count, s_idx,
+                                                                   s_val);
+            RTOPK_LAUNCH_CHECK();
+        }
         const dim3 rgrid((g.nfine + kCoarseBins + kReduceThreads - 1) / kReduceThreads, kHistRows);
         k_reduce<<<rgrid, kReduceThreads, 0, stream>>>(partials, grid, ctl, hist);
         RTOPK_LAUNCH_CHECK();
