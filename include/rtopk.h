@@ -133,6 +133,22 @@ int rtopk_encode_stats(const void *workspace, void *stream, rtopk_encode_stats_t
 #define RTOPK_STAGE_ALL 100
 int rtopk_trace_next_encode(int stage, void *ev_begin, void *ev_end);
 
+/*
+ * Test hook: the NEXT rtopk_encode issued from the calling host thread behaves
+ * as if one of its two statistical shortcuts had failed, so that the exact
+ * fallbacks behind them can be exercised on ordinary inputs; the request is
+ * then forgotten. The results must not change, only rtopk_encode_stats.path.
+ *   RTOPK_FORCE_ESTIMATE_MISS    the sampled threshold estimate keeps no
+ *                                candidates: the vector itself is walked
+ *   RTOPK_FORCE_KEY_WINDOW_MISS  the a-priori window around the k-th smallest
+ *                                sampling key is empty: the key cut comes from
+ *                                a selection over all candidates
+ * Passing 0 cancels a pending request.
+ */
+#define RTOPK_FORCE_ESTIMATE_MISS 1u
+#define RTOPK_FORCE_KEY_WINDOW_MISS 2u
+int rtopk_force_next_encode(unsigned flags);
+
 const char *rtopk_strerror(int code);
 
 /* Library version: major * 10000 + minor * 100 + patch. */

@@ -8,7 +8,9 @@ of :mod:`paper_2005_10761_amd.binding` symbols fails loudly at first use.
 """
 from .binding import (RtopkError, aggregate, aggregate_workspace_bytes, encode,
                       encode_stats, encode_workspace_bytes, library_path, load_library,
-                      strerror, trace_next_encode, version, STAGES)
+                      strerror, trace_next_encode, version, STAGES, force_next_encode,
+                      FORCE_ESTIMATE_MISS, FORCE_KEY_WINDOW_MISS)
 
 __all__ = ["RtopkError", "aggregate", "aggregate_workspace_bytes", "encode", "encode_stats",
-           "encode_workspace_bytes", "library_path", "load_library", "strerror", "trace_next_encode", "version", "STAGES"]
+           "encode_workspace_bytes", "library_path", "load_library", "strerror", "trace_next_encode", "version", "STAGES",
+           "force_next_encode", "FORCE_ESTIMATE_MISS", "FORCE_KEY_WINDOW_MISS"]

@@ -14,8 +14,8 @@ _LIB_PATH = os.path.join(_HERE, "librtopk.so")
 _LIB: Optional[ctypes.CDLL] = None
 
 EXPORTS = ("rtopk_encode_workspace_bytes", "rtopk_aggregate_workspace_bytes", "rtopk_encode",
-           "rtopk_aggregate", "rtopk_encode_stats", "rtopk_trace_next_encode", "rtopk_strerror",
-           "rtopk_version")
+           "rtopk_aggregate", "rtopk_encode_stats", "rtopk_trace_next_encode",
+           "rtopk_force_next_encode", "rtopk_strerror", "rtopk_version")
 
 
 class RtopkError(RuntimeError):
@@ -58,6 +58,8 @@ def load_library() -> ctypes.CDLL:
     L.rtopk_encode_stats.restype = ctypes.c_int
     L.rtopk_trace_next_encode.argtypes = [ctypes.c_int, vp, vp]
     L.rtopk_trace_next_encode.restype = ctypes.c_int
+    L.rtopk_force_next_encode.argtypes = [ctypes.c_uint]
+    L.rtopk_force_next_encode.restype = ctypes.c_int
     L.rtopk_strerror.argtypes = [ctypes.c_int]
     L.rtopk_strerror.restype = ctypes.c_char_p
     L.rtopk_version.argtypes = []
@@ -152,6 +154,18 @@ def trace_next_encode(stage: int, ev_begin: int, ev_end: int) -> None:
     rc = load_library().rtopk_trace_next_encode(stage, ev_begin, ev_end)
     if rc:
         raise RtopkError(rc, "rtopk_trace_next_encode")
+
+
+FORCE_ESTIMATE_MISS = 1
+FORCE_KEY_WINDOW_MISS = 2
+
+
+def force_next_encode(flags: int) -> None:
+    """rtopk_force_next_encode: make the next encode from this thread take an
+    exact fallback path (test hook)."""
+    rc = load_library().rtopk_force_next_encode(flags)
+    if rc:
+        raise RtopkError(rc, "rtopk_force_next_encode")
 
 
 def encode_stats(workspace: torch.Tensor, stream=None) -> dict:

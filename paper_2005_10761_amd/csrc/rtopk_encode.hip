@@ -147,9 +147,9 @@ struct Geom {
     u32 G3;             // classify / emit workgroups
     u32 L;              // sampled locations
     u32 nfine;          // linear histogram bins
+    u32 force_dense;    // diagnostics: make the estimate keep nothing, as if the sample had misled it
     u32 take_all;       // k == r: every member is sent, keys are never looked at
     u32 k_nlz;          // leading zeros of K_hi - K_lo
-    u32 pad;
     u64 K_lo, K_hi;     // key window
 };
 
@@ -422,8 +422,9 @@ k_estimate(const u32 *__restrict__ samples, Geom g, EncodeCtl *ctl)
     block_pick_desc<4, 2>(h, want, &bin_s[0], &before_s[0], scan_lds);
     __syncthreads();
     if (tid == 0) {
-        const u32 t_lo = lo_all ? 0u : (bin_s[0] << 19);
+        u32 t_lo = lo_all ? 0u : (bin_s[0] << 19);
         u32 t_hi = (bin_s[1] << 19) | 0x7FFFFu;
+        if (g.force_dense) t_lo = 0x7FFFFFFFu;
         if (t_hi < t_lo) t_hi = t_lo;
         u32 shift = 0;
         while (((t_hi - t_lo) >> shift) >= g.nfine) ++shift;
@@ -1243,6 +1244,7 @@ struct TraceRequest {
     hipEvent_t begin = nullptr, end = nullptr;
 };
 thread_local TraceRequest g_trace;
+thread_local unsigned g_force = 0;
 
 // records the requested pair of events around one stage of the pipeline
 struct StageScope {
@@ -1293,6 +1295,14 @@ int fused_grid_limit(unsigned *out)
 }
 }  // namespace
 
+extern "C" int rtopk_force_next_encode(unsigned flags)
+{
+    if (flags & ~(unsigned)(RTOPK_FORCE_ESTIMATE_MISS | RTOPK_FORCE_KEY_WINDOW_MISS))
+        return RTOPK_EINVAL;
+    g_force = flags;
+    return RTOPK_OK;
+}
+
 extern "C" int rtopk_trace_next_encode(int stage, void *ev_begin, void *ev_end)
 {
     if (stage != 0 && (!ev_begin || !ev_end)) return RTOPK_EINVAL;
@@ -1319,10 +1329,17 @@ extern "C" int rtopk_encode(const float *grad, float *residual, uint64_t d, uint
         const uintptr_t g0 = (uintptr_t)grad, m0 = (uintptr_t)residual;
         if (g0 < m0 + d * 4 && m0 < g0 + d * 4) return RTOPK_EINVAL;
     }
-    const Geom g = make_geom(d, r, k);
+    Geom g = make_geom(d, r, k);
     const EncodeLayout L = make_layout(g);
     if (!workspace || ((uintptr_t)workspace & 255u) || workspace_bytes < L.total)
         return RTOPK_EWORKSPACE;
+    const unsigned force = g_force;
+    g_force = 0;
+    if (force & RTOPK_FORCE_ESTIMATE_MISS) g.force_dense = 1u;
+    if ((force & RTOPK_FORCE_KEY_WINDOW_MISS) && !g.take_all) {
+        g.K_lo = g.K_hi = 0;       // a window that holds no key: the exact selection must run
+        g.k_nlz = 63u;
+    }
 
     hipStream_t stream = (hipStream_t)stream_v;
     char *ws = (char *)workspace;

@@ -32,8 +32,11 @@ class GpuWorker:
         # poison the workspace: the library must not depend on its contents
         self.ws.fill_(0xA5)
 
-    def encode(self, g: np.ndarray, seed: int, step: int, check_stats: bool = True):
+    def encode(self, g: np.ndarray, seed: int, step: int, check_stats: bool = True,
+               force: int = 0):
         self.grad.copy_(torch.from_numpy(np.ascontiguousarray(g, np.float32)))
+        if force:
+            rt.force_next_encode(force)
         rt.encode(self.grad, self.residual, self.r, self.k, seed, step, self.idx, self.val,
                   self.ws)
         st = rt.encode_stats(self.ws)
@@ -45,9 +48,9 @@ class GpuWorker:
                 self.residual.cpu().numpy().copy())
 
 
-def gpu_encode_once(g, m, r, k, seed, step, offset=0):
+def gpu_encode_once(g, m, r, k, seed, step, offset=0, force=0):
     w = GpuWorker(len(g), r, k, residual=m, offset=offset)
-    out = w.encode(g, seed, step)
+    out = w.encode(g, seed, step, force=force)
     return out + (w.stats,)
 
 

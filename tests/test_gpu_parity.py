@@ -141,6 +141,45 @@ def test_seed_and_step_use_all_64_bits():
 
 
 # --------------------------------------------------------------------------
+# the exact fallbacks behind the two statistical shortcuts
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("d,offset", [(5_000, 0), (70_001, 1), (300_000, 0)])
+def test_fallback_paths_give_the_same_message(d, offset):
+    """Ordinary input, but the sampled threshold estimate and/or the key window
+    are made to miss: the message and the residual must not change, only the
+    path the library reports."""
+    import paper_2005_10761_amd as rt
+    u = _u()
+    wl = Workload(2, d=d)
+    g = wl.gradient(0, 0)
+    m = (np.random.default_rng(d).standard_normal(d) * 1e-3).astype(np.float32)
+    want = oracle.encode(g, m, wl.r, wl.k, 99, 7)
+    plain = u.gpu_encode_once(g, m, wl.r, wl.k, 99, 7, offset=offset)
+    u.assert_encode_equal(plain, want, "no fallback")
+    assert plain[3]["path"] == 0
+    for force, bits in ((rt.FORCE_ESTIMATE_MISS, 3), (rt.FORCE_KEY_WINDOW_MISS, 1),
+                        (rt.FORCE_ESTIMATE_MISS | rt.FORCE_KEY_WINDOW_MISS, 3)):
+        got = u.gpu_encode_once(g, m, wl.r, wl.k, 99, 7, offset=offset, force=force)
+        u.assert_encode_equal(got, want, f"force={force}")
+        assert got[3]["path"] == bits, got[3]
+    # the request is consumed by one call
+    again = u.gpu_encode_once(g, m, wl.r, wl.k, 99, 7, offset=offset)
+    assert again[3]["path"] == 0
+
+
+def test_fallback_paths_with_ties_and_special_cases():
+    import paper_2005_10761_amd as rt
+    rng = np.random.default_rng(12)
+    d = 40_000
+    g = rng.choice([0.0, 1.0, -1.0, 2.0, 0.5], d).astype(np.float32)
+    m = np.zeros(d, np.float32)
+    for r, k in ((500, 50), (d, 1000), (3000, 3000), (1, 1)):
+        for force in (rt.FORCE_ESTIMATE_MISS, rt.FORCE_KEY_WINDOW_MISS):
+            got = _u().gpu_encode_once(g, m, r, k, 5, 5, force=force)
+            _u().assert_encode_equal(got, oracle.encode(g, m, r, k, 5, 5), f"r={r} k={k} f={force}")
+
+
+# --------------------------------------------------------------------------
 # multi-step error feedback, several workers, aggregate
 # --------------------------------------------------------------------------
 def _run_config(cfg, d, n_workers, steps, r=None, k=None, check_aggregate=True):
