@@ -17,7 +17,7 @@ workspace; the kernel durations measured then include whatever ran beside them.
 Prints ONE JSON line:
   value      = gradient bytes consumed per second over whole steps
                (n * 4d bytes per step / seconds per step), GB/s
-  roofline   = the dominant kernel (fused residual add + first histogram):
+  roofline   = the dominant kernel (fused residual add + candidate append):
                algorithmic bytes per launch (12 d) over its mean duration,
                measured with HIP events on the launch stream, against the
                8 TB/s HBM peak
@@ -40,10 +40,11 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 METRIC = "rTop-k encode gradient GB/s and % of HBM peak at d=25.6M; aggregate GB/s"
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs
-# (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); filled in
-# from the summaries under profiles/ when they exist for this kernel version.
-DOMINANT_KERNEL_TRAFFIC_BYTES = None
+# HBM bytes per launch of the dominant kernel (k_fused at d = 25,557,032) from
+# two rocprofv3 --pmc runs, FETCH_SIZE then WRITE_SIZE, each scaled by a device
+# copy of known size in the same run; the summary and the commands are in
+# profiles/k_fused_cfg3_hbm_traffic.txt. Only valid for the default workload.
+DOMINANT_KERNEL_TRAFFIC_BYTES = 311_444_277
 
 
 class HipEvents:
@@ -119,6 +120,10 @@ def main() -> int:
     ap.add_argument("--streams", type=int, default=1,
                     help="HIP streams the simulated workers are dealt to (each with its own "
                          "workspace); 1 = strictly one kernel at a time")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
+                    help="after the timed region, also run N plain device copies of d floats "
+                         "(4d bytes read + 4d bytes written each): a kernel of known HBM "
+                         "traffic to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters with")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=2, help="oracle encodes to time")
     args = ap.parse_args()
@@ -204,6 +209,12 @@ def main() -> int:
     fused_ms = [ev.elapsed_ms(a, b) for row in fused_pairs for (a, b) in row]
     ev.close()
 
+    if args.copy_calibration > 0:
+        src = grads[0][0]
+        for _ in range(args.copy_calibration):
+            out.copy_(src)
+        torch.cuda.synchronize()
+
     for s in range(S):
         stats = rt.encode_stats(ws[s])
         if stats["error_flags"] != 0:
@@ -247,7 +258,7 @@ def main() -> int:
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "traffic": DOMINANT_KERNEL_TRAFFIC_BYTES,
+            "traffic": DOMINANT_KERNEL_TRAFFIC_BYTES if args.config == 3 else None,
             "bytes_per_launch": 12 * d,
             "avg_launch_ms": round(fused_ms_avg, 5),
             "launches": len(fused_ms),
