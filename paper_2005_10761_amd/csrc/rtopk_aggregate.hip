@@ -1,82 +1,181 @@
 // rtopk_aggregate: the master step of Algorithm 1, ghat = (1/n) sum_i ghat_i,
 // from n sorted sparse messages to one dense vector, in a single kernel.
 //
-// Each workgroup owns one tile of 4096 consecutive output coordinates. For
-// every worker it finds, by binary search in that worker's ascending index
-// list, the slice of the message that falls into the tile, and adds the
-// slice into an LDS copy of the tile, one worker after the other (so the
-// order of the binary32 additions is fixed: +0, then worker 0, 1, ...). The
-// tile is then divided by n and written with 16-byte stores. HBM traffic:
-// 4d bytes written + 8nk bytes read; no global atomics, no sort.
+// The output is cut into tiles of 2048 consecutive coordinates and every
+// WAVEFRONT owns a run of consecutive tiles and an LDS copy of the tile it is
+// working on; wavefronts never synchronise with each other. Lane w remembers
+// how far the wavefront has come in worker w's ascending index list: where
+// the wavefront's first tile starts in it is found once, by a search in which
+// the 64 lanes probe several positions per worker at a time. For every tile
+// and worker the wavefront then reads the next 64 (index, value) pairs of the
+// message with one coalesced load (eight workers' loads in flight together),
+// adds the pairs that fall below the tile's end into the LDS tile and moves
+// the worker's position on by their number; a slice that fills all 64 lanes
+// simply continues with the next 64. No search is needed from tile to tile.
+// Workers are taken in order 0, 1, ... and a wavefront's LDS accesses execute
+// in program order, so the order of the binary32 additions is fixed: +0, then
+// worker 0, 1, ... The tile is finally divided by n and written with 16-byte
+// stores. HBM traffic: 4d bytes written + 8nk bytes read; no atomics, no
+// sort, no workspace.
 #include "rtopk_common.h"
 #include "../../include/rtopk.h"
 
 namespace rtopk {
 
 constexpr int kAggThreads = 256;
-constexpr int kAggTile = 4096;
-constexpr int kAggWorkerChunk = 64;
+constexpr int kAggWaves = kAggThreads / kWave;
+constexpr int kAggTile = 2048;
+constexpr int kAggAhead = 8;              // workers whose next pairs are fetched together
+constexpr unsigned kAggMaxWaves = 4096;
 
-__device__ __forceinline__ u64 lower_bound_u32(const u32 *__restrict__ a, u64 n, u64 x)
+__device__ __forceinline__ u32 popc_mask(u64 m) { return (u32)__popcll((unsigned long long)m); }
+
+__device__ __forceinline__ u64 read_lane_u64(u64 v, int lane)
 {
-    u64 lo = 0, hi = n;
-    while (lo < hi) {
-        const u64 mid = (lo + hi) >> 1;
-        if ((u64)a[mid] < x) lo = mid + 1; else hi = mid;
+    const u32 lo = (u32)__builtin_amdgcn_readlane((int)(u32)v, lane);
+    const u32 hi = (u32)__builtin_amdgcn_readlane((int)(u32)(v >> 32), lane);
+    return ((u64)hi << 32) | lo;
+}
+
+// For each of nw <= 64 workers (worker w0 + w <-> the group of P lanes
+// starting at lane w * P, P = the largest power of two with nw * P <= 64): the
+// first position in the worker's ascending index list whose entry is >= x.
+// Every step the P lanes of a group probe P evenly spaced positions of the
+// remaining range, which shrinks (P + 1)-fold. Returns the result of worker
+// `lane` in lane `lane` (lanes >= nw: unspecified).
+__device__ __forceinline__ u64 wave_lower_bounds(const u32 *__restrict__ idx, u32 w0, u32 nw, u64 k,
+                                                 u64 x)
+{
+    const u32 lane = lane_id();
+    u32 P = 1;
+    while (2 * P * nw <= (u32)kWave) P *= 2;
+    const u32 w = lane / P, p = lane % P;
+    const bool live = w < nw;
+    const u32 *wi = idx + (u64)(w0 + (live ? w : 0)) * k;
+    u64 lo = 0, hi = live ? k : 0;                  // the answer lies in [lo, hi]
+    const float inv = 1.0f / (float)(P + 1);
+    while (__any(hi > lo)) {
+        // probe positions lo <= pos_0 <= pos_1 <= ... < hi, roughly evenly spaced (any
+        // non-decreasing choice inside the range is valid; this one needs no division)
+        const float len = (float)(hi - lo);
+        auto probe_at = [&](u32 q) {
+            const u64 t = lo + (u64)(len * ((float)(q + 1) * inv));
+            return t < hi ? t : hi - 1;
+        };
+        const bool below = hi > lo && (u64)wi[probe_at(p)] < x;
+        const u64 mask = __ballot(below);
+        // sorted list: the group's probes below x form a prefix
+        const u32 m = __popcll((mask >> (w * P)) & (P == 64 ? ~0ull : ((1ull << P) - 1ull)));
+        if (hi > lo) {
+            const u64 new_lo = m > 0 ? probe_at(m - 1) + 1 : lo;
+            const u64 new_hi = m < P ? probe_at(m) : hi;
+            lo = new_lo;
+            hi = new_hi;
+        }
     }
-    return lo;
+    // hand the result of worker w (held by all lanes of group w) to lane w
+    const u32 lo_lo = __shfl((u32)lo, (int)((lane < nw ? lane : 0) * P), kWave);
+    const u32 lo_hi = __shfl((u32)(lo >> 32), (int)((lane < nw ? lane : 0) * P), kWave);
+    return ((u64)lo_hi << 32) | lo_lo;
 }
 
 __global__ void __launch_bounds__(kAggThreads)
 k_aggregate(const u32 *__restrict__ idx, const float *__restrict__ val, u32 n, u64 k, u64 d,
-            float *__restrict__ out)
+            u64 tiles, u32 tiles_per_wave, float *__restrict__ out)
 {
-    __shared__ float tile[kAggTile];
-    __shared__ u64 lo_s[kAggWorkerChunk], hi_s[kAggWorkerChunk];
-    const u64 tile_base = (u64)blockIdx.x * kAggTile;
-    const u64 tile_end = tile_base + kAggTile < d ? tile_base + kAggTile : d;
-    for (int t = threadIdx.x; t < kAggTile; t += kAggThreads) tile[t] = 0.0f;
-
-    for (u32 w0 = 0; w0 < n; w0 += kAggWorkerChunk) {
-        const u32 nw = n - w0 < (u32)kAggWorkerChunk ? n - w0 : (u32)kAggWorkerChunk;
-        __syncthreads();
-        if (threadIdx.x < 2 * nw) {
-            const u32 w = threadIdx.x >> 1;
-            const u32 *wi = idx + (u64)(w0 + w) * k;
-            if (threadIdx.x & 1) hi_s[w] = lower_bound_u32(wi, k, tile_end);
-            else lo_s[w] = lower_bound_u32(wi, k, tile_base);
-        }
-        __syncthreads();
-        for (u32 w = 0; w < nw; ++w) {
-            const u64 b = lo_s[w], e = hi_s[w];
-            const u32 *wi = idx + (u64)(w0 + w) * k;
-            const float *wv = val + (u64)(w0 + w) * k;
-            for (u64 j = b + threadIdx.x; j < e; j += kAggThreads) {
-                const u32 i = wi[j];
-                // a repeated index is folded in by the first entry of its run
-                if (j > b && wi[j - 1] == i) continue;
-                float s = tile[i - tile_base];
-                u64 jj = j;
-                do { s += wv[jj]; ++jj; } while (jj < e && wi[jj] == i);
-                tile[i - tile_base] = s;
-            }
-            __syncthreads();
-        }
-    }
-    __syncthreads();
+    __shared__ float tile_s[kAggWaves][kAggTile];
+    const u32 lane = lane_id(), wave = threadIdx.x / kWave;
+    float *tile = tile_s[wave];
+    const u64 gw = (u64)blockIdx.x * kAggWaves + wave;
+    const u64 first_tile = gw * tiles_per_wave;
+    const u64 last_tile = first_tile + tiles_per_wave < tiles ? first_tile + tiles_per_wave : tiles;
+    if (first_tile >= last_tile) return;
+    // one correctly rounded division per output; for n a power of two the
+    // product with 1/n is the same number
     const float fn = (float)n;
-    const bool vec_ok = ((uintptr_t)out & 15u) == 0 && tile_base + kAggTile <= d;
-    if (vec_ok) {
-        float4 *o4 = reinterpret_cast<float4 *>(out + tile_base);
-        for (int t = threadIdx.x; t < kAggTile / 4; t += kAggThreads) {
-            float4 v;
-            v.x = tile[4 * t + 0] / fn; v.y = tile[4 * t + 1] / fn;
-            v.z = tile[4 * t + 2] / fn; v.w = tile[4 * t + 3] / fn;
-            o4[t] = v;
+    const bool n_pow2 = (n & (n - 1u)) == 0u;
+    const float rn = 1.0f / fn;
+    const bool out_vec = ((uintptr_t)out & 15u) == 0;
+    const u32 groups = (n + kWave - 1) / kWave;    // workers are taken 64 at a time
+    // lane w: where the current tile starts in the message of worker w (first group only;
+    // with more than 64 workers the position is searched again for every tile)
+    u64 pos0 = 0;
+    if (groups == 1) pos0 = wave_lower_bounds(idx, 0, n, k, first_tile * kAggTile);
+
+    for (u64 t = first_tile; t < last_tile; ++t) {
+        const u64 tile_base = t * kAggTile;
+        const u64 tile_end = tile_base + kAggTile < d ? tile_base + kAggTile : d;
+        for (int i = lane; i < kAggTile / 4; i += kWave)
+            reinterpret_cast<float4 *>(tile)[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+
+        for (u32 w0 = 0; w0 < n; w0 += kWave) {
+            const u32 nw = n - w0 < (u32)kWave ? n - w0 : (u32)kWave;
+            u64 lo = groups == 1 ? pos0 : wave_lower_bounds(idx, w0, nw, k, tile_base);
+            // ---- worker after worker: the next 64 pairs of its message in one
+            //      coalesced load, those below the tile's end added into the tile;
+            //      the loads of kAggAhead workers are in flight together --------
+            for (u32 g0 = 0; g0 < nw; g0 += kAggAhead) {
+                u64 from[kAggAhead];
+                u32 ri[kAggAhead];
+                float rv[kAggAhead];
+#pragma unroll
+                for (int q = 0; q < kAggAhead; ++q) {
+                    const u32 w = g0 + q < nw ? g0 + q : nw - 1;
+                    from[q] = read_lane_u64(lo, (int)w);
+                    const u64 j = from[q] + lane;
+                    const bool in = g0 + q < nw && j < k;
+                    ri[q] = in ? idx[(u64)(w0 + w) * k + j] : 0xFFFFFFFFu;
+                    rv[q] = in ? val[(u64)(w0 + w) * k + j] : 0.0f;
+                }
+#pragma unroll
+                for (int q = 0; q < kAggAhead; ++q) {
+                    if (g0 + q >= nw) break;
+                    const u32 w = g0 + q;
+                    const u32 *si = idx + (u64)(w0 + w) * k;
+                    const float *sv = val + (u64)(w0 + w) * k;
+                    u64 at = from[q];
+                    u32 i = ri[q];
+                    float v = rv[q];
+                    while (true) {
+                        const bool inside = (u64)i < tile_end;     // 0xFFFFFFFF marks "no entry"
+                        const u64 mask = __ballot(inside);         // a prefix of the lanes: sorted
+                        // repeated indices inside one message (never produced by the
+                        // encoder, but allowed) must be added in position order
+                        const u32 left = __shfl_up(i, 1, kWave);
+                        const bool dup = inside && lane > 0 && left == i;
+                        if (!__any(dup)) {
+                            if (inside) tile[i - tile_base] += v;
+                        } else {
+                            for (u64 rest = mask; rest; rest &= rest - 1) {
+                                const int src = __ffsll((unsigned long long)rest) - 1;
+                                if ((int)lane == src) tile[i - tile_base] += v;
+                            }
+                        }
+                        const u32 took = popc_mask(mask);
+                        at += took;
+                        if (took < (u32)kWave) break;              // the slice ended inside these 64
+                        const u64 j = at + lane;
+                        i = j < k ? si[j] : 0xFFFFFFFFu;
+                        v = j < k ? sv[j] : 0.0f;
+                    }
+                    // the new position of worker w goes back into lane w
+                    if (lane == w) lo = at;
+                }
+            }
+            if (groups == 1) pos0 = lo;
         }
-    } else {
-        for (u64 t = threadIdx.x; tile_base + t < tile_end; t += kAggThreads)
-            out[tile_base + t] = tile[t] / fn;
+        if (out_vec && tile_base + kAggTile <= d) {
+            float4 *o4 = reinterpret_cast<float4 *>(out + tile_base);
+            for (int i = lane; i < kAggTile / 4; i += kWave) {
+                float4 v = reinterpret_cast<const float4 *>(tile)[i];
+                if (n_pow2) { v.x *= rn; v.y *= rn; v.z *= rn; v.w *= rn; }
+                else { v.x /= fn; v.y /= fn; v.z /= fn; v.w /= fn; }
+                o4[i] = v;
+            }
+        } else {
+            for (u64 i = lane; tile_base + i < tile_end; i += kWave)
+                out[tile_base + i] = tile[i] / fn;
+        }
     }
 }
 
@@ -102,7 +201,10 @@ extern "C" int rtopk_aggregate(const uint32_t *idx, const float *val, uint32_t n
     if (workspace && ((uintptr_t)workspace & 255u)) return RTOPK_EWORKSPACE;
     hipStream_t stream = (hipStream_t)stream_v;
     const u64 tiles = (d + kAggTile - 1) / kAggTile;
-    k_aggregate<<<(unsigned)tiles, kAggThreads, 0, stream>>>(idx, val, n, k, d, out);
+    const u32 tiles_per_wave = (u32)((tiles + kAggMaxWaves - 1) / kAggMaxWaves);
+    const u64 waves = (tiles + tiles_per_wave - 1) / tiles_per_wave;
+    const unsigned grid = (unsigned)((waves + kAggWaves - 1) / kAggWaves);
+    k_aggregate<<<grid, kAggThreads, 0, stream>>>(idx, val, n, k, d, tiles, tiles_per_wave, out);
     if (hipGetLastError() != hipSuccess) return RTOPK_EHIP;
     return RTOPK_OK;
 }
