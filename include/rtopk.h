@@ -9,11 +9,14 @@
  * Conventions for every entry point
  *   - Pointers marked "device" are HIP device pointers valid on the current
  *     device; pointers marked "host" are ordinary host pointers.
- *   - The library allocates nothing, keeps no state between calls and never
- *     synchronises the host (rtopk_encode_stats excepted). Work is enqueued
- *     on `stream` (a hipStream_t, may be NULL for the default stream) and the
- *     call returns at once. The caller owns all buffers, workspace included,
- *     and must keep them alive until the stream has drained.
+ *   - The library allocates no device memory and never synchronises the host
+ *     (rtopk_encode_stats excepted). All state that links one call to the
+ *     next is in the caller's buffers (the residual) and arguments (step); the
+ *     library itself only remembers, per device, the launch width of its
+ *     streaming kernel. Work is enqueued on `stream` (a hipStream_t, may be
+ *     NULL for the default stream) and the call returns at once. The caller
+ *     owns all buffers, workspace included, and must keep them alive until the
+ *     stream has drained.
  *   - Two calls may run concurrently only with distinct workspaces, residuals
  *     and outputs.
  *   - Return value: RTOPK_OK or a negative error code; rtopk_strerror() gives
@@ -66,8 +69,11 @@ int rtopk_aggregate_workspace_bytes(uint64_t d, uint32_t n, uint64_t k, uint64_t
  *            distinct `seed`s give independent workers
  * out_idx    device, [k] uint32, the set U in strictly ascending order
  * out_val    device, [k] binary32, out_val[j] = a[out_idx[j]]
- * workspace  device, 256-byte aligned, >= rtopk_encode_workspace_bytes(d,r,k);
- *            contents on entry are irrelevant, contents on return unspecified
+ * workspace  device, 256-byte aligned, >= rtopk_encode_workspace_bytes(d,r,k)
+ *            (about 8 bytes per element plus 14 MB: every chunk of the vector
+ *            owns room for all its elements as candidates, of which only the
+ *            kept ones are ever written); contents on entry are irrelevant,
+ *            contents on return unspecified
  * stream     hipStream_t
  */
 int rtopk_encode(const float *grad, float *residual,

@@ -1,5 +1,5 @@
 // rtopk_encode: one node-side step of Algorithm 1 (error compensation, the
-// rTop-k operator of Definition 3, residual write-back) as a chain of six
+// rTop-k operator of Definition 3, residual write-back) as a chain of eight
 // gfx950 kernels that stream the gradient and the residual exactly once
 // (12d bytes). All cross-kernel state lives in the caller's workspace.
 //
@@ -14,22 +14,24 @@
 //
 // Pipeline:
 //   sample     a = g + m at 16384 jittered, stratified locations (4 elements
-//              each); clears the control block and the global histogram
+//              each); clears the control block
 //   estimate   one workgroup: from the sample's order statistics, a lower
 //              bound t_lo that the r-th largest magnitude exceeds and an upper
 //              bound t_hi that it stays below, both with ~6 sigma of margin;
 //              [t_lo, t_hi] becomes the finely binned part of the histogram
 //   fused      a = g + m, stored into the residual buffer (12d bytes, the
 //              dominant kernel); entries with magnitude >= t_lo -> S, and
-//              into a 4096-bin histogram: 2048 linear bins over the fine
-//              range, 2048 coarse bins (top 11 magnitude bits) above it
-//   classify   every workgroup picks the histogram bin that holds the r-th
-//              largest magnitude. Entries of S above that bin are certain
-//              members of the top-r set: their Philox key is compared with an
-//              a-priori window [K_lo, K_hi] around the k-th smallest of r
-//              uniform keys - below: certain winner (counted per chunk),
-//              inside: copied to the short list M. Entries inside the
-//              deciding bin are copied to the short list B
+//              into the workgroup's own histogram row: up to 2048 linear bins
+//              over the fine range, 256 exponent bins above it
+//   reduce     the workgroups' histogram rows -> 32 rows
+//   pick       one workgroup: sum of the 32 rows, and the bin that holds the
+//              r-th largest magnitude (the deciding bin)
+//   classify   entries of S above the deciding bin are certain members of
+//              the top-r set: their Philox key is compared with an a-priori
+//              window [K_lo, K_hi] around the k-th smallest of r uniform
+//              keys - below: certain winner (counted per chunk), inside:
+//              copied to the short list M. Entries inside the deciding bin
+//              are copied to the short list B
 //   finalize   one workgroup: exact r-th largest (magnitude, lower index
 //              first) inside B -> (T, I*); members of B join the key lists;
 //              exact (k - #certain)-th smallest (key, index) in M -> (K*, J*);
@@ -40,16 +42,16 @@
 //              index order, starting at the chunk's prefix; residual at the
 //              sent positions <- a - a
 // If the sample misleads the estimate so far that S holds fewer than r
-// entries, the histogram shows it; classify then raises a flag and finalize
-// and emit walk the vector a itself instead of S (slow, exact).
+// entries, the histogram shows it; pick then raises a flag and classify,
+// finalize and emit walk the vector a itself instead of S (slow, exact).
 //
 // What the hardware punishes shaped this: a device-scope fence inside a
 // kernel costs tens of microseconds once a few hundred workgroups execute
-// one, and atomics on a single address retire at about one per 12 ns. So no
-// kernel here uses a fence, a ticket or a "last workgroup out" protocol;
-// workgroups never wait for each other; global atomics only go to histogram
-// bins and per-chunk counters; small decisions are recomputed by every
-// workgroup that needs them.
+// one, atomics on a single address retire at about one per 12 ns, and
+// atomics on one 64-byte line queue behind each other too. So no kernel here
+// uses a fence, a ticket or a "last workgroup out" protocol; workgroups never
+// wait for each other; histograms are accumulated in LDS and stored as plain
+// rows; global atomics only go to per-chunk counters.
 #include "rtopk_common.h"
 #include "../../include/rtopk.h"
 
@@ -623,11 +625,11 @@ struct Candidates {
 // i first fetches the size of the i-th of them (there are at most
 // kUnitChunks), a prefix sum turns flat positions into (chunk, entry) pairs,
 // and every iteration of the walk hands 64 consecutive positions to the 64
-// lanes; the entries of one chunk stay in index order. f(valid, i, chunk,
-// entry, first, p0) is called by all lanes in every iteration, so it may use
-// wave-wide operations; i is the ordinal of the chunk among the wavefront's
-// chunks, first the flat position of the chunk's first entry and p0 the flat
-// position lane 0 holds.
+// lanes; the entries of one chunk stay in index order. f(valid, i, index,
+// pattern, first, p0) is called by all lanes in every iteration, so it may use
+// wave-wide operations; (index, pattern) is the lane's entry, i the ordinal of
+// its chunk among the wavefront's chunks, first the flat position of the
+// chunk's first entry and p0 the flat position lane 0 holds.
 struct UnitWalk {
     u32 u, stride, excl, inc, total;
 
@@ -644,22 +646,46 @@ struct UnitWalk {
         total = __shfl(inc, kWave - 1, kWave);
     }
 
+    // flat position p -> ordinal of its chunk and the flat position of that chunk's first entry
+    __device__ __forceinline__ void locate(u32 p, u32 *ordinal, u32 *first) const
+    {
+        // number of chunks that end at or before position p = ordinal of p's chunk
+        u32 c = 0;
+#pragma unroll
+        for (u32 step = kUnitChunks / 2; step > 0; step >>= 1) {
+            const u32 end_of = __shfl(inc, c + step - 1, kWave);
+            if (end_of <= p) c += step;
+        }
+        c &= kUnitChunks - 1;
+        *ordinal = c;
+        *first = __shfl(excl, c, kWave);
+    }
+
+    // f(valid, i, index, pattern, first, p0), see above; the entries of four
+    // iterations are fetched together while that many are left
     template <class F>
-    __device__ __forceinline__ void for_each(F &&f) const
+    __device__ __forceinline__ void for_each(const Candidates &cand, F &&f) const
     {
         const u32 lane = lane_id();
-        for (u32 p0 = 0; p0 < total; p0 += kWave) {
-            const u32 p = p0 + lane;
-            // number of chunks that end at or before position p = ordinal of p's chunk
-            u32 c = 0;
+        constexpr u32 kAhead = 4;
+        u32 p0 = 0;
+        for (; p0 + kAhead * kWave <= total; p0 += kAhead * kWave) {
+            u32 c[kAhead], first[kAhead], idx[kAhead], bits[kAhead];
 #pragma unroll
-            for (u32 step = kUnitChunks / 2; step > 0; step >>= 1) {
-                const u32 end_of = __shfl(inc, c + step - 1, kWave);
-                if (end_of <= p) c += step;
+            for (u32 q = 0; q < kAhead; ++q) {
+                const u32 p = p0 + q * kWave + lane;
+                locate(p, &c[q], &first[q]);
+                cand.entry(u + c[q] * stride, p - first[q], &idx[q], &bits[q]);
             }
-            c &= kUnitChunks - 1;
-            const u32 first = __shfl(excl, c, kWave);
-            f(p < total, c, u + c * stride, p - first, first, p0);
+#pragma unroll
+            for (u32 q = 0; q < kAhead; ++q) f(true, c[q], idx[q], bits[q], first[q], p0 + q * kWave);
+        }
+        for (; p0 < total; p0 += kWave) {
+            const u32 p = p0 + lane;
+            u32 c, first, idx = 0, bits = 0;
+            locate(p, &c, &first);
+            if (p < total) cand.entry(u + c * stride, p - first, &idx, &bits);
+            f(p < total, c, idx, bits, first, p0);
         }
     }
 };
@@ -771,10 +797,8 @@ k_classify(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ seg_
     // entry p of this workgroup's short lists lives at [p][workgroup]: the
     // finalize kernel reads entry p of all workgroups with one coalesced load
     auto slot = [&](u32 p) { return (u64)p * g.G3 + blockIdx.x; };
-    walk.for_each([&](bool valid, u32 i, u32 s, u32 j, u32, u32) {
+    walk.for_each(cand, [&](bool valid, u32 i, u32 idx, u32 bits, u32, u32) {
         if (!valid) return;
-        u32 idx, bits;
-        cand.entry(s, j, &idx, &bits);
         const u32 m = mag_of(bits);
         if (m > bd_hi) {
             bool sure = g.take_all != 0u;
@@ -1187,11 +1211,9 @@ k_emit(Geom g, PhiloxSeed seed, const EncodeCtl *__restrict__ ctl,
     const u64 below = lanes_below();
     u32 run = 0;          // winners at flat positions before this iteration
     u32 carry = 0;        // winners before the first entry of the chunk that runs into this iteration
-    walk.for_each([&](bool valid, u32 i, u32 s, u32 j, u32 first, u32 p0) {
+    walk.for_each(cand, [&](bool valid, u32 i, u32 idx, u32 bits, u32 first, u32 p0) {
         bool win = false;
-        u32 idx = 0, bits = 0;
         if (valid) {
-            cand.entry(s, j, &idx, &bits);
             const u32 m = mag_of(bits);
             win = m > T || (m == T && idx <= I_star);
             if (win && !g.take_all) win = pair_le(sample_key(idx, seed), idx, kcut);
