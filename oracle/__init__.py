@@ -29,7 +29,7 @@ _f32p = ctypes.POINTER(ctypes.c_float)
 def build() -> str:
     """Compile the oracle with gcc (strict IEEE arithmetic, no contraction)."""
     cmd = ["gcc", "-O2", "-std=c11", "-fno-fast-math", "-ffp-contract=off",
-           "-Wall", "-Wextra", "-shared", "-fPIC", "-o", _SO, _SRC]
+           "-Wall", "-Wextra", "-shared", "-fPIC", "-o", _SO, _SRC, "-lm"]
     subprocess.run(cmd, check=True)
     return _SO
 
@@ -55,6 +55,14 @@ def lib() -> ctypes.CDLL:
             fn.argtypes = [_u32p, _f32p, ctypes.c_uint32, ctypes.c_uint64,
                            ctypes.c_uint64, _f32p]
             fn.restype = ctypes.c_int
+        L.rtopk_oracle_aggregate_update.argtypes = [
+            _u32p, _f32p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_uint64,
+            ctypes.c_double, ctypes.c_double, _f32p, _f32p]
+        L.rtopk_oracle_aggregate_update.restype = ctypes.c_int
+        L.rtopk_oracle_aggregate_update_f32.argtypes = [
+            _u32p, _f32p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_uint64,
+            ctypes.c_float, ctypes.c_float, _f32p, _f32p]
+        L.rtopk_oracle_aggregate_update_f32.restype = ctypes.c_int
         _LIB = L
     return _LIB
 
@@ -129,3 +137,32 @@ def aggregate(idx: np.ndarray, val: np.ndarray, n: int, d: int) -> np.ndarray:
 def aggregate_f32(idx: np.ndarray, val: np.ndarray, n: int, d: int) -> np.ndarray:
     """The same average in binary32, workers added in order 0..n-1."""
     return _aggregate("rtopk_oracle_aggregate_f32", idx, val, n, d)
+
+
+def _aggregate_update(fn_name: str, idx, val, n: int, d: int, eta: float, scale: float,
+                      omega: np.ndarray) -> np.ndarray:
+    idx = np.ascontiguousarray(idx, dtype=np.uint32).reshape(-1)
+    val = _f32(val).reshape(-1)
+    omega = _f32(omega).reshape(-1)
+    if idx.size != val.size or n < 1 or idx.size % n != 0 or omega.size != d:
+        raise ValueError("idx/val must hold n messages of equal length, omega d weights")
+    k = idx.size // n
+    out = np.empty(d, dtype=np.float32)
+    rc = getattr(lib(), fn_name)(idx.ctypes.data_as(_u32p), val.ctypes.data_as(_f32p), n, k, d,
+                                 eta, scale, omega.ctypes.data_as(_f32p),
+                                 out.ctypes.data_as(_f32p))
+    _check(rc, fn_name)
+    return out
+
+
+def aggregate_update(idx, val, n: int, d: int, eta: float, scale: float,
+                     omega: np.ndarray) -> np.ndarray:
+    """Both master lines of Algorithm 1: omega - eta * scale * mean, binary64, one rounding."""
+    return _aggregate_update("rtopk_oracle_aggregate_update", idx, val, n, d, eta, scale, omega)
+
+
+def aggregate_update_f32(idx, val, n: int, d: int, eta: float, scale: float,
+                         omega: np.ndarray) -> np.ndarray:
+    """The same update in binary32: worker-order sum, / n, fma(-(eta * scale), mean, omega)."""
+    return _aggregate_update("rtopk_oracle_aggregate_update_f32", idx, val, n, d, eta, scale,
+                             omega)

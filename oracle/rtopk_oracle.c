@@ -14,6 +14,13 @@
  *   - encode         Definition 3 (rTop-k) inside Algorithm 1's node loop:
  *                    g <- g + m ; ghat <- rTop_k(g) ; m <- g - ghat.
  *   - aggregate      Algorithm 1, master: ghat <- (1/n) sum_i ghat_i.
+ *   - aggregate_update  the master's two lines together:
+ *                    omega <- omega - eta * scale * (1/n) sum_i ghat_i.
+ *                    scale = 1 is Algorithm 1 as printed; scale = r/k divides
+ *                    what a node kept by the fraction k/r it kept of its
+ *                    top-r set, the way the estimator in the proof of the
+ *                    estimation upper bound divides the subsampled vector by
+ *                    its subsampling fraction (unbiased for the top-r part).
  *
  * Readings taken where the paper leaves a choice open (they make the result
  * unique, so that another implementation can be compared bit for bit):
@@ -36,6 +43,7 @@
  *
  * Build: gcc -O2 -ffp-contract=off -fno-fast-math -shared -fPIC
  */
+#include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -257,5 +265,62 @@ int rtopk_oracle_aggregate_f32(const uint32_t *idx, const float *val,
         volatile float q = out[i] / fn;
         out[i] = q;
     }
+    return ORACLE_OK;
+}
+
+/*
+ * Master step of Algorithm 1 with the weight update folded in:
+ *     omega_out = omega_in - eta * scale * (1/n) * sum_i ghat_i.
+ * Sum in binary64 in worker order, everything else in binary64, one rounding
+ * to binary32 at the end. omega_in and omega_out may be the same array.
+ */
+int rtopk_oracle_aggregate_update(const uint32_t *idx, const float *val,
+                                  uint32_t n, uint64_t k, uint64_t d,
+                                  double eta, double scale,
+                                  const float *omega_in, float *omega_out)
+{
+    if (!idx || !val || !omega_in || !omega_out || n < 1 || k < 1 || d < 1 ||
+        d > 0xFFFFFFFFull)
+        return ORACLE_EINVAL;
+    double *acc = (double *)calloc((size_t)d, sizeof *acc);
+    if (!acc) return ORACLE_ENOMEM;
+    for (uint32_t w = 0; w < n; ++w)
+        for (uint64_t j = 0; j < k; ++j) {
+            uint32_t i = idx[(uint64_t)w * k + j];
+            if (i >= d) { free(acc); return ORACLE_EINVAL; }
+            acc[i] += (double)val[(uint64_t)w * k + j];
+        }
+    for (uint64_t i = 0; i < d; ++i) {
+        const double ghat = acc[i] / (double)n;
+        omega_out[i] = (float)((double)omega_in[i] - eta * scale * ghat);
+    }
+    free(acc);
+    return ORACLE_OK;
+}
+
+/*
+ * The same update in binary32 with a fixed order of operations: the average
+ * exactly as rtopk_oracle_aggregate_f32 forms it (sum from +0 in worker
+ * order, one division by (float)n), the step c = (float)eta * (float)scale
+ * rounded once, and omega_out = fma(-c, average, omega_in) with the single
+ * rounding of a fused multiply-add. A coordinate whose sum is zero keeps its
+ * weight bit for bit (fma(-c, 0, w) == w for every w, signed zeros included).
+ */
+int rtopk_oracle_aggregate_update_f32(const uint32_t *idx, const float *val,
+                                      uint32_t n, uint64_t k, uint64_t d,
+                                      float eta, float scale,
+                                      const float *omega_in, float *omega_out)
+{
+    if (!idx || !val || !omega_in || !omega_out || n < 1 || k < 1 || d < 1 ||
+        d > 0xFFFFFFFFull)
+        return ORACLE_EINVAL;
+    float *avg = (float *)malloc((size_t)d * sizeof *avg);
+    if (!avg) return ORACLE_ENOMEM;
+    int rc = rtopk_oracle_aggregate_f32(idx, val, n, k, d, avg);
+    if (rc != ORACLE_OK) { free(avg); return rc; }
+    volatile float c = eta * scale;
+    const float neg_c = -c;
+    for (uint64_t i = 0; i < d; ++i) omega_out[i] = fmaf(neg_c, avg[i], omega_in[i]);
+    free(avg);
     return ORACLE_OK;
 }

@@ -368,3 +368,115 @@ def test_encode_then_aggregate_matches_brute_force_end_to_end():
             dense[bi] += bv.astype(np.float64)
         out = oracle.aggregate(np.concatenate(msgs_i), np.concatenate(msgs_v), n, d)
         assert np.array_equal(out, (dense / n).astype(np.float32))
+
+
+# --------------------------------------------------------------------------
+# master, both lines: omega <- omega - eta * scale * (1/n) sum_i ghat_i
+# --------------------------------------------------------------------------
+def test_aggregate_update_worked_example_by_hand():
+    # two workers, six weights, all numbers dyadic so that every step is exact:
+    # worker 0 sends (1, 0.5), (4, -2); worker 1 sends (1, 1.5), (3, 4)
+    # mean = [0, 1, 0, 2, -1, 0]
+    idx = np.array([1, 4, 1, 3], np.uint32)
+    val = np.array([0.5, -2.0, 1.5, 4.0], np.float32)
+    omega = np.array([1, 2, 3, 4, 5, 6], np.float32)
+    for fn in (oracle.aggregate_update, oracle.aggregate_update_f32):
+        # eta = 1/2, as printed in Algorithm 1 (scale 1)
+        assert np.array_equal(fn(idx, val, 2, 6, 0.5, 1.0, omega),
+                              np.array([1, 1.5, 3, 3, 5.5, 6], np.float32))
+        # the same with what was kept divided by a kept fraction of 1/2
+        assert np.array_equal(fn(idx, val, 2, 6, 0.5, 2.0, omega),
+                              np.array([1, 1, 3, 2, 6, 6], np.float32))
+        # a step against the gradient direction's sign: eta < 0 moves the other way
+        assert np.array_equal(fn(idx, val, 2, 6, -0.25, 1.0, omega),
+                              np.array([1, 2.25, 3, 4.5, 4.75, 6], np.float32))
+
+
+def test_aggregate_update_reduces_to_the_average_and_to_the_identity():
+    rng = np.random.default_rng(71)
+    d, n, k = 500, 6, 30
+    idx = np.stack([np.sort(rng.choice(d, k, replace=False)) for _ in range(n)]).astype(np.uint32)
+    val = rng.standard_normal((n, k)).astype(np.float32)
+    omega = rng.standard_normal(d).astype(np.float32)
+    omega[::7] = -0.0
+    zero = np.zeros(d, np.float32)
+    # from zero weights with eta = -1 the update is the average itself
+    assert np.array_equal(oracle.aggregate_update(idx, val, n, d, -1.0, 1.0, zero),
+                          oracle.aggregate(idx, val, n, d))
+    assert np.array_equal(oracle.aggregate_update_f32(idx, val, n, d, -1.0, 1.0, zero),
+                          oracle.aggregate_f32(idx, val, n, d))
+    # eta = 0 leaves every weight as it is; so does a coordinate nobody sent
+    assert np.array_equal(oracle.aggregate_update(idx, val, n, d, 0.0, 1.0, omega), omega)
+    out32 = oracle.aggregate_update_f32(idx, val, n, d, 0.3, 5.0, omega)
+    out64 = oracle.aggregate_update(idx, val, n, d, 0.3, 5.0, omega)
+    untouched = np.setdiff1d(np.arange(d), idx.reshape(-1))
+    assert np.array_equal(bits(out32[untouched]), bits(omega[untouched]))
+    assert np.array_equal(bits(out64[untouched]), bits(omega[untouched]))
+    touched = np.unique(idx.reshape(-1))
+    assert np.all(out64[touched] != omega[touched])
+
+
+def test_aggregate_update_equals_the_dense_formula_and_f32_variant_is_close():
+    rng = np.random.default_rng(72)
+    d, n, k = 400, 5, 60
+    idx = np.stack([np.sort(rng.choice(d, k, replace=False)) for _ in range(n)]).astype(np.uint32)
+    val = (rng.standard_normal((n, k)) * 10.0 ** rng.uniform(-3, 1, (n, k))).astype(np.float32)
+    omega = rng.standard_normal(d).astype(np.float32)
+    eta, scale = float(np.float32(0.05)), float(np.float32(2.5))
+    dense = np.zeros((n, d), np.float64)
+    for w in range(n):
+        for j in range(k):                           # ghat_w as a dense vector, entry by entry
+            dense[w, idx[w, j]] += float(val[w, j])
+    ghat = dense.sum(axis=0) / n
+    want = omega.astype(np.float64) - eta * scale * ghat
+    out64 = oracle.aggregate_update(idx, val, n, d, eta, scale, omega)
+    assert np.array_equal(out64, want.astype(np.float32))
+    out32 = oracle.aggregate_update_f32(idx, val, n, d, eta, scale, omega)
+    size = np.abs(omega.astype(np.float64)) + eta * scale * np.abs(dense).sum(axis=0) / n
+    assert np.all(np.abs(out32.astype(np.float64) - want) <= 1e-6 * size)
+    # the order of the two scalars matters to nobody: (eta, scale) and (eta * scale, 1)
+    swapped = oracle.aggregate_update(idx, val, n, d, eta * scale, 1.0, omega)
+    assert np.array_equal(swapped, out64)
+
+
+def test_aggregate_update_f32_uses_one_rounding_for_multiply_and_subtract():
+    # omega = 1, mean = 1 + 2^-12, c = 1 + 2^-12: the product 1 + 2^-11 + 2^-24
+    # needs 25 bits. Fused: 1 - that = -(2^-11 + 2^-24), exact in binary32.
+    # A rounded product (1 + 2^-11, the tie goes to even) would give -2^-11.
+    v = np.float32(1.0 + 2.0 ** -12)
+    out = oracle.aggregate_update_f32(np.array([0], np.uint32), np.array([v], np.float32), 1, 1,
+                                      float(v), 1.0, np.array([1.0], np.float32))
+    assert float(out[0]) == -(2.0 ** -11 + 2.0 ** -24)
+    out64 = oracle.aggregate_update(np.array([0], np.uint32), np.array([v], np.float32), 1, 1,
+                                    float(v), 1.0, np.array([1.0], np.float32))
+    assert float(out64[0]) == -(2.0 ** -11 + 2.0 ** -24)
+
+
+def test_scale_r_over_k_makes_the_sent_vector_unbiased_for_the_top_r_part():
+    # The estimator in the proof of the estimation upper bound divides the
+    # subsampled vector by its subsampling fraction. Here the fraction is k/r:
+    # over many independent draws (steps) the mean of (r/k) * rTop_k(x) must
+    # approach top_r(x). One worker, zero weights, eta = -1: the update is
+    # scale * ghat.
+    rng = np.random.default_rng(73)
+    d, r, k, N = 120, 40, 8, 3000
+    x = rng.standard_normal(d).astype(np.float32)
+    top = oracle.top_r(x, r)
+    want = np.zeros(d, np.float64)
+    want[top] = x[top]
+    acc = np.zeros(d, np.float64)
+    zero = np.zeros(d, np.float32)
+    for t in range(N):
+        oi, ov, _ = oracle.encode(x, zero, r, k, 99, t)
+        acc += oracle.aggregate_update(oi, ov, 1, d, -1.0, r / k, zero)
+    sd = np.sqrt((r / k - 1.0) / N) * np.abs(want)   # sd of the mean of (r/k) * x * Bernoulli(k/r)
+    assert np.all(np.abs(acc / N - want) <= 6 * sd)
+    assert np.any(np.abs(acc / N - want * k / r) > 6 * sd)   # and the unscaled mean is not
+
+
+def test_aggregate_update_rejects_out_of_range_index_and_wrong_length():
+    one = np.array([1.0], np.float32)
+    with pytest.raises(ValueError):
+        oracle.aggregate_update(np.array([4], np.uint32), one, 1, 4, 0.1, 1.0, np.zeros(4, np.float32))
+    with pytest.raises(ValueError):
+        oracle.aggregate_update(np.array([1], np.uint32), one, 1, 4, 0.1, 1.0, np.zeros(3, np.float32))
