@@ -104,6 +104,38 @@ int rtopk_aggregate(const uint32_t *idx, const float *val,
                     void *workspace, uint64_t workspace_bytes, void *stream);
 
 /*
+ * Both master lines of Algorithm 1 in one step, without the dense average in
+ * between: omega[i] <- omega[i] - eta * scale * (1/n) * sum_{w<n} message_w[i].
+ * scale = 1 is the algorithm as printed. scale = r/k divides what a node kept
+ * by the fraction k/r it kept of its top-r set, in the manner of the
+ * estimator in the proof of the estimation upper bound, which divides the
+ * subsampled vector by its subsampling fraction; the mean over the random
+ * subsets then equals the top-r part of the node's vector.
+ *
+ * Arithmetic, all binary32: the sum and the division by n exactly as in
+ * rtopk_aggregate; the step c = eta * scale rounded once; then one fused
+ * multiply-add, omega[i] = fma(-c, average[i], omega[i]). A coordinate whose
+ * sum is zero (nobody sent it, or what was sent cancels) keeps its bits.
+ * Reproducible bit for bit; no atomics.
+ *
+ * idx, val, n, k, d   as for rtopk_aggregate; n <= 65535
+ * omega   device, [d] binary32, updated in place. Only weights that move are
+ *         written; where many indices fall close together, the 16-byte groups
+ *         around them are read and written back whole, the unmoved weights
+ *         with the bits they had. Must not overlap idx, val or workspace.
+ * workspace  device, 256-byte aligned, >= rtopk_aggregate_update_workspace_bytes
+ *            (4 bytes per worker and per 2048 coordinates); contents on entry
+ *            are irrelevant, contents on return unspecified
+ * Errors: RTOPK_EINVAL, RTOPK_EWORKSPACE, RTOPK_EHIP as for rtopk_encode.
+ */
+int rtopk_aggregate_update_workspace_bytes(uint64_t d, uint32_t n, uint64_t k, uint64_t *bytes);
+int rtopk_aggregate_update(const uint32_t *idx, const float *val,
+                           uint32_t n, uint64_t k, uint64_t d,
+                           float eta, float scale,
+                           float *omega,
+                           void *workspace, uint64_t workspace_bytes, void *stream);
+
+/*
  * Diagnostics of the most recent rtopk_encode that used `workspace`.
  * Synchronises `stream`, then copies a few counters to the host. Not part of
  * the hot path; tests and profiling use it.

@@ -292,6 +292,10 @@ int rtopk_oracle_aggregate_update(const uint32_t *idx, const float *val,
         }
     for (uint64_t i = 0; i < d; ++i) {
         const double ghat = acc[i] / (double)n;
+        /* a coordinate the average does not move is copied, not recomputed:
+           the same number for every finite weight, and not-a-number weights
+           keep their bit pattern */
+        if (ghat == 0.0) { omega_out[i] = omega_in[i]; continue; }
         omega_out[i] = (float)((double)omega_in[i] - eta * scale * ghat);
     }
     free(acc);
@@ -304,7 +308,9 @@ int rtopk_oracle_aggregate_update(const uint32_t *idx, const float *val,
  * order, one division by (float)n), the step c = (float)eta * (float)scale
  * rounded once, and omega_out = fma(-c, average, omega_in) with the single
  * rounding of a fused multiply-add. A coordinate whose sum is zero keeps its
- * weight bit for bit (fma(-c, 0, w) == w for every w, signed zeros included).
+ * weight bit for bit: it is copied (fma(-c, 0, w) would give the same number
+ * for every finite w, signed zeros included, but would quieten a signalling
+ * not-a-number).
  */
 int rtopk_oracle_aggregate_update_f32(const uint32_t *idx, const float *val,
                                       uint32_t n, uint64_t k, uint64_t d,
@@ -320,7 +326,8 @@ int rtopk_oracle_aggregate_update_f32(const uint32_t *idx, const float *val,
     if (rc != ORACLE_OK) { free(avg); return rc; }
     volatile float c = eta * scale;
     const float neg_c = -c;
-    for (uint64_t i = 0; i < d; ++i) omega_out[i] = fmaf(neg_c, avg[i], omega_in[i]);
+    for (uint64_t i = 0; i < d; ++i)
+        omega_out[i] = avg[i] != 0.0f ? fmaf(neg_c, avg[i], omega_in[i]) : omega_in[i];
     free(avg);
     return ORACLE_OK;
 }

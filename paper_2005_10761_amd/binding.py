@@ -14,7 +14,8 @@ _LIB_PATH = os.path.join(_HERE, "librtopk.so")
 _LIB: Optional[ctypes.CDLL] = None
 
 EXPORTS = ("rtopk_encode_workspace_bytes", "rtopk_aggregate_workspace_bytes", "rtopk_encode",
-           "rtopk_aggregate", "rtopk_encode_stats", "rtopk_trace_next_encode",
+           "rtopk_aggregate", "rtopk_aggregate_update", "rtopk_aggregate_update_workspace_bytes",
+           "rtopk_encode_stats", "rtopk_trace_next_encode",
            "rtopk_force_next_encode", "rtopk_strerror", "rtopk_version")
 
 
@@ -54,6 +55,11 @@ def load_library() -> ctypes.CDLL:
     L.rtopk_encode.restype = ctypes.c_int
     L.rtopk_aggregate.argtypes = [vp, vp, u32, u64, u64, vp, vp, u64, vp]
     L.rtopk_aggregate.restype = ctypes.c_int
+    L.rtopk_aggregate_update_workspace_bytes.argtypes = [u64, u32, u64, ctypes.POINTER(u64)]
+    L.rtopk_aggregate_update_workspace_bytes.restype = ctypes.c_int
+    L.rtopk_aggregate_update.argtypes = [vp, vp, u32, u64, u64, ctypes.c_float, ctypes.c_float,
+                                         vp, vp, u64, vp]
+    L.rtopk_aggregate_update.restype = ctypes.c_int
     L.rtopk_encode_stats.argtypes = [vp, vp, ctypes.POINTER(EncodeStats)]
     L.rtopk_encode_stats.restype = ctypes.c_int
     L.rtopk_trace_next_encode.argtypes = [ctypes.c_int, vp, vp]
@@ -143,6 +149,32 @@ def aggregate(idx: torch.Tensor, val: torch.Tensor, n: int, k: int, out: torch.T
                                         _ptr(workspace), ws_bytes, _stream_handle(stream))
     if rc:
         raise RtopkError(rc, "rtopk_aggregate")
+
+
+def aggregate_update_workspace_bytes(d: int, n: int, k: int) -> int:
+    out = ctypes.c_uint64(0)
+    rc = load_library().rtopk_aggregate_update_workspace_bytes(d, n, k, ctypes.byref(out))
+    if rc:
+        raise RtopkError(rc, "rtopk_aggregate_update_workspace_bytes")
+    return out.value
+
+
+def aggregate_update(idx: torch.Tensor, val: torch.Tensor, n: int, k: int, eta: float,
+                     scale: float, omega: torch.Tensor, workspace: torch.Tensor,
+                     stream=None) -> None:
+    """rtopk_aggregate_update: enqueue omega -= eta * scale * (average of the n
+    messages), in place on ``omega`` (d elements)."""
+    _need(idx, torch.int32, "idx")
+    _need(val, torch.float32, "val")
+    _need(omega, torch.float32, "omega")
+    if idx.numel() < n * k or val.numel() < n * k:
+        raise ValueError("idx/val must hold n*k entries")
+    rc = load_library().rtopk_aggregate_update(_ptr(idx), _ptr(val), n, k, omega.numel(),
+                                               eta, scale, _ptr(omega), _ptr(workspace),
+                                               workspace.numel() * workspace.element_size(),
+                                               _stream_handle(stream))
+    if rc:
+        raise RtopkError(rc, "rtopk_aggregate_update")
 
 
 STAGES = {"prepare": 1, "fused": 2, "classify": 3, "finalize": 4, "emit": 5, "all": 100}

@@ -17,6 +17,17 @@
 // worker 0, 1, ... The tile is finally divided by n and written with 16-byte
 // stores. HBM traffic: 4d bytes written + 8nk bytes read; no atomics, no
 // sort, no workspace.
+//
+// rtopk_aggregate_update applies the master's next line, omega <- omega -
+// eta * ghat, to the weights directly, so the dense ghat is never stored and
+// only weights that some worker sent are read and written. It uses the same
+// 2048-coordinate tiles with one wavefront per tile, but where a tile starts
+// in each worker's list is not searched: a first kernel looks at every pair
+// of neighbouring entries and, wherever the tile number changes, writes the
+// entry's position into a [tile][worker] table for all tiles in between.
+// The second kernel reads its tile's row and the next one, leaves at once if
+// the tile is empty, and otherwise adds the entries into its LDS tile in
+// worker order, then updates the weights at the non-zero positions.
 #include "rtopk_common.h"
 #include "../../include/rtopk.h"
 
@@ -179,6 +190,178 @@ k_aggregate(const u32 *__restrict__ idx, const float *__restrict__ val, u32 n, u
     }
 }
 
+// ---------------------------------------------------------------------------
+// tile_starts: start[t * n + w] = the first position in worker w's list whose
+// index lies in tile t or later, for t = 0 .. tiles (the last row is k).
+// Thread j of worker w compares the tiles of entries j - 1 and j (tile -1
+// before the list, tile `tiles` after it) and fills the rows in between;
+// since the list ascends, every row is written exactly once. A long run of
+// empty tiles is filled by the whole wavefront. blockIdx.y is the worker.
+// ---------------------------------------------------------------------------
+constexpr int kStartThreads = 256;
+
+__global__ void __launch_bounds__(kStartThreads)
+k_tile_starts(const u32 *__restrict__ idx, u32 n, u64 k, u64 tiles, u32 *__restrict__ start)
+{
+    const u32 w = blockIdx.y;
+    const u32 *wi = idx + (u64)w * k;
+    const u64 j = (u64)blockIdx.x * kStartThreads + threadIdx.x;
+    // rows (from, to] get the value j; an index past the last tile (a broken
+    // precondition) is treated as the end of the list
+    u64 from = 0, to = 0;
+    if (j <= k) {
+        const u64 t_prev = j > 0 ? (u64)wi[j - 1] / kAggTile + 1 : 0;   // first row to fill
+        u64 t_cur = j < k ? (u64)wi[j] / kAggTile : tiles;
+        if (t_cur > tiles) t_cur = tiles;
+        from = t_prev;
+        to = t_cur + 1;                                                  // one past the last row
+        if (to < from) to = from;
+    }
+    const bool is_long = to - from > 8;
+    if (!is_long)
+        for (u64 t = from; t < to; ++t) start[t * n + w] = (u32)j;
+    for (u64 rest = __ballot(is_long); rest; rest &= rest - 1) {
+        const int src = __ffsll((unsigned long long)rest) - 1;
+        const u64 a = read_lane_u64(from, src), b = read_lane_u64(to, src);
+        const u32 v = (u32)read_lane_u64(j, src);
+        for (u64 t = a + lane_id(); t < b; t += kWave) start[t * n + w] = v;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// update: one wavefront per tile. omega[i] = fma(neg_step, average[i],
+// omega[i]) wherever the sum of what the workers sent for i is not zero.
+// ---------------------------------------------------------------------------
+constexpr u32 kDenseTileEntries = 512;     // from here on the whole tile is read and written
+
+__global__ void __launch_bounds__(kAggThreads)
+k_update(const u32 *__restrict__ idx, const float *__restrict__ val, u32 n, u64 k, u64 d,
+         u64 tiles, const u32 *__restrict__ start, float neg_step, float *__restrict__ omega)
+{
+    __shared__ float tile_s[kAggWaves][kAggTile];
+    const u32 lane = lane_id(), wave = threadIdx.x / kWave;
+    float *tile = tile_s[wave];
+    const u64 t = (u64)blockIdx.x * kAggWaves + wave;
+    if (t >= tiles) return;
+    const u64 tile_base = t * kAggTile;
+    const u64 tile_end = tile_base + kAggTile < d ? tile_base + kAggTile : d;
+    const float fn = (float)n;
+    const bool n_pow2 = (n & (n - 1u)) == 0u;
+    const float rn = 1.0f / fn;
+    bool cleared = false;
+    u32 entries = 0;
+
+    for (u32 w0 = 0; w0 < n; w0 += kWave) {
+        const u32 nw = n - w0 < (u32)kWave ? n - w0 : (u32)kWave;
+        // lane w: the part [lo, hi) of worker w0 + w's list that lies in this tile
+        u64 lo = 0, hi = 0;
+        if (lane < nw) {
+            lo = start[t * n + w0 + lane];
+            hi = start[(t + 1) * n + w0 + lane];
+            if (hi > k) hi = k;
+            if (lo > hi) lo = hi;
+        }
+        const u32 here = wave_sum((u32)(hi - lo));
+        if (here == 0u) continue;
+        if (!cleared) {
+            for (int i = lane; i < kAggTile / 4; i += kWave)
+                reinterpret_cast<float4 *>(tile)[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            cleared = true;
+        }
+        entries += here;
+        for (u32 g0 = 0; g0 < nw; g0 += kAggAhead) {
+            u64 from[kAggAhead], to[kAggAhead];
+            u32 ri[kAggAhead];
+            float rv[kAggAhead];
+#pragma unroll
+            for (int q = 0; q < kAggAhead; ++q) {
+                const u32 w = g0 + q < nw ? g0 + q : nw - 1;
+                from[q] = read_lane_u64(lo, (int)w);
+                to[q] = g0 + q < nw ? read_lane_u64(hi, (int)w) : from[q];
+                const u64 j = from[q] + lane;
+                const bool in = j < to[q];
+                ri[q] = in ? idx[(u64)(w0 + w) * k + j] : 0xFFFFFFFFu;
+                rv[q] = in ? val[(u64)(w0 + w) * k + j] : 0.0f;
+            }
+#pragma unroll
+            for (int q = 0; q < kAggAhead; ++q) {
+                if (g0 + q >= nw) break;
+                const u32 *si = idx + (u64)(w0 + g0 + q) * k;
+                const float *sv = val + (u64)(w0 + g0 + q) * k;
+                u64 at = from[q];
+                u32 i = ri[q];
+                float v = rv[q];
+                while (at < to[q]) {
+                    // the table says these entries belong to the tile; the check keeps a
+                    // list that is not sorted (a broken precondition) inside the LDS tile
+                    const bool inside = at + lane < to[q] && (u64)i >= tile_base && (u64)i < tile_end;
+                    // repeated indices inside one message must be added in position order
+                    const u32 left = __shfl_up(i, 1, kWave);
+                    const bool dup = inside && lane > 0 && left == i;
+                    if (!__any(dup)) {
+                        if (inside) tile[i - tile_base] += v;
+                    } else {
+                        for (u64 rest = __ballot(inside); rest; rest &= rest - 1) {
+                            const int src = __ffsll((unsigned long long)rest) - 1;
+                            if ((int)lane == src) tile[i - tile_base] += v;
+                        }
+                    }
+                    at += kWave;
+                    if (at >= to[q]) break;
+                    const u64 j = at + lane;
+                    i = j < to[q] ? si[j] : 0xFFFFFFFFu;
+                    v = j < to[q] ? sv[j] : 0.0f;
+                }
+            }
+        }
+    }
+    if (!cleared) return;                               // nobody sent anything in this tile
+
+    auto step = [&](float sum, float w) {
+        const float avg = n_pow2 ? sum * rn : sum / fn;
+        return fmaf(neg_step, avg, w);
+    };
+    constexpr int kVecs = kAggTile / 4 / kWave;         // float4 per lane
+    float4 s4[kVecs];
+#pragma unroll
+    for (int q = 0; q < kVecs; ++q) s4[q] = reinterpret_cast<const float4 *>(tile)[q * kWave + lane];
+    if (entries >= kDenseTileEntries && ((uintptr_t)omega & 15u) == 0 &&
+        tile_base + kAggTile <= d) {
+        float4 *o4 = reinterpret_cast<float4 *>(omega + tile_base);
+        float4 w[kVecs];
+#pragma unroll
+        for (int q = 0; q < kVecs; ++q) w[q] = o4[q * kWave + lane];
+#pragma unroll
+        for (int q = 0; q < kVecs; ++q) {
+            const float4 s = s4[q];
+            if (s.x == 0.0f && s.y == 0.0f && s.z == 0.0f && s.w == 0.0f) continue;
+            if (s.x != 0.0f) w[q].x = step(s.x, w[q].x);
+            if (s.y != 0.0f) w[q].y = step(s.y, w[q].y);
+            if (s.z != 0.0f) w[q].z = step(s.z, w[q].z);
+            if (s.w != 0.0f) w[q].w = step(s.w, w[q].w);
+            o4[q * kWave + lane] = w[q];
+        }
+    } else {
+        // few entries: only the weights that move are read; all loads first
+        float *o = omega + tile_base + 4 * lane;
+        float w[kVecs][4];
+#pragma unroll
+        for (int q = 0; q < kVecs; ++q) {
+            const float sv[4] = {s4[q].x, s4[q].y, s4[q].z, s4[q].w};
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                w[q][c] = sv[c] != 0.0f ? o[q * 4 * kWave + c] : 0.0f;
+        }
+#pragma unroll
+        for (int q = 0; q < kVecs; ++q) {
+            const float sv[4] = {s4[q].x, s4[q].y, s4[q].z, s4[q].w};
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (sv[c] != 0.0f) o[q * 4 * kWave + c] = step(sv[c], w[q][c]);
+        }
+    }
+}
+
 }  // namespace rtopk
 
 using namespace rtopk;
@@ -205,6 +388,40 @@ extern "C" int rtopk_aggregate(const uint32_t *idx, const float *val, uint32_t n
     const u64 waves = (tiles + tiles_per_wave - 1) / tiles_per_wave;
     const unsigned grid = (unsigned)((waves + kAggWaves - 1) / kAggWaves);
     k_aggregate<<<grid, kAggThreads, 0, stream>>>(idx, val, n, k, d, tiles, tiles_per_wave, out);
+    if (hipGetLastError() != hipSuccess) return RTOPK_EHIP;
+    return RTOPK_OK;
+}
+
+extern "C" int rtopk_aggregate_update_workspace_bytes(uint64_t d, uint32_t n, uint64_t k,
+                                                      uint64_t *bytes)
+{
+    if (!bytes || n < 1 || k < 1 || k > 0xFFFFFFFFull || d < 1 || d > 0xFFFFFFFFull)
+        return RTOPK_EINVAL;
+    const u64 tiles = (d + kAggTile - 1) / kAggTile;
+    *bytes = align_up((tiles + 1) * (u64)n * sizeof(u32), 256);
+    return RTOPK_OK;
+}
+
+extern "C" int rtopk_aggregate_update(const uint32_t *idx, const float *val, uint32_t n,
+                                      uint64_t k, uint64_t d, float eta, float scale,
+                                      float *omega, void *workspace, uint64_t workspace_bytes,
+                                      void *stream_v)
+{
+    uint64_t need = 0;
+    if (!idx || !val || !omega || rtopk_aggregate_update_workspace_bytes(d, n, k, &need) != RTOPK_OK)
+        return RTOPK_EINVAL;
+    if (n > 65535u) return RTOPK_EINVAL;                // workers are a grid dimension
+    if (!workspace || ((uintptr_t)workspace & 255u) || workspace_bytes < need)
+        return RTOPK_EWORKSPACE;
+    hipStream_t stream = (hipStream_t)stream_v;
+    const u64 tiles = (d + kAggTile - 1) / kAggTile;
+    u32 *start = static_cast<u32 *>(workspace);
+    const dim3 sgrid((unsigned)((k + 1 + kStartThreads - 1) / kStartThreads), n);
+    k_tile_starts<<<sgrid, kStartThreads, 0, stream>>>(idx, n, k, tiles, start);
+    if (hipGetLastError() != hipSuccess) return RTOPK_EHIP;
+    volatile float step = eta * scale;                  // one binary32 rounding, then negated
+    const unsigned grid = (unsigned)((tiles + kAggWaves - 1) / kAggWaves);
+    k_update<<<grid, kAggThreads, 0, stream>>>(idx, val, n, k, d, tiles, start, -step, omega);
     if (hipGetLastError() != hipSuccess) return RTOPK_EHIP;
     return RTOPK_OK;
 }

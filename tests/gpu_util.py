@@ -66,6 +66,37 @@ def gpu_aggregate(idx: np.ndarray, val: np.ndarray, n: int, d: int) -> np.ndarra
     return out.cpu().numpy()
 
 
+def gpu_aggregate_update(idx: np.ndarray, val: np.ndarray, n: int, d: int, eta: float,
+                         scale: float, omega: np.ndarray, offset: int = 0) -> np.ndarray:
+    """``offset`` (in elements) shifts omega off its 16-byte alignment."""
+    idx = np.ascontiguousarray(idx, np.uint32).reshape(-1)
+    val = np.ascontiguousarray(val, np.float32).reshape(-1)
+    k = idx.size // n
+    ti = torch.from_numpy(idx.view(np.int32)).to(DEV)
+    tv = torch.from_numpy(val).to(DEV)
+    buf = torch.zeros(d + offset, dtype=torch.float32, device=DEV)
+    tw = buf[offset:]
+    tw.copy_(torch.from_numpy(np.ascontiguousarray(omega, np.float32)))
+    ws = torch.empty(rt.aggregate_update_workspace_bytes(d, n, k), dtype=torch.uint8, device=DEV)
+    ws.fill_(0xA5)                                   # whatever the workspace held must not matter
+    rt.aggregate_update(ti, tv, n, k, eta, scale, tw, ws)
+    torch.cuda.synchronize()
+    return tw.cpu().numpy()
+
+
+def assert_update_close(got, idx, val, n, d, eta, scale, omega, want64):
+    """|gpu - ref| <= 1e-6 * (|omega| + |eta scale| sum_w |v_w| / n)."""
+    size = np.zeros(d)
+    np.add.at(size, np.asarray(idx).reshape(-1).astype(np.int64),
+              np.abs(np.asarray(val, np.float64).reshape(-1)) / n)
+    size = np.abs(omega.astype(np.float64)) + abs(eta * scale) * size
+    fin = np.isfinite(omega) & np.isfinite(want64)   # the rest is compared bit for bit elsewhere
+    assert np.all(np.abs(got[fin].astype(np.float64) - want64[fin].astype(np.float64))
+                  <= 1e-6 * size[fin])
+    assert np.array_equal(np.isnan(got), np.isnan(want64))
+    assert np.array_equal(got[~fin & ~np.isnan(got)], want64[~fin & ~np.isnan(got)])
+
+
 def assert_encode_equal(got, want, what=""):
     gi, gv, gm = got[:3]
     wi, wv, wm = want

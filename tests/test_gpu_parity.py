@@ -289,3 +289,110 @@ def test_aggregate_repeated_index_inside_one_message_is_added_again():
     val = np.array([[1, 2, 3, 4, 5, 6], [7, 8, 9, 10, 11, 12]], np.float32) * np.float32(0.1)
     out = u.gpu_aggregate(idx, val, n, d)
     assert np.array_equal(u.bits(out), u.bits(oracle.aggregate_f32(idx, val, n, d)))
+
+
+# --------------------------------------------------------------------------
+# both master lines in one step: omega -= eta * scale * average
+# --------------------------------------------------------------------------
+def _check_update(u, idx, val, n, d, eta, scale, omega, offset=0):
+    got = u.gpu_aggregate_update(idx, val, n, d, eta, scale, omega, offset=offset)
+    u.assert_update_close(got, idx, val, n, d, eta, scale, omega,
+                          oracle.aggregate_update(idx, val, n, d, eta, scale, omega))
+    want32 = oracle.aggregate_update_f32(idx, val, n, d, eta, scale, omega)
+    assert np.array_equal(u.bits(got), u.bits(want32))
+    return got
+
+
+def test_update_special_cases():
+    u = _u()
+    d = 10_000
+    idx = np.array([3, 9, 4096, 9999], np.uint32)
+    val = np.array([1.5, -2.0, 1e-40, 7.0], np.float32)
+    rng = np.random.default_rng(3)
+    omega = rng.standard_normal(d).astype(np.float32)
+    omega[::5] = -0.0
+    omega[7] = np.float32(np.inf)
+    omega.view(np.uint32)[11] = 0x7FA00001          # a signalling NaN nobody touches
+    omega.view(np.uint32)[4097] = 0xFFC12345        # a quiet NaN with a payload, same
+    got = _check_update(u, idx, val, 1, d, 0.25, 1.0, omega)
+    untouched = np.setdiff1d(np.arange(d), idx)
+    assert np.array_equal(u.bits(got[untouched]), u.bits(omega[untouched]))
+    # eta = 0 and a message that cancels leave the weights bit for bit
+    got = u.gpu_aggregate_update(idx, val, 1, d, 0.0, 1.0, omega)
+    assert np.array_equal(u.bits(got), u.bits(omega))
+    cidx = np.array([[5, 4100], [5, 4100]], np.uint32)
+    cval = np.array([[1.5, -2.0], [-1.5, 2.0]], np.float32)
+    got = u.gpu_aggregate_update(cidx, cval, 2, d, 0.5, 3.0, omega)
+    assert np.array_equal(u.bits(got), u.bits(omega))
+    # the single-rounding case: 1 - (1 + 2^-12)^2 needs the unrounded product
+    v = np.float32(1.0 + 2.0 ** -12)
+    got = u.gpu_aggregate_update(np.array([2], np.uint32), np.array([v]), 1, 3, float(v), 1.0,
+                                 np.ones(3, np.float32))
+    assert float(got[2]) == -(2.0 ** -11 + 2.0 ** -24) and got[0] == 1 and got[1] == 1
+
+
+@pytest.mark.parametrize("d,n,k,offset", [(5000, 3, 100, 0), (4096 * 5 + 3, 16, 700, 0),
+                                          (1_000_003, 8, 10_000, 0), (1_000_003, 5, 300, 1),
+                                          (70, 70, 5, 0), (100_000, 130, 50, 0), (1, 1, 1, 0),
+                                          (2048, 2, 2048, 0), (300_000, 8, 3, 3)])
+def test_update_random_messages(d, n, k, offset):
+    u = _u()
+    rng = np.random.default_rng(d + n)
+    idx = np.stack([np.sort(rng.choice(d, k, replace=False)) for _ in range(n)]).astype(np.uint32)
+    val = (rng.standard_normal((n, k)) * 10.0 ** rng.uniform(-3, 1, (n, k))).astype(np.float32)
+    omega = rng.standard_normal(d).astype(np.float32)
+    eta, scale = float(np.float32(0.05)), float(np.float32(n * 1.0))
+    print(f"update d={d} n={n} k={k} offset={offset}", flush=True)
+    _check_update(u, idx, val, n, d, eta, scale, omega, offset=offset)
+
+
+def test_update_clustered_messages_leave_far_tiles_alone():
+    # all entries inside two narrow ranges far apart; everything between them
+    # and around them must come back bit for bit
+    u = _u()
+    rng = np.random.default_rng(17)
+    d, n, k = 3_000_000, 8, 4000
+    idx = np.stack([np.concatenate([
+        np.sort(rng.choice(np.arange(700_000, 706_000), k // 2, replace=False)),
+        np.sort(rng.choice(np.arange(2_900_000, 2_999_999), k // 2, replace=False))])
+        for _ in range(n)]).astype(np.uint32)
+    val = rng.standard_normal((n, k)).astype(np.float32)
+    omega = rng.standard_normal(d).astype(np.float32)
+    got = _check_update(u, idx, val, n, d, 0.1, 5.0, omega)
+    far = np.ones(d, bool)
+    far[idx.reshape(-1)] = False
+    assert np.array_equal(u.bits(got[far]), u.bits(omega[far]))
+
+
+def test_update_repeated_index_inside_one_message_is_added_again():
+    u = _u()
+    d, n = 9000, 2
+    idx = np.array([[5, 5, 5, 4100, 4100, 8999], [5, 6, 6, 4100, 8999, 8999]], np.uint32)
+    val = np.array([[1, 2, 3, 4, 5, 6], [7, 8, 9, 10, 11, 12]], np.float32) * np.float32(0.1)
+    omega = np.linspace(-1, 1, d).astype(np.float32)
+    _check_update(u, idx, val, n, d, 0.3, 1.0, omega)
+
+
+def test_training_loop_of_algorithm_1_on_the_device_matches_the_oracle():
+    """Nodes encode, the master averages and steps; three rounds, weights and
+    residuals carried on both sides."""
+    u = _u()
+    d, r, k, n, eta = 200_003, 2000, 400, 5, 0.1
+    rng = np.random.default_rng(23)
+    w_gpu = rng.standard_normal(d).astype(np.float32)
+    w_ref = w_gpu.copy()
+    workers = [u.GpuWorker(d, r, k) for _ in range(n)]
+    res = [np.zeros(d, np.float32) for _ in range(n)]
+    for t in range(3):
+        mi, mv = [], []
+        for w in range(n):
+            g = (rng.standard_normal(d) * 0.01 + 0.001 * w_ref).astype(np.float32)
+            gi, gv, _ = workers[w].encode(g, 42 + w, t)
+            oi, ov, res[w] = oracle.encode(g, res[w], r, k, 42 + w, t)
+            assert np.array_equal(gi, oi) and np.array_equal(u.bits(gv), u.bits(ov))
+            mi.append(oi)
+            mv.append(ov)
+        ai, av = np.stack(mi), np.stack(mv)
+        w_gpu = u.gpu_aggregate_update(ai, av, n, d, eta, r / k, w_gpu)
+        w_ref = oracle.aggregate_update_f32(ai, av, n, d, eta, r / k, w_ref)
+        assert np.array_equal(u.bits(w_gpu), u.bits(w_ref))

@@ -480,3 +480,16 @@ def test_aggregate_update_rejects_out_of_range_index_and_wrong_length():
         oracle.aggregate_update(np.array([4], np.uint32), one, 1, 4, 0.1, 1.0, np.zeros(4, np.float32))
     with pytest.raises(ValueError):
         oracle.aggregate_update(np.array([1], np.uint32), one, 1, 4, 0.1, 1.0, np.zeros(3, np.float32))
+
+
+def test_aggregate_update_copies_coordinates_the_average_does_not_move():
+    # nobody sent coordinate 1 and the two entries at 2 cancel: both keep their
+    # bits, a signalling not-a-number and a negative zero included
+    omega = np.array([1.0, 0.0, -0.0, 4.0], np.float32)
+    omega.view(np.uint32)[1] = 0x7FA00001
+    idx = np.array([0, 2, 2, 3], np.uint32)
+    val = np.array([1.0, 2.5, -2.5, 2.0], np.float32)
+    for fn in (oracle.aggregate_update, oracle.aggregate_update_f32):
+        out = fn(idx, val, 2, 4, 0.5, 1.0, omega)
+        assert list(bits(out)) == [bits(np.float32(0.75)), 0x7FA00001, 0x80000000,
+                                   bits(np.float32(3.5))]
