@@ -209,6 +209,25 @@ def main() -> int:
     fused_ms = [ev.elapsed_ms(a, b) for row in fused_pairs for (a, b) in row]
     ev.close()
 
+    # ---- outside the timed region: the master's fused update on the last
+    #      step's messages (averaging and weight step in one call) ------------
+    upd_ws = torch.empty(rt.aggregate_update_workspace_bytes(d, n, k), dtype=torch.uint8,
+                         device=dev)
+    omegas = [torch.randn(d, dtype=torch.float32, device=dev) for _ in range(4)]
+    upd = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+    upd_calls = 5 * len(omegas)
+    with torch.cuda.stream(streams[0]):
+        for om in omegas:
+            rt.aggregate_update(idx, val, n, k, 0.1, r / k, om, upd_ws, streams[0])
+        upd[0].record(streams[0])
+        for c in range(upd_calls):
+            rt.aggregate_update(idx, val, n, k, 0.1, r / k, omegas[c % len(omegas)], upd_ws,
+                                streams[0])
+        upd[1].record(streams[0])
+    torch.cuda.synchronize()
+    upd_ms_call = upd[0].elapsed_time(upd[1]) / upd_calls
+    del omegas
+
     if args.copy_calibration > 0:
         src = grads[0][0]
         for _ in range(args.copy_calibration):
@@ -247,6 +266,7 @@ def main() -> int:
                                             / HBM_PEAK_GBPS, 2),
         "aggregate_GBps": round(4.0 * d / (agg_ms_call * 1e-3) / 1e9, 2),
         "aggregate_ms_per_call": round(agg_ms_call, 4),
+        "aggregate_update_ms_per_call": round(upd_ms_call, 4),
         "wall_ms_per_step": round((t_wall1 - t_wall0) * 1e3 / K, 4),
         "last_encode": {"path": stats["path"], "superset": stats["superset_size"],
                         "boundary_list": stats["boundary_list_size"],

@@ -27,7 +27,11 @@
 // entry's position into a [tile][worker] table for all tiles in between.
 // The second kernel reads its tile's row and the next one, leaves at once if
 // the tile is empty, and otherwise adds the entries into its LDS tile in
-// worker order, then updates the weights at the non-zero positions.
+// worker order, then updates the weights at the non-zero positions. With up
+// to 16 workers and up to 64 entries per worker in the tile, every entry
+// stays in a register of one lane from the load to the store: the weight at
+// its index is fetched while the LDS sums are formed, and the first entry to
+// swap the finished sum out of LDS writes the new weight.
 #include "rtopk_common.h"
 #include "../../include/rtopk.h"
 
@@ -233,6 +237,7 @@ k_tile_starts(const u32 *__restrict__ idx, u32 n, u64 k, u64 tiles, u32 *__restr
 // omega[i]) wherever the sum of what the workers sent for i is not zero.
 // ---------------------------------------------------------------------------
 constexpr u32 kDenseTileEntries = 512;     // from here on the whole tile is read and written
+constexpr int kUpdateAhead = 16;           // workers whose entries are held in registers together
 
 __global__ void __launch_bounds__(kAggThreads)
 k_update(const u32 *__restrict__ idx, const float *__restrict__ val, u32 n, u64 k, u64 d,
@@ -250,6 +255,82 @@ k_update(const u32 *__restrict__ idx, const float *__restrict__ val, u32 n, u64 
     const float rn = 1.0f / fn;
     bool cleared = false;
     u32 entries = 0;
+    auto step = [&](float sum, float w) {
+        const float avg = n_pow2 ? sum * rn : sum / fn;
+        return fmaf(neg_step, avg, w);
+    };
+
+    // ---- few workers with at most 64 entries each in this tile (the usual
+    //      case): every entry stays in a register of "its" lane. The weight at
+    //      the entry's index is fetched while the sums are formed in LDS;
+    //      afterwards every entry swaps a zero into its LDS word, and the one
+    //      that gets the sum back (the first to arrive) writes the weight. ----
+    if (n <= kUpdateAhead) {
+        u32 lo = 0, cnt = 0;
+        if (lane < n) {
+            u64 a = start[t * n + lane], b = start[(t + 1) * n + lane];
+            if (b > k) b = k;
+            if (a > b) a = b;
+            lo = (u32)a;
+            cnt = (u32)(b - a);
+        }
+        if (__ballot(cnt != 0u) == 0ull) return;           // nobody sent anything in this tile
+        if (__ballot(cnt > (u32)kWave) == 0ull) {
+            for (int i = lane; i < kAggTile / 4; i += kWave)
+                reinterpret_cast<float4 *>(tile)[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            u32 ei[kUpdateAhead];
+            float ev[kUpdateAhead], ew[kUpdateAhead];
+            bool in[kUpdateAhead];
+#pragma unroll
+            for (int q = 0; q < kUpdateAhead; ++q) {
+                in[q] = false;
+                ei[q] = 0xFFFFFFFFu;
+                ev[q] = 0.0f;
+                if ((u32)q < n) {
+                    const u32 from = (u32)__builtin_amdgcn_readlane((int)lo, q);
+                    const u32 c = (u32)__builtin_amdgcn_readlane((int)cnt, q);
+                    if (lane < c) {
+                        ei[q] = idx[(u64)q * k + from + lane];
+                        ev[q] = val[(u64)q * k + from + lane];
+                    }
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < kUpdateAhead; ++q) {
+                // the range check keeps a list that is not sorted (a broken
+                // precondition) inside the LDS tile
+                in[q] = (u64)ei[q] >= tile_base && (u64)ei[q] < tile_end;
+                ew[q] = in[q] ? omega[ei[q]] : 0.0f;
+            }
+#pragma unroll
+            for (int q = 0; q < kUpdateAhead; ++q) {
+                if ((u32)q < n) {
+                    // repeated indices inside one message must be added in position order
+                    const u32 mine = ei[q];
+                    const float v = ev[q];
+                    const bool inside = in[q];
+                    const u32 left = __shfl_up(mine, 1, kWave);
+                    const bool dup = inside && lane > 0 && left == mine;
+                    if (!__any(dup)) {
+                        if (inside) tile[mine - tile_base] += v;
+                    } else {
+                        for (u64 rest = __ballot(inside); rest; rest &= rest - 1) {
+                            const int src = __ffsll((unsigned long long)rest) - 1;
+                            if ((int)lane == src) tile[mine - tile_base] += v;
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < kUpdateAhead; ++q) {
+                if ((u32)q < n && in[q]) {
+                    const float sum = atomicExch(&tile[ei[q] - tile_base], 0.0f);
+                    if (sum != 0.0f) omega[ei[q]] = step(sum, ew[q]);
+                }
+            }
+            return;
+        }
+    }
 
     for (u32 w0 = 0; w0 < n; w0 += kWave) {
         const u32 nw = n - w0 < (u32)kWave ? n - w0 : (u32)kWave;
@@ -317,10 +398,6 @@ k_update(const u32 *__restrict__ idx, const float *__restrict__ val, u32 n, u64 
     }
     if (!cleared) return;                               // nobody sent anything in this tile
 
-    auto step = [&](float sum, float w) {
-        const float avg = n_pow2 ? sum * rn : sum / fn;
-        return fmaf(neg_step, avg, w);
-    };
     constexpr int kVecs = kAggTile / 4 / kWave;         // float4 per lane
     float4 s4[kVecs];
 #pragma unroll
