@@ -33,18 +33,22 @@ class GpuWorker:
         self.ws.fill_(0xA5)
 
     def encode(self, g: np.ndarray, seed: int, step: int, check_stats: bool = True,
-               force: int = 0):
+               force: int = 0, r: int = None, k: int = None):
+        """``r``/``k`` override the sizes of this call only (they must not need
+        more workspace or a longer message than the worker was built for)."""
+        r = self.r if r is None else r
+        k = self.k if k is None else k
+        assert k <= self.k and rt.encode_workspace_bytes(self.d, r, k) <= self.ws.numel()
         self.grad.copy_(torch.from_numpy(np.ascontiguousarray(g, np.float32)))
         if force:
             rt.force_next_encode(force)
-        rt.encode(self.grad, self.residual, self.r, self.k, seed, step, self.idx, self.val,
-                  self.ws)
+        rt.encode(self.grad, self.residual, r, k, seed, step, self.idx, self.val, self.ws)
         st = rt.encode_stats(self.ws)
         if check_stats:
             assert st["error_flags"] == 0, st
         self.stats = st
-        return (self.idx.cpu().numpy().view(np.uint32).copy(),
-                self.val.cpu().numpy().copy(),
+        return (self.idx[:k].cpu().numpy().view(np.uint32).copy(),
+                self.val[:k].cpu().numpy().copy(),
                 self.residual.cpu().numpy().copy())
 
 

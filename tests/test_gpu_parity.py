@@ -396,3 +396,32 @@ def test_training_loop_of_algorithm_1_on_the_device_matches_the_oracle():
         w_gpu = u.gpu_aggregate_update(ai, av, n, d, eta, r / k, w_gpu)
         w_ref = oracle.aggregate_update_f32(ai, av, n, d, eta, r / k, w_ref)
         assert np.array_equal(u.bits(w_gpu), u.bits(w_ref))
+
+
+# --------------------------------------------------------------------------
+# per-step (r, k): the warm-up of the experiments section raises the sparsity
+# step by step; one worker, one workspace sized for the densest step
+# --------------------------------------------------------------------------
+def test_warmup_schedule_of_r_and_k_with_one_workspace():
+    u = _u()
+    wl = Workload(3, d=400_003)
+    d, n = wl.d, 5
+    kept = [0.25, 0.0625, 0.015625, 0.004, 0.001, 0.001]       # fraction of d sent per step
+    sched = []
+    for f in kept:
+        k = int(np.ceil(f * d))
+        sched.append((min(d, n * k), k))                        # k / r = 1 / n, capped at d
+    r_ws, k_ws = max(sched, key=lambda rk: rt_ws(u, d, *rk))
+    w = u.GpuWorker(d, r_ws, max(k for _, k in sched))
+    assert all(rt_ws(u, d, r, k) <= w.ws.numel() for r, k in sched)
+    res = np.zeros(d, np.float32)
+    for t, (r, k) in enumerate(sched):
+        g = wl.gradient(0, t)
+        print(f"schedule step {t}: r={r} k={k}", flush=True)
+        got = w.encode(g, 42, t, r=r, k=k)
+        oi, ov, res = oracle.encode(g, res, r, k, 42, t)
+        u.assert_encode_equal(got, (oi, ov, res), f"schedule t={t} r={r} k={k}")
+
+
+def rt_ws(u, d, r, k):
+    return u.rt.encode_workspace_bytes(d, r, k)
