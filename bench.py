@@ -19,8 +19,8 @@ Prints ONE JSON line:
                (n * 4d bytes per step / seconds per step), GB/s
   roofline   = the dominant kernel (fused residual add + candidate append):
                algorithmic bytes per launch (12 d) over its mean duration,
-               measured with HIP events on the launch stream, against the
-               8 TB/s HBM peak
+               measured with HIP events on the launch stream (one launch per
+               step by default, see --trace-stride), against the 8 TB/s HBM peak
   cpu_baseline = the CPU oracle, one thread, timed on a bounded sample of the
                same workload
 """
@@ -44,7 +44,7 @@ METRIC = "rTop-k encode gradient GB/s and % of HBM peak at d=25.6M; aggregate GB
 # two rocprofv3 --pmc runs, FETCH_SIZE then WRITE_SIZE, each scaled by a device
 # copy of known size in the same run; the summary and the commands are in
 # profiles/k_fused_cfg3_hbm_traffic.txt. Only valid for the default workload.
-DOMINANT_KERNEL_TRAFFIC_BYTES = 311_444_277
+DOMINANT_KERNEL_TRAFFIC_BYTES = 311_237_687
 
 
 class HipEvents:
@@ -120,6 +120,11 @@ def main() -> int:
     ap.add_argument("--streams", type=int, default=1,
                     help="HIP streams the simulated workers are dealt to (each with its own "
                          "workspace); 1 = strictly one kernel at a time")
+    ap.add_argument("--trace-stride", type=int, default=0, metavar="N",
+                    help="bracket every N-th launch of the dominant kernel with HIP events "
+                         "(default: the number of workers, i.e. one launch per step, a "
+                         "different worker each step; 1 = every launch). The two event "
+                         "records cost the stream a few microseconds per traced launch.")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
                     help="after the timed region, also run N plain device copies of d floats "
                          "(4d bytes read + 4d bytes written each): a kernel of known HBM "
@@ -174,7 +179,7 @@ def main() -> int:
             phase[0].record(streams[0])
         for w in range(n):
             s = w % S
-            if trace is not None:
+            if trace is not None and trace[w] is not None:
                 rt.trace_next_encode(rt.STAGES["fused"], *trace[w])
             rt.encode(grads[t][w], residual[w], r, k, philox_seed_for_worker(w), t,
                       idx[w * k:(w + 1) * k], val[w * k:(w + 1) * k], ws[s], streams[s])
@@ -195,7 +200,10 @@ def main() -> int:
 
     # ---- timed region: K steps, events on the launch streams ---------------
     ev = HipEvents()
-    fused_pairs = [[(ev.new(), ev.new()) for _ in range(n)] for _ in range(K)]
+    stride = args.trace_stride if args.trace_stride > 0 else n
+    offset = 0 if stride == 1 else 1             # n | stride would always pick worker 0
+    fused_pairs = [[(ev.new(), ev.new()) if (s_ * (n + offset) + w) % stride == 0 else None
+                    for w in range(n)] for s_ in range(K)]
     phase = [tuple(torch.cuda.Event(enable_timing=True) for _ in range(3)) for _ in range(K)]
     torch.cuda.synchronize()
     t_wall0 = time.perf_counter()
@@ -206,7 +214,7 @@ def main() -> int:
     total_ms = phase[0][0].elapsed_time(phase[-1][2])
     enc_ms_call = sum(p[0].elapsed_time(p[1]) for p in phase) / (K * n)
     agg_ms_call = sum(p[1].elapsed_time(p[2]) for p in phase) / K
-    fused_ms = [ev.elapsed_ms(a, b) for row in fused_pairs for (a, b) in row]
+    fused_ms = [ev.elapsed_ms(*pair) for row in fused_pairs for pair in row if pair is not None]
     ev.close()
 
     # ---- outside the timed region: the master's fused update on the last
