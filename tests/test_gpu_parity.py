@@ -334,7 +334,11 @@ def test_update_special_cases():
 @pytest.mark.parametrize("d,n,k,offset", [(5000, 3, 100, 0), (4096 * 5 + 3, 16, 700, 0),
                                           (1_000_003, 8, 10_000, 0), (1_000_003, 5, 300, 1),
                                           (70, 70, 5, 0), (100_000, 130, 50, 0), (1, 1, 1, 0),
-                                          (2048, 2, 2048, 0), (300_000, 8, 3, 3)])
+                                          (2048, 2, 2048, 0), (300_000, 8, 3, 3),
+                                          # many entries per tile: the scanning path, with
+                                          # whole-tile vector accesses, misaligned, ragged end
+                                          (8192, 3, 5000, 0), (8192, 3, 5000, 1),
+                                          (2048 * 2 + 100, 2, 2000, 0), (50_000, 20, 9000, 0)])
 def test_update_random_messages(d, n, k, offset):
     u = _u()
     rng = np.random.default_rng(d + n)
