@@ -67,7 +67,7 @@ constexpr u32 kCoarseShift = 23;              // coarse bins above them: the 8 e
 constexpr u32 kCoarseBins = 256;
 constexpr u32 kMaxBins = kMaxFineBins + kCoarseBins;
 constexpr u32 kMaxFusedBlocks = 1024;         // rows of per-workgroup histograms
-constexpr u32 kHistRows = 32;                 // rows left after the first reduction step
+constexpr u32 kHistRows = 16;                 // rows left after the first reduction step
 
 constexpr u32 kSampleLoc = 16384;             // sampled locations, 4 consecutive elements each
 constexpr u32 kSampleThreads = 256;
@@ -725,8 +725,30 @@ k_pick(const u32 *__restrict__ hist, Geom g, EncodeCtl *ctl)
     __shared__ u32 scan_lds[kPickThreads / kWave + 1];
     __shared__ u32 bin_s;
     __shared__ u32 before_s;
+    __shared__ u32 total[kMaxBins];
     const Bins bins = ctl->bins;
     const u32 nbins = bins.nfine + kCoarseBins;
+    // the rows are added up in LDS: consecutive threads read consecutive words of the
+    // row-major array, every thread a few of them, all loads in flight together
+    for (u32 b = threadIdx.x; b < nbins; b += kPickThreads) total[b] = 0u;
+    if (threadIdx.x == 0) { bin_s = kMaxBins; before_s = 0u; }
+    lds_barrier();
+    const u32 words = nbins * kHistRows;
+    constexpr u32 kAhead = 8;
+    for (u32 i0 = threadIdx.x; i0 < words; i0 += kAhead * kPickThreads) {
+        u32 v[kAhead];
+#pragma unroll
+        for (u32 q = 0; q < kAhead; ++q) {
+            const u32 i = i0 + q * kPickThreads;
+            v[q] = i < words ? hist[i] : 0u;
+        }
+#pragma unroll
+        for (u32 q = 0; q < kAhead; ++q) {
+            const u32 i = i0 + q * kPickThreads;
+            if (i < words && v[q]) atomicAdd(&total[i % nbins], v[q]);
+        }
+    }
+    __syncthreads();
     // thread t owns the bins at walking positions kPickPer*t .. (bin nbins-1 comes first)
     const u32 first = threadIdx.x * kPickPer;
     u32 c[kPickPer];
@@ -734,14 +756,9 @@ k_pick(const u32 *__restrict__ hist, Geom g, EncodeCtl *ctl)
 #pragma unroll
     for (u32 q = 0; q < kPickPer; ++q) {
         const u32 pos = first + q;
-        c[q] = 0u;
-        if (pos < nbins) {
-#pragma unroll
-            for (u32 row = 0; row < kHistRows; ++row) c[q] += hist[row * nbins + (nbins - 1u - pos)];
-        }
+        c[q] = pos < nbins ? total[nbins - 1u - pos] : 0u;
         mine += c[q];
     }
-    if (threadIdx.x == 0) { bin_s = kMaxBins; before_s = 0u; }
     const u32 before = block_exclusive_sum(mine, scan_lds);   // candidates number less than 2^32
     const u64 need = g.r;
     if ((u64)before < need && need <= (u64)before + mine) {
@@ -1287,12 +1304,14 @@ struct StageScope {
     }
 };
 
-// Workgroups of the streaming kernel: as many as the device holds at once, at
-// most three per compute unit (all start together and share the chunks
-// evenly, so none waits for a slot). A property of the device and of the
-// compiled kernel, looked up at the first call on the device.
+// Workgroups of the streaming kernel: one per compute unit (all start
+// together and share the chunks evenly, so none waits for a slot). Eight
+// wavefronts per compute unit with 8 x 16 bytes in flight per lane saturate
+// HBM; two or three workgroups per unit stream no faster, leave three times
+// the histogram rows to reduce and less room for kernels of other streams.
+// The count of units is looked up at the first call on the device.
 constexpr int kMaxDevices = 64;
-constexpr int kFusedBlocksPerCU = 3;
+constexpr int kFusedBlocksPerCU = 1;
 std::mutex g_device_mutex;
 unsigned g_fused_grid[kMaxDevices];
 
