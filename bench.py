@@ -46,7 +46,7 @@ METRIC = "rTop-k encode gradient GB/s and % of HBM peak at d=25.6M; aggregate GB
 # two rocprofv3 --pmc runs, FETCH_SIZE then WRITE_SIZE, each scaled by a device
 # copy of known size in the same run; the summary and the commands are in
 # profiles/k_fused_cfg3_hbm_traffic.txt. Only valid for the default workload.
-DOMINANT_KERNEL_TRAFFIC_BYTES = 311_237_687
+DOMINANT_KERNEL_TRAFFIC_BYTES = 309_655_484
 
 
 class HipEvents:
