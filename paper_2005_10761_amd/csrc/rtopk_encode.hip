@@ -322,7 +322,9 @@ __device__ __forceinline__ u64 stratum_start(const Geom &g, u32 j)
 {
     // strata of (almost) equal length; only monotonicity and the two ends matter
     if (j >= g.L) return g.d;
-    const u64 x = (u64)((double)g.d * (double)j / (double)g.L);
+    static_assert((kSampleLoc & (kSampleLoc - 1)) == 0, "the usual count of strata is a power of two");
+    const u64 x = g.L == kSampleLoc ? (g.d * (u64)j) / kSampleLoc     // d * j < 2^46; a shift
+                                    : (u64)((double)g.d * (double)j / (double)g.L);
     return x < g.d ? x : g.d;
 }
 
@@ -366,7 +368,12 @@ k_sample(const float *__restrict__ grad, const float *__restrict__ residual, Geo
 __global__ void __launch_bounds__(kEstThreads)
 k_estimate(const u32 *__restrict__ samples, Geom g, EncodeCtl *ctl)
 {
-    __shared__ u32 h[4096];
+    // One compute unit looks at 65,536 samples: the work per sample is what this
+    // kernel costs, so the two passes over them are a handful of instructions per
+    // 16-byte group. A sample is a magnitude pattern (< 2^31) or kNoSample
+    // (all ones): as signed integers the missing ones are -1, below every real one.
+    __shared__ u32 h_max[4096];                           // buckets of the per-thread maxima
+    __shared__ u32 h[4096];                               // buckets of the samples that matter
     __shared__ u32 scan_lds[kEstThreads / kWave + 1];
     __shared__ u32 bin_s[3], before_s[3];
     const u32 tid = threadIdx.x;
@@ -375,17 +382,30 @@ k_estimate(const u32 *__restrict__ samples, Geom g, EncodeCtl *ctl)
     uint4 v[kVecs];
 #pragma unroll
     for (u32 q = 0; q < kVecs; ++q) v[q] = s4[q * kEstThreads + tid];
-    for (u32 b = tid; b < 4096u; b += kEstThreads) h[b] = 0u;
+    for (u32 b = tid; b < 4096u; b += kEstThreads) { h[b] = 0u; h_max[b] = 0u; }
     if (tid < 3u) { bin_s[tid] = 0u; before_s[tid] = 0u; }
-    u32 nvalid = 0, tmax = 0;
-    auto look = [&](u32 m) {
-        if (m == kNoSample) return;
-        ++nvalid;
-        tmax = m > tmax ? m : tmax;
-    };
+    auto smax = [](int a, int b) { return a > b ? a : b; };
+    int gmax[kVecs];                                      // largest of each group, -1 if none
+    int tmax = -1;
 #pragma unroll
-    for (u32 q = 0; q < kVecs; ++q) { look(v[q].x); look(v[q].y); look(v[q].z); look(v[q].w); }
-    const u32 n = block_sum(nvalid, scan_lds);            // also orders the clearing of h
+    for (u32 q = 0; q < kVecs; ++q) {
+        gmax[q] = smax(smax((int)v[q].x, (int)v[q].y), smax((int)v[q].z, (int)v[q].w));
+        tmax = smax(tmax, gmax[q]);
+    }
+    // Number of samples: four per location once every stratum is longer than
+    // four elements; counted otherwise (short vectors).
+    u32 n;
+    if ((u64)g.L * 5ull <= g.d) {
+        n = 4u * g.L;
+        lds_barrier();                                    // orders the clearing of the histograms
+    } else {
+        u32 nvalid = 0;
+#pragma unroll
+        for (u32 q = 0; q < kVecs; ++q)
+            nvalid += (v[q].x != kNoSample) + (v[q].y != kNoSample) + (v[q].z != kNoSample) +
+                      (v[q].w != kNoSample);
+        n = block_sum(nvalid, scan_lds);
+    }
 
     const float p = (float)((double)g.r / (double)g.d);
     const float np = (float)n * p;
@@ -400,23 +420,25 @@ k_estimate(const u32 *__restrict__ samples, Geom g, EncodeCtl *ctl)
     // maxima is not above it: buckets below that maximum's bucket need no count.
     u32 cut_bucket = 0;
     if (s_lo < kEstThreads) {
-        if (nvalid) atomicAdd(&h[tmax >> 19], 1u);
-        __syncthreads();
+        if (tmax >= 0) atomicAdd(&h_max[(u32)tmax >> 19], 1u);
+        lds_barrier();
         const u32 want_cut[1] = {s_lo};
-        block_pick_desc<4, 1>(h, want_cut, &bin_s[2], &before_s[2], scan_lds);
-        __syncthreads();
+        block_pick_desc<4, 1>(h_max, want_cut, &bin_s[2], &before_s[2], scan_lds);
+        lds_barrier();
         cut_bucket = bin_s[2];                     // stays 0 when fewer than s_lo threads hold samples
-        for (u32 b = tid; b < 4096u; b += kEstThreads) h[b] = 0u;
-        __syncthreads();
     }
+    const int cut = (int)(cut_bucket << 19);       // >= 0: missing samples never pass
     u32 nzero = 0;
     auto count = [&](u32 m) {
-        if (m == kNoSample || (m >> 19) < cut_bucket) return;
+        if ((int)m < cut) return;
         if (m == 0u) ++nzero;                     // exact zeros come in long runs: count them aside
         else atomicAdd(&h[m >> 19], 1u);
     };
 #pragma unroll
-    for (u32 q = 0; q < kVecs; ++q) { count(v[q].x); count(v[q].y); count(v[q].z); count(v[q].w); }
+    for (u32 q = 0; q < kVecs; ++q) {
+        if (gmax[q] < cut) continue;               // nearly every group
+        count(v[q].x); count(v[q].y); count(v[q].z); count(v[q].w);
+    }
     nzero = wave_sum(nzero);
     if (lane_id() == 0 && nzero) atomicAdd(&h[0], nzero);
     __syncthreads();
