@@ -83,6 +83,31 @@ int rtopk_encode(const float *grad, float *residual,
                  void *workspace, uint64_t workspace_bytes, void *stream);
 
 /*
+ * The same step of Algorithm 1 for n independent vectors of equal sizes in
+ * one call: the n workers that Algorithm 1's node loop runs over (when one
+ * device holds several of them), or the tensors of one model. Member i is
+ * computed exactly as rtopk_encode(grad[i], residual[i], d, r, k, seed[i],
+ * step, out_idx[i], out_val[i], ...) computes it, bit for bit; the members
+ * only share kernel launches (up to 16 per launch), so the short kernels of
+ * all members run side by side and the streaming kernel does not drain in
+ * between.
+ *
+ * grad, residual, out_idx, out_val   HOST arrays of n device pointers each,
+ *            read during the call; every pointer as for rtopk_encode. No two
+ *            members may share or overlap a residual or an output buffer.
+ * seed       HOST array of n seeds
+ * workspace  device, 256-byte aligned, >= n * rtopk_encode_workspace_bytes(d,r,k);
+ *            member i uses the i-th slice of that size, and rtopk_encode_stats
+ *            on the slice's address reports on member i
+ */
+int rtopk_encode_batch(uint32_t n,
+                       const float *const *grad, float *const *residual,
+                       uint64_t d, uint64_t r, uint64_t k,
+                       const uint64_t *seed, uint64_t step,
+                       uint32_t *const *out_idx, float *const *out_val,
+                       void *workspace, uint64_t workspace_bytes, void *stream);
+
+/*
  * Master step of Algorithm 1: out = (1/n) * sum_{w<n} message_w as a dense
  * vector. Every coordinate is divided by n, whether or not all workers sent
  * it; coordinates nobody sent are +0. Sums are formed in binary32 starting

@@ -14,6 +14,7 @@ _LIB_PATH = os.path.join(_HERE, "librtopk.so")
 _LIB: Optional[ctypes.CDLL] = None
 
 EXPORTS = ("rtopk_encode_workspace_bytes", "rtopk_aggregate_workspace_bytes", "rtopk_encode",
+           "rtopk_encode_batch",
            "rtopk_aggregate", "rtopk_aggregate_update", "rtopk_aggregate_update_workspace_bytes",
            "rtopk_encode_stats", "rtopk_trace_next_encode",
            "rtopk_force_next_encode", "rtopk_strerror", "rtopk_version")
@@ -53,6 +54,8 @@ def load_library() -> ctypes.CDLL:
     L.rtopk_aggregate_workspace_bytes.restype = ctypes.c_int
     L.rtopk_encode.argtypes = [vp, vp, u64, u64, u64, u64, u64, vp, vp, vp, u64, vp]
     L.rtopk_encode.restype = ctypes.c_int
+    L.rtopk_encode_batch.argtypes = [u32, vp, vp, u64, u64, u64, vp, u64, vp, vp, vp, u64, vp]
+    L.rtopk_encode_batch.restype = ctypes.c_int
     L.rtopk_aggregate.argtypes = [vp, vp, u32, u64, u64, vp, vp, u64, vp]
     L.rtopk_aggregate.restype = ctypes.c_int
     L.rtopk_aggregate_update_workspace_bytes.argtypes = [u64, u32, u64, ctypes.POINTER(u64)]
@@ -133,6 +136,35 @@ def encode(grad: torch.Tensor, residual: torch.Tensor, r: int, k: int, seed: int
         workspace.numel() * workspace.element_size(), _stream_handle(stream))
     if rc:
         raise RtopkError(rc, "rtopk_encode")
+
+
+def encode_batch(grads, residuals, r: int, k: int, seeds, step: int, out_idx, out_val,
+                 workspace: torch.Tensor, stream=None) -> None:
+    """rtopk_encode_batch: one node-side step of Algorithm 1 for every member of
+    a list of equally sized vectors, in shared kernel launches. ``grads``,
+    ``residuals``, ``out_idx``, ``out_val`` are sequences of tensors (as for
+    :func:`encode`), ``seeds`` a sequence of ints; ``workspace`` holds
+    ``len(grads)`` slices of ``encode_workspace_bytes(d, r, k)`` bytes."""
+    n = len(grads)
+    if n < 1 or not (len(residuals) == len(seeds) == len(out_idx) == len(out_val) == n):
+        raise ValueError("grads, residuals, seeds, out_idx, out_val must have the same length >= 1")
+    d = grads[0].numel()
+    for g, m, oi, ov in zip(grads, residuals, out_idx, out_val):
+        _need(g, torch.float32, "grad")
+        _need(m, torch.float32, "residual")
+        _need(oi, torch.int32, "out_idx")
+        _need(ov, torch.float32, "out_val")
+        if g.numel() != d or m.numel() != d or oi.numel() < k or ov.numel() < k:
+            raise ValueError("every member needs d gradient and residual elements and k outputs")
+    vp_arr = ctypes.c_void_p * n
+    seeds_arr = (ctypes.c_uint64 * n)(*[s & (2**64 - 1) for s in seeds])
+    rc = load_library().rtopk_encode_batch(
+        n, vp_arr(*[_ptr(t) for t in grads]), vp_arr(*[_ptr(t) for t in residuals]), d, r, k,
+        seeds_arr, step & (2**64 - 1), vp_arr(*[_ptr(t) for t in out_idx]),
+        vp_arr(*[_ptr(t) for t in out_val]), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if rc:
+        raise RtopkError(rc, "rtopk_encode_batch")
 
 
 def aggregate(idx: torch.Tensor, val: torch.Tensor, n: int, k: int, out: torch.Tensor,

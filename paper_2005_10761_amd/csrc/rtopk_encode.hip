@@ -328,8 +328,8 @@ __device__ __forceinline__ u64 stratum_start(const Geom &g, u32 j)
     return x < g.d ? x : g.d;
 }
 
-__global__ void __launch_bounds__(kSampleThreads)
-k_sample(const float *__restrict__ grad, const float *__restrict__ residual, Geom g,
+__device__ __forceinline__ void
+sample_body(const float *__restrict__ grad, const float *__restrict__ residual, Geom g,
          u32 *__restrict__ zero_base, u32 zero_words, u32 *__restrict__ samples)
 {
     const u32 j = blockIdx.x * kSampleThreads + threadIdx.x;
@@ -365,8 +365,8 @@ k_sample(const float *__restrict__ grad, const float *__restrict__ residual, Geo
 // that holds the sample of rank np - 6 sd - 8 (fewer than r entries lie
 // above it).
 // ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(kEstThreads)
-k_estimate(const u32 *__restrict__ samples, Geom g, EncodeCtl *ctl)
+__device__ __forceinline__ void
+estimate_body(const u32 *__restrict__ samples, Geom g, EncodeCtl *ctl)
 {
     // One compute unit looks at 65,536 samples: the work per sample is what this
     // kernel costs, so the two passes over them are a handful of instructions per
@@ -518,8 +518,8 @@ constexpr u32 kFusedThreads = 512;
 constexpr u32 kFusedWaves = kFusedThreads / kWave;
 
 template <bool kVec4>
-__global__ void __launch_bounds__(kFusedThreads)
-k_fused(const float *__restrict__ grad, float *__restrict__ residual, Geom g,
+__device__ __forceinline__ void
+fused_body(const float *__restrict__ grad, float *__restrict__ residual, Geom g,
         const EncodeCtl *__restrict__ ctl, u32 *__restrict__ partials,
         u32 *__restrict__ seg_count, u32 *__restrict__ s_idx, u32 *__restrict__ s_val)
 {
@@ -721,8 +721,8 @@ struct UnitWalk {
 // ---------------------------------------------------------------------------
 constexpr u32 kReduceThreads = 256;
 
-__global__ void __launch_bounds__(kReduceThreads)
-k_reduce(const u32 *__restrict__ partials, u32 n_rows, const EncodeCtl *__restrict__ ctl,
+__device__ __forceinline__ void
+reduce_body(const u32 *__restrict__ partials, u32 n_rows, const EncodeCtl *__restrict__ ctl,
          u32 *__restrict__ hist)
 {
     const u32 nbins = ctl->bins.nfine + kCoarseBins;
@@ -741,8 +741,8 @@ k_reduce(const u32 *__restrict__ partials, u32 n_rows, const EncodeCtl *__restri
 constexpr u32 kPickThreads = 1024;
 constexpr u32 kPickPer = (kMaxBins + kPickThreads - 1) / kPickThreads;
 
-__global__ void __launch_bounds__(kPickThreads)
-k_pick(const u32 *__restrict__ hist, Geom g, EncodeCtl *ctl)
+__device__ __forceinline__ void
+pick_body(const u32 *__restrict__ hist, Geom g, EncodeCtl *ctl)
 {
     __shared__ u32 scan_lds[kPickThreads / kWave + 1];
     __shared__ u32 bin_s;
@@ -813,8 +813,8 @@ k_pick(const u32 *__restrict__ hist, Geom g, EncodeCtl *ctl)
 // classify: walk S; certain members are keyed against the window, entries
 // of the deciding bin go to the short list B.
 // ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(kWalkThreads)
-k_classify(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ seg_count,
+__device__ __forceinline__ void
+classify_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ seg_count,
            const u32 *__restrict__ s_idx, const u32 *__restrict__ s_val,
            u32 *__restrict__ win_cnt, u32 *__restrict__ blk_sure, u32 *__restrict__ n_m,
            u32 *__restrict__ n_b, u64 *__restrict__ m_key, u32 *__restrict__ m_idx,
@@ -981,8 +981,8 @@ __device__ __forceinline__ bool pair_le(u64 hi, u32 lo, const Pair96 &p)
 // finalize: one workgroup turns the short lists into the two cut points and
 // the output offset of every chunk.
 // ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(kFinThreads)
-k_finalize(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__ a,
+__device__ __forceinline__ void
+finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__ a,
            const u32 *__restrict__ seg_count, const u32 *__restrict__ s_idx,
            const u32 *__restrict__ s_val, u32 *win_cnt, const u32 *__restrict__ blk_sure,
            const u32 *__restrict__ n_m, const u32 *__restrict__ n_b,
@@ -1235,8 +1235,8 @@ k_finalize(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__ a,
 // winners before it in the chunk; the latter is kept as the difference of two
 // running totals over the wavefront's flat walk.
 // ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(kWalkThreads)
-k_emit(Geom g, PhiloxSeed seed, const EncodeCtl *__restrict__ ctl,
+__device__ __forceinline__ void
+emit_body(Geom g, PhiloxSeed seed, const EncodeCtl *__restrict__ ctl,
        const u32 *__restrict__ seg_count, const u32 *__restrict__ s_idx,
        const u32 *__restrict__ s_val, const u32 *__restrict__ chunk_base,
        u32 *__restrict__ out_idx, float *__restrict__ out_val, float *residual)
@@ -1277,6 +1277,108 @@ k_emit(Geom g, PhiloxSeed seed, const EncodeCtl *__restrict__ ctl,
         carry = __shfl(at_start, kWave - 1, kWave);
         run += popc64(mask);
     });
+}
+
+// ---------------------------------------------------------------------------
+// The kernels. One launch serves up to kMaxBatch independent vectors of the
+// same sizes ("members": the workers of one node, or the tensors of one
+// model): blockIdx.z is the member, and every member has its own workspace,
+// ws_stride bytes after the previous one. Each member is computed exactly as
+// if it were alone; batching only lets the short kernels of all members run
+// side by side and the streaming kernel run on without draining in between.
+// ---------------------------------------------------------------------------
+constexpr u32 kMaxBatch = 16;
+
+struct Batch {
+    const float *grad[kMaxBatch];
+    float *residual[kMaxBatch];
+    u32 *out_idx[kMaxBatch];
+    float *out_val[kMaxBatch];
+    u32 seed_lo[kMaxBatch], seed_hi[kMaxBatch];
+    u32 step_lo, step_hi;
+    char *ws;
+    u64 ws_stride;
+};
+
+// what the workgroup's member works on
+struct Member {
+    const float *grad;
+    float *residual;
+    u32 *out_idx;
+    float *out_val;
+    PhiloxSeed seed;
+    char *ws;
+    __device__ __forceinline__ Member(const Batch &B)
+    {
+        const u32 i = blockIdx.z;
+        grad = B.grad[i];
+        residual = B.residual[i];
+        out_idx = B.out_idx[i];
+        out_val = B.out_val[i];
+        seed = PhiloxSeed{B.seed_lo[i], B.seed_hi[i], B.step_lo, B.step_hi};
+        ws = B.ws + (u64)i * B.ws_stride;
+    }
+    template <class T>
+    __device__ __forceinline__ T *at(u64 offset) const { return reinterpret_cast<T *>(ws + offset); }
+};
+
+__global__ void __launch_bounds__(kSampleThreads) k_sample(Batch B, Geom g, EncodeLayout L)
+{
+    const Member m(B);
+    sample_body(m.grad, m.residual, g, m.at<u32>(0), (u32)(L.zero_bytes / 4), m.at<u32>(L.samples));
+}
+
+__global__ void __launch_bounds__(kEstThreads) k_estimate(Batch B, Geom g, EncodeLayout L)
+{
+    const Member m(B);
+    estimate_body(m.at<u32>(L.samples), g, m.at<EncodeCtl>(L.ctl));
+}
+
+template <bool kVec4>
+__global__ void __launch_bounds__(kFusedThreads) k_fused(Batch B, Geom g, EncodeLayout L)
+{
+    const Member m(B);
+    fused_body<kVec4>(m.grad, m.residual, g, m.at<EncodeCtl>(L.ctl), m.at<u32>(L.partials),
+                      m.at<u32>(L.seg_count), m.at<u32>(L.s_idx), m.at<u32>(L.s_val));
+}
+
+__global__ void __launch_bounds__(kReduceThreads) k_reduce(Batch B, u32 n_rows, EncodeLayout L)
+{
+    const Member m(B);
+    reduce_body(m.at<u32>(L.partials), n_rows, m.at<EncodeCtl>(L.ctl), m.at<u32>(L.hist));
+}
+
+__global__ void __launch_bounds__(kPickThreads) k_pick(Batch B, Geom g, EncodeLayout L)
+{
+    const Member m(B);
+    pick_body(m.at<u32>(L.hist), g, m.at<EncodeCtl>(L.ctl));
+}
+
+__global__ void __launch_bounds__(kWalkThreads) k_classify(Batch B, Geom g, EncodeLayout L)
+{
+    const Member m(B);
+    classify_body(g, m.seed, m.at<EncodeCtl>(L.ctl), m.at<u32>(L.seg_count), m.at<u32>(L.s_idx),
+                  m.at<u32>(L.s_val), m.at<u32>(L.win_cnt), m.at<u32>(L.blk_sure),
+                  m.at<u32>(L.n_m), m.at<u32>(L.n_b), m.at<u64>(L.m_key), m.at<u32>(L.m_idx),
+                  m.at<u32>(L.b_mag), m.at<u32>(L.b_idx));
+}
+
+__global__ void __launch_bounds__(kFinThreads) k_finalize(Batch B, Geom g, EncodeLayout L)
+{
+    const Member m(B);
+    finalize_body(g, m.seed, m.at<EncodeCtl>(L.ctl), m.residual, m.at<u32>(L.seg_count),
+                  m.at<u32>(L.s_idx), m.at<u32>(L.s_val), m.at<u32>(L.win_cnt),
+                  m.at<u32>(L.blk_sure), m.at<u32>(L.n_m), m.at<u32>(L.n_b), m.at<u64>(L.m_key),
+                  m.at<u32>(L.m_idx), m.at<u32>(L.b_mag), m.at<u32>(L.b_idx), m.at<u64>(L.dm_key),
+                  m.at<u32>(L.dm_idx), m.at<u64>(L.db_key), m.at<u32>(L.db_idx),
+                  m.at<u32>(L.chunk_base));
+}
+
+__global__ void __launch_bounds__(kWalkThreads) k_emit(Batch B, Geom g, EncodeLayout L)
+{
+    const Member m(B);
+    emit_body(g, m.seed, m.at<EncodeCtl>(L.ctl), m.at<u32>(L.seg_count), m.at<u32>(L.s_idx),
+              m.at<u32>(L.s_val), m.at<u32>(L.chunk_base), m.out_idx, m.out_val, m.residual);
 }
 
 }  // namespace rtopk
@@ -1383,21 +1485,24 @@ extern "C" int rtopk_trace_next_encode(int stage, void *ev_begin, void *ev_end)
         if (hipGetLastError() != hipSuccess) return RTOPK_EHIP; \
     } while (0)
 
-extern "C" int rtopk_encode(const float *grad, float *residual, uint64_t d, uint64_t r,
-                            uint64_t k, uint64_t seed, uint64_t step, uint32_t *out_idx,
-                            float *out_val, void *workspace, uint64_t workspace_bytes,
-                            void *stream_v)
+extern "C" int rtopk_encode_batch(uint32_t n, const float *const *grad, float *const *residual,
+                                  uint64_t d, uint64_t r, uint64_t k, const uint64_t *seed,
+                                  uint64_t step, uint32_t *const *out_idx, float *const *out_val,
+                                  void *workspace, uint64_t workspace_bytes, void *stream_v)
 {
-    if (!grad || !residual || !out_idx || !out_val) return RTOPK_EINVAL;
+    if (n < 1 || !grad || !residual || !seed || !out_idx || !out_val) return RTOPK_EINVAL;
     const int rc = check_sizes(d, r, k);
     if (rc) return rc;
-    {
-        const uintptr_t g0 = (uintptr_t)grad, m0 = (uintptr_t)residual;
+    bool vec4 = true;
+    for (uint32_t i = 0; i < n; ++i) {
+        if (!grad[i] || !residual[i] || !out_idx[i] || !out_val[i]) return RTOPK_EINVAL;
+        const uintptr_t g0 = (uintptr_t)grad[i], m0 = (uintptr_t)residual[i];
         if (g0 < m0 + d * 4 && m0 < g0 + d * 4) return RTOPK_EINVAL;
+        vec4 = vec4 && ((g0 | m0) & 15u) == 0;
     }
     Geom g = make_geom(d, r, k);
     const EncodeLayout L = make_layout(g);
-    if (!workspace || ((uintptr_t)workspace & 255u) || workspace_bytes < L.total)
+    if (!workspace || ((uintptr_t)workspace & 255u) || workspace_bytes / n < L.total)
         return RTOPK_EWORKSPACE;
     const unsigned force = g_force;
     g_force = 0;
@@ -1406,82 +1511,81 @@ extern "C" int rtopk_encode(const float *grad, float *residual, uint64_t d, uint
         g.K_lo = g.K_hi = 0;       // a window that holds no key: the exact selection must run
         g.k_nlz = 63u;
     }
-
     hipStream_t stream = (hipStream_t)stream_v;
-    char *ws = (char *)workspace;
-    EncodeCtl *ctl = (EncodeCtl *)(ws + L.ctl);
-    u32 *hist = (u32 *)(ws + L.hist), *samples = (u32 *)(ws + L.samples);
-    u32 *partials = (u32 *)(ws + L.partials);
-    u32 *seg_count = (u32 *)(ws + L.seg_count), *win_cnt = (u32 *)(ws + L.win_cnt);
-    u32 *chunk_base = (u32 *)(ws + L.chunk_base), *blk_sure = (u32 *)(ws + L.blk_sure);
-    u32 *n_m = (u32 *)(ws + L.n_m), *n_b = (u32 *)(ws + L.n_b);
-    u64 *m_key = (u64 *)(ws + L.m_key), *dm_key = (u64 *)(ws + L.dm_key);
-    u64 *db_key = (u64 *)(ws + L.db_key);
-    u32 *m_idx = (u32 *)(ws + L.m_idx), *b_mag = (u32 *)(ws + L.b_mag);
-    u32 *b_idx = (u32 *)(ws + L.b_idx), *dm_idx = (u32 *)(ws + L.dm_idx);
-    u32 *db_idx = (u32 *)(ws + L.db_idx);
-    u32 *s_idx = (u32 *)(ws + L.s_idx), *s_val = (u32 *)(ws + L.s_val);
-
-    const PhiloxSeed ps{(u32)seed, (u32)(seed >> 32), (u32)step, (u32)(step >> 32)};
-    const bool vec4 = (((uintptr_t)grad | (uintptr_t)residual) & 15u) == 0;
     unsigned grid_limit = 0;
     const int rc2 = fused_grid_limit(&grid_limit);
     if (rc2) return rc2;
+    unsigned fgrid = (g.W + kFusedWaves - 1) / kFusedWaves;
+    if (fgrid > grid_limit) fgrid = grid_limit;
 
     const TraceRequest trace = g_trace;
     g_trace = TraceRequest{};
     StageScope whole(trace, RTOPK_STAGE_ALL, stream);
 
-    {
-        StageScope sc(trace, RTOPK_STAGE_PREPARE, stream);
-        k_sample<<<kSampleLoc / kSampleThreads, kSampleThreads, 0, stream>>>(
-            grad, residual, g, (u32 *)ws, (u32)(L.zero_bytes / 4), samples);
-        RTOPK_LAUNCH_CHECK();
-        k_estimate<<<1, kEstThreads, 0, stream>>>(samples, g, ctl);
-        RTOPK_LAUNCH_CHECK();
-    }
-    {
-        unsigned grid = (g.W + kFusedWaves - 1) / kFusedWaves;
-        if (grid > grid_limit) grid = grid_limit;
+    for (uint32_t first = 0; first < n; first += kMaxBatch) {
+        const unsigned nb = n - first < kMaxBatch ? n - first : kMaxBatch;
+        Batch B{};
+        for (unsigned i = 0; i < nb; ++i) {
+            B.grad[i] = grad[first + i];
+            B.residual[i] = residual[first + i];
+            B.out_idx[i] = out_idx[first + i];
+            B.out_val[i] = out_val[first + i];
+            B.seed_lo[i] = (u32)seed[first + i];
+            B.seed_hi[i] = (u32)(seed[first + i] >> 32);
+        }
+        B.step_lo = (u32)step;
+        B.step_hi = (u32)(step >> 32);
+        B.ws = (char *)workspace + (u64)first * L.total;
+        B.ws_stride = L.total;
         {
-            StageScope sc(trace, RTOPK_STAGE_FUSED, stream);
-            if (vec4)
-                k_fused<true><<<grid, kFusedThreads, 0, stream>>>(grad, residual, g, ctl, partials,
-                                                                  seg_count, s_idx, s_val);
-            else
-                k_fused<false><<<grid, kFusedThreads, 0, stream>>>(grad, residual, g, ctl,
-                                                                   partials, seg_count, s_idx,
-                                                                   s_val);
+            StageScope sc(trace, RTOPK_STAGE_PREPARE, stream);
+            k_sample<<<dim3(kSampleLoc / kSampleThreads, 1, nb), kSampleThreads, 0, stream>>>(B, g, L);
+            RTOPK_LAUNCH_CHECK();
+            k_estimate<<<dim3(1, 1, nb), kEstThreads, 0, stream>>>(B, g, L);
             RTOPK_LAUNCH_CHECK();
         }
-        const dim3 rgrid((g.nfine + kCoarseBins + kReduceThreads - 1) / kReduceThreads, kHistRows);
-        k_reduce<<<rgrid, kReduceThreads, 0, stream>>>(partials, grid, ctl, hist);
-        RTOPK_LAUNCH_CHECK();
-    }
-    {
-        StageScope sc(trace, RTOPK_STAGE_CLASSIFY, stream);
-        k_pick<<<1, kPickThreads, 0, stream>>>(hist, g, ctl);
-        RTOPK_LAUNCH_CHECK();
-        k_classify<<<g.G3, kWalkThreads, 0, stream>>>(g, ps, ctl, seg_count, s_idx, s_val,
-                                                      win_cnt, blk_sure, n_m, n_b, m_key, m_idx,
-                                                      b_mag, b_idx);
-        RTOPK_LAUNCH_CHECK();
-    }
-    {
-        StageScope sc(trace, RTOPK_STAGE_FINALIZE, stream);
-        k_finalize<<<1, kFinThreads, 0, stream>>>(g, ps, ctl, residual, seg_count, s_idx, s_val,
-                                                  win_cnt, blk_sure, n_m, n_b, m_key, m_idx,
-                                                  b_mag, b_idx, dm_key, dm_idx, db_key, db_idx,
-                                                  chunk_base);
-        RTOPK_LAUNCH_CHECK();
-    }
-    {
-        StageScope sc(trace, RTOPK_STAGE_EMIT, stream);
-        k_emit<<<g.G3, kWalkThreads, 0, stream>>>(g, ps, ctl, seg_count, s_idx, s_val, chunk_base,
-                                                  out_idx, out_val, residual);
-        RTOPK_LAUNCH_CHECK();
+        {
+            {
+                StageScope sc(trace, RTOPK_STAGE_FUSED, stream);
+                if (vec4)
+                    k_fused<true><<<dim3(fgrid, 1, nb), kFusedThreads, 0, stream>>>(B, g, L);
+                else
+                    k_fused<false><<<dim3(fgrid, 1, nb), kFusedThreads, 0, stream>>>(B, g, L);
+                RTOPK_LAUNCH_CHECK();
+            }
+            const dim3 rgrid((g.nfine + kCoarseBins + kReduceThreads - 1) / kReduceThreads,
+                             kHistRows, nb);
+            k_reduce<<<rgrid, kReduceThreads, 0, stream>>>(B, fgrid, L);
+            RTOPK_LAUNCH_CHECK();
+        }
+        {
+            StageScope sc(trace, RTOPK_STAGE_CLASSIFY, stream);
+            k_pick<<<dim3(1, 1, nb), kPickThreads, 0, stream>>>(B, g, L);
+            RTOPK_LAUNCH_CHECK();
+            k_classify<<<dim3(g.G3, 1, nb), kWalkThreads, 0, stream>>>(B, g, L);
+            RTOPK_LAUNCH_CHECK();
+        }
+        {
+            StageScope sc(trace, RTOPK_STAGE_FINALIZE, stream);
+            k_finalize<<<dim3(1, 1, nb), kFinThreads, 0, stream>>>(B, g, L);
+            RTOPK_LAUNCH_CHECK();
+        }
+        {
+            StageScope sc(trace, RTOPK_STAGE_EMIT, stream);
+            k_emit<<<dim3(g.G3, 1, nb), kWalkThreads, 0, stream>>>(B, g, L);
+            RTOPK_LAUNCH_CHECK();
+        }
     }
     return RTOPK_OK;
+}
+
+extern "C" int rtopk_encode(const float *grad, float *residual, uint64_t d, uint64_t r,
+                            uint64_t k, uint64_t seed, uint64_t step, uint32_t *out_idx,
+                            float *out_val, void *workspace, uint64_t workspace_bytes,
+                            void *stream_v)
+{
+    return rtopk_encode_batch(1, &grad, &residual, d, r, k, &seed, step, &out_idx, &out_val,
+                              workspace, workspace_bytes, stream_v);
 }
 
 extern "C" int rtopk_encode_stats(const void *workspace, void *stream_v,

@@ -429,3 +429,70 @@ def test_warmup_schedule_of_r_and_k_with_one_workspace():
 
 def rt_ws(u, d, r, k):
     return u.rt.encode_workspace_bytes(d, r, k)
+
+
+# --------------------------------------------------------------------------
+# several vectors in one call: every member exactly as if encoded alone
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("n,d,misalign", [(3, 150_001, None), (8, 70_000, None), (17, 20_011, None),
+                                          (4, 90_004, 2)])
+def test_batch_members_match_the_oracle_one_by_one(n, d, misalign):
+    import torch
+    u = _u()
+    rt = u.rt
+    r, k = max(2, d // 100), max(1, d // 1000)
+    wl = Workload(3, d=d, r=r, k=k)
+    dev = u.DEV
+    stride = rt.encode_workspace_bytes(d, r, k)
+    ws = torch.empty(n * stride, dtype=torch.uint8, device=dev)
+    ws.fill_(0xA5)
+    offs = [1 if i == misalign else 0 for i in range(n)]      # one member off 16-byte alignment
+    g_store = [torch.empty(d + 4, dtype=torch.float32, device=dev) for _ in range(n)]
+    m_store = [torch.zeros(d + 4, dtype=torch.float32, device=dev) for _ in range(n)]
+    grads = [g_store[i][offs[i]:offs[i] + d] for i in range(n)]
+    resid = [m_store[i][offs[i]:offs[i] + d] for i in range(n)]
+    idx = torch.full((n * k,), -1, dtype=torch.int32, device=dev)
+    val = torch.full((n * k,), float("nan"), dtype=torch.float32, device=dev)
+    out_i = [idx[i * k:(i + 1) * k] for i in range(n)]
+    out_v = [val[i * k:(i + 1) * k] for i in range(n)]
+    seeds = [philox_seed_for_worker(i) + (1 << 40) * i for i in range(n)]
+    ref_m = [np.zeros(d, np.float32) for _ in range(n)]
+    for t in range(2):
+        gs = [wl.gradient(i, t) for i in range(n)]
+        for i in range(n):
+            grads[i].copy_(torch.from_numpy(gs[i]))
+        print(f"batch n={n} d={d} step={t}", flush=True)
+        rt.encode_batch(grads, resid, r, k, seeds, t, out_i, out_v, ws)
+        torch.cuda.synchronize()
+        for i in range(n):
+            st = rt.encode_stats(ws[i * stride:(i + 1) * stride])
+            assert st["error_flags"] == 0 and st["count_greater"] + st["ties_taken"] == r, (i, st)
+            oi, ov, ref_m[i] = oracle.encode(gs[i], ref_m[i], r, k, seeds[i], t)
+            got = (out_i[i].cpu().numpy().view(np.uint32), out_v[i].cpu().numpy(),
+                   resid[i].cpu().numpy())
+            u.assert_encode_equal(got, (oi, ov, ref_m[i]), f"member {i} step {t}")
+        # the messages sit back to back: the master's average takes them as they are
+        out = torch.empty(d, dtype=torch.float32, device=dev)
+        rt.aggregate(idx, val, n, k, out)
+        torch.cuda.synchronize()
+        want = oracle.aggregate_f32(idx.cpu().numpy().view(np.uint32), val.cpu().numpy(), n, d)
+        assert np.array_equal(u.bits(out.cpu().numpy()), u.bits(want))
+
+
+def test_batch_rejects_bad_arguments():
+    import torch
+    u = _u()
+    rt = u.rt
+    d, r, k = 1000, 10, 2
+    dev = u.DEV
+    g = torch.zeros(d, dtype=torch.float32, device=dev)
+    m = torch.zeros(d, dtype=torch.float32, device=dev)
+    oi = torch.zeros(k, dtype=torch.int32, device=dev)
+    ov = torch.zeros(k, dtype=torch.float32, device=dev)
+    ws = torch.empty(rt.encode_workspace_bytes(d, r, k), dtype=torch.uint8, device=dev)
+    with pytest.raises(rt.RtopkError):        # workspace for one member, two members
+        rt.encode_batch([g, g], [m, m.clone()], r, k, [1, 2], 0, [oi, oi.clone()], [ov, ov.clone()], ws)
+    with pytest.raises(rt.RtopkError):        # gradient and residual are the same buffer
+        rt.encode_batch([g], [g], r, k, [1], 0, [oi], [ov], ws)
+    with pytest.raises(ValueError):
+        rt.encode_batch([g], [m], r, k, [1, 2], 0, [oi], [ov], ws)
