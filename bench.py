@@ -2,27 +2,24 @@
 """Benchmark of the rTop-k hot path on one MI355X.
 
 One *step* is one pass of the whole hot path over one batch of synthetic
-input: n workers each run ``rtopk_encode`` (error-compensated rTop-k
-sparsification of a fresh d-element gradient) and the master runs
-``rtopk_aggregate`` on the n messages. The workload is the ResNet-50-sized
-configuration (d = 25,557,032, r = 0.5% d, k = 0.1% d, n = 8 workers) that the
-headline metric is quoted on. All gradients of the warm-up and timed steps are
-resident in HBM before the clock starts.
-
-By default everything runs on one stream, one kernel at a time. The n workers
-of a step are independent (Algorithm 1 runs them on n nodes), so with
-``--streams S`` their encodes are dealt to S HIP streams, each with its own
-workspace; the kernel durations measured then include whatever ran beside them.
-After the timed region the same steps are run once more on two streams and
-reported as ``two_stream`` (a secondary figure; ``value`` is the one-stream one).
+input: the n workers' fresh d-element gradients go through the
+error-compensated rTop-k sparsifier (``rtopk_encode_batch``: one call, shared
+kernel launches, every worker computed exactly as by ``rtopk_encode``) and the
+master runs ``rtopk_aggregate`` on the n messages. The workload is the
+ResNet-50-sized configuration (d = 25,557,032, r = 0.5% d, k = 0.1% d, n = 8
+workers) that the headline metric is quoted on. All gradients of the warm-up
+and timed steps are resident in HBM before the clock starts; everything runs
+on one stream. ``--sequential`` times n separate ``rtopk_encode`` calls per
+step instead; by default that variant runs once more after the timed region
+and is reported as ``per_call`` (the latency of a single call).
 
 Prints ONE JSON line:
   value      = gradient bytes consumed per second over whole steps
                (n * 4d bytes per step / seconds per step), GB/s
   roofline   = the dominant kernel (fused residual add + candidate append):
-               algorithmic bytes per launch (12 d) over its mean duration,
-               measured with HIP events on the launch stream (one launch per
-               step by default, see --trace-stride), against the 8 TB/s HBM peak
+               algorithmic bytes per launch (12 d per vector in the launch)
+               over its mean duration, measured with HIP events on the launch
+               stream, against the 8 TB/s HBM peak
   cpu_baseline = the CPU oracle, one thread, timed on a bounded sample of the
                same workload
 """
@@ -46,7 +43,8 @@ METRIC = "rTop-k encode gradient GB/s and % of HBM peak at d=25.6M; aggregate GB
 # two rocprofv3 --pmc runs, FETCH_SIZE then WRITE_SIZE, each scaled by a device
 # copy of known size in the same run; the summary and the commands are in
 # profiles/k_fused_cfg3_hbm_traffic.txt. Only valid for the default workload.
-DOMINANT_KERNEL_TRAFFIC_BYTES = 309_655_484
+SINGLE_KERNEL_TRAFFIC_BYTES = 309_655_484       # one vector per launch (--sequential)
+BATCH_KERNEL_TRAFFIC_BYTES = 8 * 309_655_484    # the default: 8 workers per launch
 
 
 class HipEvents:
@@ -118,22 +116,22 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=3, help="workload configuration (1-5)")
-    ap.add_argument("--workers", type=int, default=None, help="override the worker count")
-    ap.add_argument("--streams", type=int, default=1,
-                    help="HIP streams the simulated workers are dealt to (each with its own "
-                         "workspace); 1 = strictly one kernel at a time")
+    ap.add_argument("--workers", type=int, default=0, help="override the workload's worker count")
+    ap.add_argument("--sequential", action="store_true",
+                    help="the timed steps call rtopk_encode once per worker instead of "
+                         "rtopk_encode_batch once per step")
     ap.add_argument("--trace-stride", type=int, default=0, metavar="N",
-                    help="bracket every N-th launch of the dominant kernel with HIP events "
-                         "(default: the number of workers, i.e. one launch per step, a "
-                         "different worker each step; 1 = every launch). The two event "
+                    help="with --sequential: bracket every N-th launch of the dominant kernel "
+                         "with HIP events (default: the number of workers, i.e. one launch per "
+                         "step, a different worker each step; 1 = every launch). The two event "
                          "records cost the stream a few microseconds per traced launch.")
+    ap.add_argument("--no-per-call-leg", action="store_true",
+                    help="skip the extra pass that times one rtopk_encode call per worker")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
                     help="after the timed region, also run N plain device copies of d floats "
                          "(4d bytes read + 4d bytes written each): a kernel of known HBM "
                          "traffic to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters with")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-overlap-leg", action="store_true",
-                    help="skip the extra two-stream pass that is reported as `two_stream`")
     ap.add_argument("--cpu-sample", type=int, default=2, help="oracle encodes to time")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -155,8 +153,8 @@ def main() -> int:
     d, r, k = wl.d, wl.r, wl.k
     n = args.workers or wl.n_workers
     K, W = args.steps, args.warmup
-    S = max(1, min(args.streams, n))
     total_steps = K + W
+    batched = not args.sequential
 
     # ---- inputs: every gradient of every step resident in HBM ------------
     grads = [[torch.from_numpy(wl.gradient(w, t)).to(dev) for w in range(n)]
@@ -164,108 +162,100 @@ def main() -> int:
     residual = [torch.zeros(d, dtype=torch.float32, device=dev) for _ in range(n)]
     idx = torch.empty(n * k, dtype=torch.int32, device=dev)
     val = torch.empty(n * k, dtype=torch.float32, device=dev)
+    out_i = [idx[w * k:(w + 1) * k] for w in range(n)]
+    out_v = [val[w * k:(w + 1) * k] for w in range(n)]
+    seeds = [philox_seed_for_worker(w) for w in range(n)]
     out = torch.empty(d, dtype=torch.float32, device=dev)
     ws_bytes = rt.encode_workspace_bytes(d, r, k)
-    ws = [torch.empty(ws_bytes, dtype=torch.uint8, device=dev) for _ in range(S)]
-    streams = [torch.cuda.Stream(device=dev) for _ in range(S)]     # default priority
-    joined = [torch.cuda.Event() for _ in range(S)]
-    released = torch.cuda.Event()
+    ws = torch.empty(n * ws_bytes, dtype=torch.uint8, device=dev)   # one slice per worker
+    ws_of = [ws[w * ws_bytes:(w + 1) * ws_bytes] for w in range(n)]
+    stream = torch.cuda.Stream(device=dev)                           # default priority
     torch.cuda.synchronize()
 
-    def one_step(t: int, trace=None, phase=None):
-        """n encodes dealt round-robin to the streams, then the master's
-        average on stream 0 once every stream has finished its encodes; the
-        next step's encodes start after the average (it reads the messages
-        they overwrite)."""
-        for s in range(1, S):
-            streams[s].wait_event(released)
+    def one_step(t: int, step_no: int, as_batch: bool, trace=None, phase=None):
+        """The n workers' encodes (one batched call, or n calls) and the
+        master's average, all on one stream."""
         if phase is not None:
-            phase[0].record(streams[0])
+            phase[0].record(stream)
+        if as_batch:
+            if trace is not None and trace[0] is not None:
+                rt.trace_next_encode(rt.STAGES["fused"], *trace[0])
+            rt.encode_batch(grads[t], residual, r, k, seeds, step_no, out_i, out_v, ws, stream)
+        else:
+            for w in range(n):
+                if trace is not None and trace[w] is not None:
+                    rt.trace_next_encode(rt.STAGES["fused"], *trace[w])
+                rt.encode(grads[t][w], residual[w], r, k, seeds[w], step_no, out_i[w], out_v[w],
+                          ws_of[w], stream)
+        if phase is not None:
+            phase[1].record(stream)
+        rt.aggregate(idx, val, n, k, out, None, stream)
+        if phase is not None:
+            phase[2].record(stream)
+
+    def check_stats():
+        last = None
         for w in range(n):
-            s = w % S
-            if trace is not None and trace[w] is not None:
-                rt.trace_next_encode(rt.STAGES["fused"], *trace[w])
-            rt.encode(grads[t][w], residual[w], r, k, philox_seed_for_worker(w), t,
-                      idx[w * k:(w + 1) * k], val[w * k:(w + 1) * k], ws[s], streams[s])
-        for s in range(1, S):
-            joined[s].record(streams[s])
-            streams[0].wait_event(joined[s])
-        if phase is not None:
-            phase[1].record(streams[0])
-        rt.aggregate(idx, val, n, k, out, None, streams[0])
-        if phase is not None:
-            phase[2].record(streams[0])
-        released.record(streams[0])
+            last = rt.encode_stats(ws_of[w], stream)
+            if last["error_flags"] != 0:
+                print(f"bench.py: encode of worker {w} reported error flags {last}",
+                      file=sys.stderr)
+                return None
+        return last
 
-    released.record(streams[0])
     for t in range(W):
-        one_step(t)
+        one_step(t, t, batched)
     torch.cuda.synchronize()
 
-    # ---- timed region: K steps, events on the launch streams ---------------
+    # ---- timed region: K steps, events on the launch stream ----------------
     ev = HipEvents()
-    stride = args.trace_stride if args.trace_stride > 0 else n
-    offset = 0 if stride == 1 else 1             # n | stride would always pick worker 0
-    fused_pairs = [[(ev.new(), ev.new()) if (s_ * (n + offset) + w) % stride == 0 else None
-                    for w in range(n)] for s_ in range(K)]
+    if batched:
+        fused_pairs = [[(ev.new(), ev.new())] for _ in range(K)]
+        vectors_per_launch = n
+    else:
+        stride = args.trace_stride if args.trace_stride > 0 else n
+        offset = 0 if stride == 1 else 1             # n | stride would always pick worker 0
+        fused_pairs = [[(ev.new(), ev.new()) if (s_ * (n + offset) + w) % stride == 0 else None
+                        for w in range(n)] for s_ in range(K)]
+        vectors_per_launch = 1
     phase = [tuple(torch.cuda.Event(enable_timing=True) for _ in range(3)) for _ in range(K)]
     torch.cuda.synchronize()
     t_wall0 = time.perf_counter()
     for s_ in range(K):
-        one_step(W + s_, trace=fused_pairs[s_], phase=phase[s_])
+        one_step(W + s_, W + s_, batched, trace=fused_pairs[s_], phase=phase[s_])
     torch.cuda.synchronize()
     t_wall1 = time.perf_counter()
     total_ms = phase[0][0].elapsed_time(phase[-1][2])
-    enc_ms_call = sum(p[0].elapsed_time(p[1]) for p in phase) / (K * n)
+    enc_ms_vector = sum(p[0].elapsed_time(p[1]) for p in phase) / (K * n)
     agg_ms_call = sum(p[1].elapsed_time(p[2]) for p in phase) / K
     fused_ms = [ev.elapsed_ms(*pair) for row in fused_pairs for pair in row if pair is not None]
     ev.close()
+    stats = check_stats()
+    if stats is None:
+        return 4
 
-    # ---- outside the timed region: the same K steps once more with the
-    #      workers dealt to two streams, no launch bracketed (the n encodes of
-    #      a step are independent; the short kernels of one overlap the
-    #      streaming kernel of the next). Reported beside the headline only. ---
-    overlap = None
-    if S == 1 and n > 1 and not args.no_overlap_leg:
-        S2 = 2
-        streams2 = [streams[0], torch.cuda.Stream(device=dev)]
-        ws2 = [ws[0], torch.empty(ws_bytes, dtype=torch.uint8, device=dev)]
-        joined2, released2 = torch.cuda.Event(), torch.cuda.Event()
-        edge = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-
-        def overlapped_step(t: int, step_no: int):
-            streams2[1].wait_event(released2)
-            for w in range(n):
-                s = w % S2
-                # the gradients of step t again, on top of the residuals as they are now,
-                # under a step number not used before (fresh sampling keys: keys that
-                # already decided what left these residuals would not be independent
-                # of the top-r set any more)
-                rt.encode(grads[t][w], residual[w], r, k, philox_seed_for_worker(w),
-                          step_no, idx[w * k:(w + 1) * k], val[w * k:(w + 1) * k],
-                          ws2[s], streams2[s])
-            joined2.record(streams2[1])
-            streams2[0].wait_event(joined2)
-            rt.aggregate(idx, val, n, k, out, None, streams2[0])
-            released2.record(streams2[0])
-
-        released2.record(streams2[0])
-        overlapped_step(W, total_steps)               # warm-up of the second workspace
-        edge[0].record(streams2[0])
+    # ---- outside the timed region: the same K steps once more, one
+    #      rtopk_encode call per worker (the latency of a single call). The
+    #      gradients of step t again, on top of the residuals as they are now,
+    #      under step numbers not used before: sampling keys that already decided
+    #      what left these residuals would not be independent of the top-r set. ---
+    per_call = None
+    if batched and not args.no_per_call_leg:
+        edge = [tuple(torch.cuda.Event(enable_timing=True) for _ in range(3)) for _ in range(K)]
+        one_step(W, total_steps, False)
         for s_ in range(K):
-            overlapped_step(W + s_, total_steps + 1 + s_)
-        edge[1].record(streams2[0])
+            one_step(W + s_, total_steps + 1 + s_, False, phase=edge[s_])
         torch.cuda.synchronize()
-        ms2 = edge[0].elapsed_time(edge[1]) / K
-        overlap = {"streams": S2, "ms_per_step": round(ms2, 4),
-                   "value": round(n * 4.0 * d / (ms2 * 1e-3) / 1e9, 2), "unit": "GB/s"}
-        for w_ in ws2:
-            st2 = rt.encode_stats(w_)
-            if st2["error_flags"] != 0:
-                print(f"bench.py: encode reported error flags {st2}", file=sys.stderr)
-                return 4
-        overlap["last_encode_path"] = st2["path"]
-        del ws2
+        ms_call = sum(p[0].elapsed_time(p[1]) for p in edge) / (K * n)
+        ms_step = edge[0][0].elapsed_time(edge[-1][2]) / K
+        if check_stats() is None:
+            return 4
+        per_call = {"encode_ms_per_call": round(ms_call, 4),
+                    "encode_gradient_GBps": round(4.0 * d / (ms_call * 1e-3) / 1e9, 2),
+                    "encode_pct_hbm_peak_at_12d": round(100.0 * 12.0 * d / (ms_call * 1e-3) / 1e9
+                                                        / HBM_PEAK_GBPS, 2),
+                    "ms_per_step": round(ms_step, 4),
+                    "value": round(n * 4.0 * d / (ms_step * 1e-3) / 1e9, 2), "unit": "GB/s"}
 
     # ---- outside the timed region: the master's fused update on the last
     #      step's messages (averaging and weight step in one call) ------------
@@ -274,14 +264,12 @@ def main() -> int:
     omegas = [torch.randn(d, dtype=torch.float32, device=dev) for _ in range(4)]
     upd = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
     upd_calls = 5 * len(omegas)
-    with torch.cuda.stream(streams[0]):
-        for om in omegas:
-            rt.aggregate_update(idx, val, n, k, 0.1, r / k, om, upd_ws, streams[0])
-        upd[0].record(streams[0])
-        for c in range(upd_calls):
-            rt.aggregate_update(idx, val, n, k, 0.1, r / k, omegas[c % len(omegas)], upd_ws,
-                                streams[0])
-        upd[1].record(streams[0])
+    for om in omegas:
+        rt.aggregate_update(idx, val, n, k, 0.1, r / k, om, upd_ws, stream)
+    upd[0].record(stream)
+    for c in range(upd_calls):
+        rt.aggregate_update(idx, val, n, k, 0.1, r / k, omegas[c % len(omegas)], upd_ws, stream)
+    upd[1].record(stream)
     torch.cuda.synchronize()
     upd_ms_call = upd[0].elapsed_time(upd[1]) / upd_calls
     del omegas
@@ -292,16 +280,15 @@ def main() -> int:
             out.copy_(src)
         torch.cuda.synchronize()
 
-    for s in range(S):
-        stats = rt.encode_stats(ws[s])
-        if stats["error_flags"] != 0:
-            print(f"bench.py: encode reported error flags {stats}", file=sys.stderr)
-            return 4
-
     ms_per_step = total_ms / K
     fused_ms_avg = sum(fused_ms) / len(fused_ms)
     value = n * 4.0 * d / (ms_per_step * 1e-3) / 1e9
-    achieved = 12.0 * d / (fused_ms_avg * 1e-3) / 1e9
+    launch_bytes = vectors_per_launch * 12 * d
+    achieved = launch_bytes / (fused_ms_avg * 1e-3) / 1e9
+    traffic = None
+    if args.config == 3:
+        traffic = (BATCH_KERNEL_TRAFFIC_BYTES if batched and n == wl.n_workers
+                   else None if batched else SINGLE_KERNEL_TRAFFIC_BYTES)
     result = {
         "metric": METRIC,
         "value": round(value, 2),
@@ -316,16 +303,17 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": wl.config.name, "d": d, "r": r, "k": k, "workers": n,
-                   "streams": S,
-                   "step": f"{n} x rtopk_encode on {S} stream(s) + 1 x rtopk_aggregate"},
-        "encode_gradient_GBps": round(4.0 * d / (enc_ms_call * 1e-3) / 1e9, 2),
-        "encode_ms_per_call": round(enc_ms_call, 4),
-        "encode_pct_hbm_peak_at_12d": round(100.0 * 12.0 * d / (enc_ms_call * 1e-3) / 1e9
+                   "step": (f"1 x rtopk_encode_batch ({n} workers) + 1 x rtopk_aggregate"
+                            if batched else f"{n} x rtopk_encode + 1 x rtopk_aggregate")
+                           + ", one stream"},
+        "encode_gradient_GBps": round(4.0 * d / (enc_ms_vector * 1e-3) / 1e9, 2),
+        "encode_ms_per_vector": round(enc_ms_vector, 4),
+        "encode_pct_hbm_peak_at_12d": round(100.0 * 12.0 * d / (enc_ms_vector * 1e-3) / 1e9
                                             / HBM_PEAK_GBPS, 2),
         "aggregate_GBps": round(4.0 * d / (agg_ms_call * 1e-3) / 1e9, 2),
         "aggregate_ms_per_call": round(agg_ms_call, 4),
         "aggregate_update_ms_per_call": round(upd_ms_call, 4),
-        "two_stream": overlap,
+        "per_call": per_call,
         "wall_ms_per_step": round((t_wall1 - t_wall0) * 1e3 / K, 4),
         "last_encode": {"path": stats["path"], "superset": stats["superset_size"],
                         "boundary_list": stats["boundary_list_size"],
@@ -337,8 +325,9 @@ def main() -> int:
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "traffic": DOMINANT_KERNEL_TRAFFIC_BYTES if args.config == 3 else None,
-            "bytes_per_launch": 12 * d,
+            "traffic": traffic,
+            "bytes_per_launch": launch_bytes,
+            "vectors_per_launch": vectors_per_launch,
             "avg_launch_ms": round(fused_ms_avg, 5),
             "launches": len(fused_ms),
         },
