@@ -72,3 +72,49 @@ def test_stress_size_properties_and_one_oracle_call():
     sent[gi] = True
     assert np.all(u.bits(gm[sent]) == 0)
     assert np.array_equal(u.bits(gm[~sent]), u.bits(g[~sent]))
+
+
+@pytest.mark.parametrize("cfg,second_step_members", [(2, (0, 3, 7)), (3, (1, 6))])
+def test_full_size_batched_step_as_the_benchmark_launches_it(cfg, second_step_members):
+    """One rtopk_encode_batch over the workload's 8 workers (workspace slices,
+    messages back to back, then rtopk_aggregate), as bench.py's timed step does
+    it: every member of step 0 against the oracle, some members of step 1."""
+    import torch
+    u = _u()
+    rt = u.rt
+    wl = Workload(cfg)
+    d, r, k, n = wl.d, wl.r, wl.k, wl.n_workers
+    dev = u.DEV
+    stride = rt.encode_workspace_bytes(d, r, k)
+    ws = torch.empty(n * stride, dtype=torch.uint8, device=dev)
+    grads = [torch.empty(d, dtype=torch.float32, device=dev) for _ in range(n)]
+    resid = [torch.zeros(d, dtype=torch.float32, device=dev) for _ in range(n)]
+    idx = torch.empty(n * k, dtype=torch.int32, device=dev)
+    val = torch.empty(n * k, dtype=torch.float32, device=dev)
+    out_i = [idx[w * k:(w + 1) * k] for w in range(n)]
+    out_v = [val[w * k:(w + 1) * k] for w in range(n)]
+    seeds = [philox_seed_for_worker(w) for w in range(n)]
+    ref_m = [np.zeros(d, np.float32) for _ in range(n)]
+    for t, members in ((0, tuple(range(n))), (1, second_step_members)):
+        gs = {}
+        for w in range(n):
+            g = wl.gradient(w, t)
+            grads[w].copy_(torch.from_numpy(g))
+            if w in members:
+                gs[w] = g
+        print(f"cfg{cfg} batched step {t}: gpu", flush=True)
+        rt.encode_batch(grads, resid, r, k, seeds, t, out_i, out_v, ws)
+        torch.cuda.synchronize()
+        for w in members:
+            print(f"cfg{cfg} batched step {t}: oracle, worker {w}", flush=True)
+            st = rt.encode_stats(ws[w * stride:(w + 1) * stride])
+            assert st["error_flags"] == 0 and st["path"] == 0, (w, st)
+            oi, ov, ref_m[w] = oracle.encode(gs[w], ref_m[w], r, k, seeds[w], t)
+            got = (out_i[w].cpu().numpy().view(np.uint32), out_v[w].cpu().numpy(),
+                   resid[w].cpu().numpy())
+            u.assert_encode_equal(got, (oi, ov, ref_m[w]), f"cfg{cfg} member {w} step {t}")
+        out = torch.empty(d, dtype=torch.float32, device=dev)
+        rt.aggregate(idx, val, n, k, out)
+        torch.cuda.synchronize()
+        ai, av = idx.cpu().numpy().view(np.uint32), val.cpu().numpy()
+        assert np.array_equal(u.bits(out.cpu().numpy()), u.bits(oracle.aggregate_f32(ai, av, n, d)))
