@@ -82,6 +82,12 @@ constexpr u32 kUnitChunks = kTargetChunks / kMaxUnits;   // chunks one of them w
 constexpr u32 kWalkThreads = 256;             // fused / classify / emit workgroups: 4 wavefronts
 constexpr u32 kWalkWaves = kWalkThreads / kWave;
 constexpr u32 kMaxWalkBlocks = kMaxUnits / kWalkWaves;
+
+// The numbers of candidates kept per chunk are stored unit by unit: the
+// kUnitChunks chunks u, u + U, u + 2U, ... that one walking wavefront takes lie
+// next to each other, so it reads them as one 32-byte piece instead of
+// kUnitChunks separate cache lines.
+__host__ __device__ inline u32 chunk_slot(u32 s, u32 U) { return (s % U) * kUnitChunks + s / U; }
 constexpr u32 kListCap = 512;                 // short-list slots per classify workgroup
 constexpr int kFinThreads = 1024;
 constexpr u32 kFinWaves = kFinThreads / kWave;
@@ -160,7 +166,7 @@ struct EncodeLayout {
     u64 samples, seg_count, win_cnt, chunk_base, blk_sure, n_m, n_b;
     u64 m_key, m_idx, b_mag, b_idx;
     u64 dm_key, dm_idx, db_key, db_idx;
-    u64 s_idx, s_val;
+    u64 s_ent;
     u64 total;
 };
 
@@ -224,8 +230,7 @@ static EncodeLayout make_layout(const Geom &g)
     L.db_key = take(slots * 8);
     L.db_idx = take(slots * 4);
     const u64 cap = (u64)g.W * g.C;
-    L.s_idx = take(cap * 4);
-    L.s_val = take(cap * 4);
+    L.s_ent = take(cap * 8);
     L.total = o;
     return L;
 }
@@ -478,8 +483,7 @@ __device__ __forceinline__ u64 elem_index(u64 base, int e)
 
 template <bool kVec4>
 __device__ __forceinline__ void append_hits(const u32 (&bits)[4], const bool (&hit)[4], u64 base,
-                                            u32 &run, u32 *__restrict__ my_idx,
-                                            u32 *__restrict__ my_val)
+                                            u32 &run, uint2 *__restrict__ my_ent)
 {
     const u64 b0 = __ballot(hit[0]), b1 = __ballot(hit[1]), b2 = __ballot(hit[2]),
               b3 = __ballot(hit[3]);
@@ -500,8 +504,7 @@ __device__ __forceinline__ void append_hits(const u32 (&bits)[4], const bool (&h
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         if (hit[e]) {
-            my_idx[pos[e]] = (u32)elem_index<kVec4>(base, e);
-            my_val[pos[e]] = bits[e];
+            my_ent[pos[e]] = make_uint2((u32)elem_index<kVec4>(base, e), bits[e]);
         }
     }
     run += popc64(b0) + popc64(b1) + popc64(b2) + popc64(b3);
@@ -521,7 +524,7 @@ template <bool kVec4>
 __device__ __forceinline__ void
 fused_body(const float *__restrict__ grad, float *__restrict__ residual, Geom g,
         const EncodeCtl *__restrict__ ctl, u32 *__restrict__ partials,
-        u32 *__restrict__ seg_count, u32 *__restrict__ s_idx, u32 *__restrict__ s_val)
+        u32 *__restrict__ seg_count, uint2 *__restrict__ s_ent)
 {
     __shared__ u32 h[kMaxBins];
     const Bins bins = ctl->bins;
@@ -533,7 +536,7 @@ fused_body(const float *__restrict__ grad, float *__restrict__ residual, Geom g,
     for (u32 w = blockIdx.x * kFusedWaves + threadIdx.x / kWave; w < g.W; w += wave_stride) {
         const u64 c0 = (u64)w * g.C;
         const u64 c1 = c0 + g.C < g.d ? c0 + g.C : g.d;
-        u32 *my_idx = s_idx + c0, *my_val = s_val + c0;
+        uint2 *my_ent = s_ent + c0;
         u32 run = 0;
         auto keep = [&](const u32 (&bits)[4], const bool (&valid)[4], u64 base) {
             bool hit[4];
@@ -543,7 +546,7 @@ fused_body(const float *__restrict__ grad, float *__restrict__ residual, Geom g,
                 hit[e] = valid[e] && m >= bins.t_lo;
                 if (hit[e]) atomicAdd(&h[bin_of(bins, m)], 1u);
             }
-            append_hits<kVec4>(bits, hit, base, run, my_idx, my_val);
+            append_hits<kVec4>(bits, hit, base, run, my_ent);
         };
         const bool all_valid[4] = {true, true, true, true};
         // NR full iterations at a time, all loads issued before the first use. Every
@@ -609,7 +612,7 @@ fused_body(const float *__restrict__ grad, float *__restrict__ residual, Geom g,
             }
             keep(bits, valid, base);
         }
-        if (lane_id() == 0) seg_count[w] = run;
+        if (lane_id() == 0) seg_count[chunk_slot(w, g.U)] = run;
     }
     __syncthreads();
     // The workgroup's histogram goes out as one dense row with plain stores:
@@ -625,23 +628,22 @@ fused_body(const float *__restrict__ grad, float *__restrict__ residual, Geom g,
 // ---------------------------------------------------------------------------
 struct Candidates {
     const u32 *__restrict__ seg_count;
-    const u32 *__restrict__ s_idx;
-    const u32 *__restrict__ s_val;
+    const uint2 *__restrict__ s_ent;
     const float *__restrict__ a;
     u64 d;
-    u32 C;
+    u32 C, U;
     bool dense;
 
     __device__ __forceinline__ u32 count(u32 s) const
     {
-        if (!dense) return seg_count[s];
+        if (!dense) return seg_count[chunk_slot(s, U)];
         const u64 c0 = (u64)s * C;
         return (u32)(c0 + C < d ? C : d - c0);
     }
     __device__ __forceinline__ void entry(u32 s, u32 j, u32 *idx, u32 *bits) const
     {
         const u64 at = (u64)s * C + j;
-        if (!dense) { *idx = s_idx[at]; *bits = s_val[at]; }
+        if (!dense) { const uint2 e = s_ent[at]; *idx = e.x; *bits = e.y; }
         else { *idx = (u32)at; *bits = __float_as_uint(a[at]); }
     }
 };
@@ -815,7 +817,7 @@ pick_body(const u32 *__restrict__ hist, Geom g, EncodeCtl *ctl)
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ void
 classify_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ seg_count,
-           const u32 *__restrict__ s_idx, const u32 *__restrict__ s_val,
+           const uint2 *__restrict__ s_ent,
            u32 *__restrict__ win_cnt, u32 *__restrict__ blk_sure, u32 *__restrict__ n_m,
            u32 *__restrict__ n_b, u64 *__restrict__ m_key, u32 *__restrict__ m_idx,
            u32 *__restrict__ b_mag, u32 *__restrict__ b_idx)
@@ -830,7 +832,7 @@ classify_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ s
         if (threadIdx.x == 0) { blk_sure[blockIdx.x] = 0u; n_m[blockIdx.x] = 0u; n_b[blockIdx.x] = 0u; }
         return;
     }
-    const Candidates cand{seg_count, s_idx, s_val, nullptr, g.d, g.C, false};
+    const Candidates cand{seg_count, s_ent, nullptr, g.d, g.C, g.U, false};
     const UnitWalk walk(cand, g, u);
     if (threadIdx.x == 0) { cnt_m = 0u; cnt_b = 0u; cnt_sure = 0u; }
     if (lane < kUnitChunks) per_chunk[wave][lane] = 0u;
@@ -983,8 +985,8 @@ __device__ __forceinline__ bool pair_le(u64 hi, u32 lo, const Pair96 &p)
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ void
 finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__ a,
-           const u32 *__restrict__ seg_count, const u32 *__restrict__ s_idx,
-           const u32 *__restrict__ s_val, u32 *win_cnt, const u32 *__restrict__ blk_sure,
+           const u32 *__restrict__ seg_count, const uint2 *__restrict__ s_ent,
+           u32 *win_cnt, const u32 *__restrict__ blk_sure,
            const u32 *__restrict__ n_m, const u32 *__restrict__ n_b,
            const u64 *__restrict__ m_key, const u32 *__restrict__ m_idx,
            const u32 *__restrict__ b_mag, const u32 *__restrict__ b_idx, u64 *dm_key,
@@ -1004,7 +1006,7 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
     const u32 tid = threadIdx.x;
     const u32 wave = tid / kWave, lane = lane_id();
     const bool dense = ctl->dense != 0u;
-    const Candidates cand{seg_count, s_idx, s_val, a, g.d, g.C, dense};
+    const Candidates cand{seg_count, s_ent, a, g.d, g.C, g.U, dense};
     // every candidate, split wavefront by chunk; f(index, pattern, chunk)
     auto each_s = [&](auto &&f) {
         for (u32 s = wave; s < g.W; s += kFinWaves) {
@@ -1237,14 +1239,14 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ void
 emit_body(Geom g, PhiloxSeed seed, const EncodeCtl *__restrict__ ctl,
-       const u32 *__restrict__ seg_count, const u32 *__restrict__ s_idx,
-       const u32 *__restrict__ s_val, const u32 *__restrict__ chunk_base,
+       const u32 *__restrict__ seg_count, const uint2 *__restrict__ s_ent,
+       const u32 *__restrict__ chunk_base,
        u32 *__restrict__ out_idx, float *__restrict__ out_val, float *residual)
 {
     const u32 u = blockIdx.x * kWalkWaves + threadIdx.x / kWave;
     if (u >= g.U) return;
     const u32 lane = lane_id();
-    const Candidates cand{seg_count, s_idx, s_val, residual, g.d, g.C, ctl->dense != 0u};
+    const Candidates cand{seg_count, s_ent, residual, g.d, g.C, g.U, ctl->dense != 0u};
     const UnitWalk walk(cand, g, u);
     const u32 my_chunk = u + lane * g.U;
     const u32 my_base = (lane < kUnitChunks && my_chunk < g.W) ? chunk_base[my_chunk] : 0u;
@@ -1339,7 +1341,7 @@ __global__ void __launch_bounds__(kFusedThreads) k_fused(Batch B, Geom g, Encode
 {
     const Member m(B);
     fused_body<kVec4>(m.grad, m.residual, g, m.at<EncodeCtl>(L.ctl), m.at<u32>(L.partials),
-                      m.at<u32>(L.seg_count), m.at<u32>(L.s_idx), m.at<u32>(L.s_val));
+                      m.at<u32>(L.seg_count), m.at<uint2>(L.s_ent));
 }
 
 __global__ void __launch_bounds__(kReduceThreads) k_reduce(Batch B, u32 n_rows, EncodeLayout L)
@@ -1357,8 +1359,8 @@ __global__ void __launch_bounds__(kPickThreads) k_pick(Batch B, Geom g, EncodeLa
 __global__ void __launch_bounds__(kWalkThreads) k_classify(Batch B, Geom g, EncodeLayout L)
 {
     const Member m(B);
-    classify_body(g, m.seed, m.at<EncodeCtl>(L.ctl), m.at<u32>(L.seg_count), m.at<u32>(L.s_idx),
-                  m.at<u32>(L.s_val), m.at<u32>(L.win_cnt), m.at<u32>(L.blk_sure),
+    classify_body(g, m.seed, m.at<EncodeCtl>(L.ctl), m.at<u32>(L.seg_count),
+                  m.at<uint2>(L.s_ent), m.at<u32>(L.win_cnt), m.at<u32>(L.blk_sure),
                   m.at<u32>(L.n_m), m.at<u32>(L.n_b), m.at<u64>(L.m_key), m.at<u32>(L.m_idx),
                   m.at<u32>(L.b_mag), m.at<u32>(L.b_idx));
 }
@@ -1367,7 +1369,7 @@ __global__ void __launch_bounds__(kFinThreads) k_finalize(Batch B, Geom g, Encod
 {
     const Member m(B);
     finalize_body(g, m.seed, m.at<EncodeCtl>(L.ctl), m.residual, m.at<u32>(L.seg_count),
-                  m.at<u32>(L.s_idx), m.at<u32>(L.s_val), m.at<u32>(L.win_cnt),
+                  m.at<uint2>(L.s_ent), m.at<u32>(L.win_cnt),
                   m.at<u32>(L.blk_sure), m.at<u32>(L.n_m), m.at<u32>(L.n_b), m.at<u64>(L.m_key),
                   m.at<u32>(L.m_idx), m.at<u32>(L.b_mag), m.at<u32>(L.b_idx), m.at<u64>(L.dm_key),
                   m.at<u32>(L.dm_idx), m.at<u64>(L.db_key), m.at<u32>(L.db_idx),
@@ -1377,8 +1379,8 @@ __global__ void __launch_bounds__(kFinThreads) k_finalize(Batch B, Geom g, Encod
 __global__ void __launch_bounds__(kWalkThreads) k_emit(Batch B, Geom g, EncodeLayout L)
 {
     const Member m(B);
-    emit_body(g, m.seed, m.at<EncodeCtl>(L.ctl), m.at<u32>(L.seg_count), m.at<u32>(L.s_idx),
-              m.at<u32>(L.s_val), m.at<u32>(L.chunk_base), m.out_idx, m.out_val, m.residual);
+    emit_body(g, m.seed, m.at<EncodeCtl>(L.ctl), m.at<u32>(L.seg_count), m.at<uint2>(L.s_ent),
+              m.at<u32>(L.chunk_base), m.out_idx, m.out_val, m.residual);
 }
 
 }  // namespace rtopk
@@ -1601,11 +1603,12 @@ extern "C" int rtopk_encode_stats(const void *workspace, void *stream_v,
     uint64_t superset = 0;
     if (c.W > 0 && c.W <= kTargetChunks) {
         const EncodeLayout L = make_layout(Geom{});   // the offset of seg_count is fixed
-        std::vector<u32> counts(c.W);
-        if (hipMemcpy(counts.data(), (const char *)workspace + L.seg_count, (size_t)c.W * 4,
-                      hipMemcpyDeviceToHost) != hipSuccess)
+        std::vector<u32> counts(kTargetChunks);
+        if (hipMemcpy(counts.data(), (const char *)workspace + L.seg_count,
+                      (size_t)kTargetChunks * 4, hipMemcpyDeviceToHost) != hipSuccess)
             return RTOPK_EHIP;
-        for (u32 x : counts) superset += x;
+        const u32 U = c.W < kMaxUnits ? c.W : kMaxUnits;
+        for (u32 s2 = 0; s2 < c.W; ++s2) superset += counts[chunk_slot(s2, U)];
     }
     host_out->error_flags = c.err;
     host_out->path = c.path | (c.dense ? 2u : 0u);
