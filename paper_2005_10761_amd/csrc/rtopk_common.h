@@ -27,8 +27,10 @@ __device__ __forceinline__ u64 sample_key(u32 index, const PhiloxSeed &s)
     u32 k0 = s.seed_lo, k1 = s.seed_hi;
 #pragma unroll
     for (int i = 0; i < 10; ++i) {
-        const u32 hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
-        const u32 hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        // one 32 x 32 -> 64 bit multiply per product (both halves from one instruction)
+        const u64 p0 = (u64)0xD2511F53u * c0, p1 = (u64)0xCD9E8D57u * c2;
+        const u32 hi0 = (u32)(p0 >> 32), lo0 = (u32)p0;
+        const u32 hi1 = (u32)(p1 >> 32), lo1 = (u32)p1;
         const u32 n0 = hi1 ^ c1 ^ k0;
         const u32 n2 = hi0 ^ c3 ^ k1;
         c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
