@@ -479,6 +479,43 @@ def test_batch_members_match_the_oracle_one_by_one(n, d, misalign):
         assert np.array_equal(u.bits(out.cpu().numpy()), u.bits(want))
 
 
+@pytest.mark.parametrize("n,d,r,k,force", [(5, 37, 9, 4, 0), (2, 1, 1, 1, 0), (3, 5000, 5000, 17, 0),
+                                           (4, 30_000, 600, 600, 0), (3, 60_000, 900, 90, 1),
+                                           (3, 60_000, 900, 90, 2), (6, 4097, 300, 30, 3)])
+def test_batch_small_sizes_special_shapes_and_forced_fallbacks(n, d, r, k, force):
+    """Tiny vectors, r = d, r = k, and the exact fallback paths forced for every
+    member of a batched call."""
+    import torch
+    u = _u()
+    rt = u.rt
+    dev = u.DEV
+    rng = np.random.default_rng(1000 * n + d)
+    stride = rt.encode_workspace_bytes(d, r, k)
+    ws = torch.empty(n * stride, dtype=torch.uint8, device=dev)
+    ws.fill_(0x5A)
+    gs = [(rng.standard_normal(d) * 10.0 ** rng.uniform(-3, 0, d)).astype(np.float32) for _ in range(n)]
+    ms = [(rng.standard_normal(d) * 1e-2).astype(np.float32) for _ in range(n)]
+    grads = [torch.from_numpy(g).to(dev) for g in gs]
+    resid = [torch.from_numpy(m).to(dev) for m in ms]
+    out_i = [torch.full((k,), -1, dtype=torch.int32, device=dev) for _ in range(n)]
+    out_v = [torch.full((k,), float("nan"), dtype=torch.float32, device=dev) for _ in range(n)]
+    seeds = [7 + 13 * i for i in range(n)]
+    if force:
+        rt.force_next_encode(force)
+    rt.encode_batch(grads, resid, r, k, seeds, 5, out_i, out_v, ws)
+    torch.cuda.synchronize()
+    for i in range(n):
+        st = rt.encode_stats(ws[i * stride:(i + 1) * stride])
+        assert st["error_flags"] == 0, (i, st)
+        if force & 1:
+            assert st["path"] & 2, (i, st)
+        if force & 2 and r > k:
+            assert st["path"] & 1, (i, st)
+        want = oracle.encode(gs[i], ms[i], r, k, seeds[i], 5)
+        got = (out_i[i].cpu().numpy().view(np.uint32), out_v[i].cpu().numpy(), resid[i].cpu().numpy())
+        u.assert_encode_equal(got, want, f"member {i}")
+
+
 def test_batch_rejects_bad_arguments():
     import torch
     u = _u()
