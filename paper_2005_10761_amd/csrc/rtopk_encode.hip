@@ -351,10 +351,23 @@ sample_body(const float *__restrict__ grad, const float *__restrict__ residual, 
             // offset in [0, len - 4], scaled from the hash instead of a remainder
             p += (u64)(((u64)hsh * (u64)(len - 3)) >> 32);
         }
+        const bool aligned = (((uintptr_t)grad | (uintptr_t)residual) & 15u) == 0;
+        if (aligned && len > 4 && (p & ~3ull) + 4 <= g.d) {
+            // one 16-byte load per array, from one cache line each (the four elements
+            // may start up to three before the stratum: it stays a spread-out sample)
+            p &= ~3ull;
+            const float4 gv = *reinterpret_cast<const float4 *>(grad + p);
+            const float4 mv = *reinterpret_cast<const float4 *>(residual + p);
+            out[0] = mag_of(__float_as_uint(gv.x + mv.x));
+            out[1] = mag_of(__float_as_uint(gv.y + mv.y));
+            out[2] = mag_of(__float_as_uint(gv.z + mv.z));
+            out[3] = mag_of(__float_as_uint(gv.w + mv.w));
+        } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const u64 i = p + e;
-            if (i < end) out[e] = mag_of(__float_as_uint(grad[i] + residual[i]));
+            for (int e = 0; e < 4; ++e) {
+                const u64 i = p + e;
+                if (i < end) out[e] = mag_of(__float_as_uint(grad[i] + residual[i]));
+            }
         }
     }
     reinterpret_cast<uint4 *>(samples)[j] = make_uint4(out[0], out[1], out[2], out[3]);
