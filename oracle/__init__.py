@@ -63,6 +63,12 @@ def lib() -> ctypes.CDLL:
             _u32p, _f32p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_uint64,
             ctypes.c_float, ctypes.c_float, _f32p, _f32p]
         L.rtopk_oracle_aggregate_update_f32.restype = ctypes.c_int
+        for name, ft in (("rtopk_oracle_aggregate_update_momentum", ctypes.c_double),
+                         ("rtopk_oracle_aggregate_update_momentum_f32", ctypes.c_float)):
+            fn = getattr(L, name)
+            fn.argtypes = [_u32p, _f32p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_uint64,
+                           ft, ft, ft, _f32p, _f32p, _f32p, _f32p]
+            fn.restype = ctypes.c_int
         _LIB = L
     return _LIB
 
@@ -166,3 +172,36 @@ def aggregate_update_f32(idx, val, n: int, d: int, eta: float, scale: float,
     """The same update in binary32: worker-order sum, / n, fma(-(eta * scale), mean, omega)."""
     return _aggregate_update("rtopk_oracle_aggregate_update_f32", idx, val, n, d, eta, scale,
                              omega)
+
+
+def _aggregate_update_momentum(fn_name, idx, val, n, d, eta, scale, mu, omega, velocity):
+    idx = np.ascontiguousarray(idx, dtype=np.uint32).reshape(-1)
+    val = _f32(val).reshape(-1)
+    omega = _f32(omega).reshape(-1)
+    velocity = _f32(velocity).reshape(-1)
+    if (idx.size != val.size or n < 1 or idx.size % n != 0 or omega.size != d
+            or velocity.size != d):
+        raise ValueError("idx/val must hold n messages of equal length, omega and velocity d values")
+    k = idx.size // n
+    w_out = np.empty(d, dtype=np.float32)
+    v_out = np.empty(d, dtype=np.float32)
+    rc = getattr(lib(), fn_name)(idx.ctypes.data_as(_u32p), val.ctypes.data_as(_f32p), n, k, d,
+                                 eta, scale, mu, omega.ctypes.data_as(_f32p),
+                                 velocity.ctypes.data_as(_f32p), w_out.ctypes.data_as(_f32p),
+                                 v_out.ctypes.data_as(_f32p))
+    _check(rc, fn_name)
+    return w_out, v_out
+
+
+def aggregate_update_momentum(idx, val, n: int, d: int, eta: float, scale: float, mu: float,
+                              omega: np.ndarray, velocity: np.ndarray):
+    """v <- mu v + scale * mean; omega <- omega - eta v; binary64. Returns (omega, velocity)."""
+    return _aggregate_update_momentum("rtopk_oracle_aggregate_update_momentum", idx, val, n, d,
+                                      eta, scale, mu, omega, velocity)
+
+
+def aggregate_update_momentum_f32(idx, val, n: int, d: int, eta: float, scale: float, mu: float,
+                                  omega: np.ndarray, velocity: np.ndarray):
+    """The same in binary32: u = scale * mean, v' = fma(mu, v, u), omega' = fma(-eta, v', omega)."""
+    return _aggregate_update_momentum("rtopk_oracle_aggregate_update_momentum_f32", idx, val, n, d,
+                                      eta, scale, mu, omega, velocity)

@@ -331,3 +331,69 @@ int rtopk_oracle_aggregate_update_f32(const uint32_t *idx, const float *val,
     free(avg);
     return ORACLE_OK;
 }
+
+/*
+ * The master's update with momentum, the optimiser the experiments section
+ * names (momentum SGD; the paper gives no formula, this is the common one):
+ *     ghat = (1/n) sum_i ghat_i
+ *     v    <- mu * v + scale * ghat
+ *     w    <- w - eta * v
+ * for every coordinate (the velocity decays where nothing was sent). mu = 0
+ * is Algorithm 1's plain step. binary64 throughout, one rounding per output.
+ */
+int rtopk_oracle_aggregate_update_momentum(const uint32_t *idx, const float *val,
+                                           uint32_t n, uint64_t k, uint64_t d,
+                                           double eta, double scale, double mu,
+                                           const float *omega_in, const float *vel_in,
+                                           float *omega_out, float *vel_out)
+{
+    if (!idx || !val || !omega_in || !vel_in || !omega_out || !vel_out || n < 1 || k < 1 ||
+        d < 1 || d > 0xFFFFFFFFull)
+        return ORACLE_EINVAL;
+    double *acc = (double *)calloc((size_t)d, sizeof *acc);
+    if (!acc) return ORACLE_ENOMEM;
+    for (uint32_t w = 0; w < n; ++w)
+        for (uint64_t j = 0; j < k; ++j) {
+            uint32_t i = idx[(uint64_t)w * k + j];
+            if (i >= d) { free(acc); return ORACLE_EINVAL; }
+            acc[i] += (double)val[(uint64_t)w * k + j];
+        }
+    for (uint64_t i = 0; i < d; ++i) {
+        const double ghat = acc[i] / (double)n;
+        const double v = mu * (double)vel_in[i] + scale * ghat;
+        vel_out[i] = (float)v;
+        omega_out[i] = (float)((double)omega_in[i] - eta * v);
+    }
+    free(acc);
+    return ORACLE_OK;
+}
+
+/*
+ * The same in binary32 with a fixed order of operations: the average as
+ * rtopk_oracle_aggregate_f32 forms it, u = scale * average (one rounding),
+ * v' = fma(mu, v, u), w' = fma(-eta, v', w), where v' is the ROUNDED new
+ * velocity (the one that is stored).
+ */
+int rtopk_oracle_aggregate_update_momentum_f32(const uint32_t *idx, const float *val,
+                                               uint32_t n, uint64_t k, uint64_t d,
+                                               float eta, float scale, float mu,
+                                               const float *omega_in, const float *vel_in,
+                                               float *omega_out, float *vel_out)
+{
+    if (!idx || !val || !omega_in || !vel_in || !omega_out || !vel_out || n < 1 || k < 1 ||
+        d < 1 || d > 0xFFFFFFFFull)
+        return ORACLE_EINVAL;
+    float *avg = (float *)malloc((size_t)d * sizeof *avg);
+    if (!avg) return ORACLE_ENOMEM;
+    int rc = rtopk_oracle_aggregate_f32(idx, val, n, k, d, avg);
+    if (rc != ORACLE_OK) { free(avg); return rc; }
+    const float neg_eta = -eta;
+    for (uint64_t i = 0; i < d; ++i) {
+        volatile float u = scale * avg[i];
+        const float v = fmaf(mu, vel_in[i], u);
+        vel_out[i] = v;
+        omega_out[i] = fmaf(neg_eta, v, omega_in[i]);
+    }
+    free(avg);
+    return ORACLE_OK;
+}

@@ -493,3 +493,93 @@ def test_aggregate_update_copies_coordinates_the_average_does_not_move():
         out = fn(idx, val, 2, 4, 0.5, 1.0, omega)
         assert list(bits(out)) == [bits(np.float32(0.75)), 0x7FA00001, 0x80000000,
                                    bits(np.float32(3.5))]
+
+
+# --------------------------------------------------------------------------
+# master with momentum: v <- mu v + scale * ghat ; omega <- omega - eta v
+# --------------------------------------------------------------------------
+def test_momentum_update_worked_example_by_hand():
+    # the hand example of the plain update, with a velocity: mean = [0, 1, 0, 2, -1, 0]
+    idx = np.array([1, 4, 1, 3], np.uint32)
+    val = np.array([0.5, -2.0, 1.5, 4.0], np.float32)
+    omega = np.array([1, 2, 3, 4, 5, 6], np.float32)
+    vel = np.array([2, 0, -4, 1, 0, 8], np.float32)
+    for fn in (oracle.aggregate_update_momentum, oracle.aggregate_update_momentum_f32):
+        w, v = fn(idx, val, 2, 6, 0.5, 1.0, 0.5, omega, vel)
+        # v' = 0.5 v + mean = [1, 1, -2, 2.5, -1, 4]; w' = w - 0.5 v'
+        assert np.array_equal(v, np.array([1, 1, -2, 2.5, -1, 4], np.float32))
+        assert np.array_equal(w, np.array([0.5, 1.5, 4, 2.75, 5.5, 4], np.float32))
+        w, v = fn(idx, val, 2, 6, 0.25, 2.0, 0.0, omega, vel)
+        # mu = 0, scale = 2: v' = 2 mean; w' = w - 0.25 v'
+        assert np.array_equal(v, np.array([0, 2, 0, 4, -2, 0], np.float32))
+        assert np.array_equal(w, np.array([1, 1.5, 3, 3, 5.5, 6], np.float32))
+
+
+def test_momentum_update_reduces_to_the_plain_update_and_matches_the_closed_form():
+    rng = np.random.default_rng(81)
+    d, n, k = 300, 4, 40
+    idx = np.stack([np.sort(rng.choice(d, k, replace=False)) for _ in range(n)]).astype(np.uint32)
+    val = rng.standard_normal((n, k)).astype(np.float32)
+    omega = rng.standard_normal(d).astype(np.float32)
+    zero = np.zeros(d, np.float32)
+    eta, scale = float(np.float32(0.125)), 2.0            # dyadic: eta * scale is exact
+    # mu = 0: the weights move as in the plain update, whatever the old velocity was
+    w, v = oracle.aggregate_update_momentum(idx, val, n, d, eta, scale, 0.0, omega,
+                                            rng.standard_normal(d).astype(np.float32))
+    assert np.array_equal(w, oracle.aggregate_update(idx, val, n, d, eta, scale, omega))
+    assert np.array_equal(v, (scale * oracle.aggregate(idx, val, n, d).astype(np.float64))
+                          .astype(np.float32))
+    # the same message T times from rest: v_T = g (1 - mu^T) / (1 - mu),
+    # w_T = w_0 - eta g (T - mu (1 - mu^T) / (1 - mu)) / (1 - mu)
+    mu, T = 0.5, 6
+    g = scale * oracle.aggregate(idx, val, n, d).astype(np.float64)
+    w, v = omega.astype(np.float64), zero.astype(np.float64)
+    w32, v32 = omega, zero
+    for _ in range(T):
+        w32, v32 = oracle.aggregate_update_momentum(idx, val, n, d, eta, scale, mu, w32, v32)
+    v_T = g * (1 - mu ** T) / (1 - mu)
+    w_T = omega.astype(np.float64) - eta * g * (T - mu * (1 - mu ** T) / (1 - mu)) / (1 - mu)
+    assert np.allclose(v32, v_T, rtol=1e-6, atol=1e-7)
+    assert np.allclose(w32, w_T, rtol=1e-5, atol=1e-6)
+    # nothing sent anywhere near coordinate i: the velocity only decays there
+    untouched = np.setdiff1d(np.arange(d), idx.reshape(-1))
+    vel = rng.standard_normal(d).astype(np.float32)
+    w, v = oracle.aggregate_update_momentum(idx, val, n, d, eta, scale, 0.25, omega, vel)
+    assert np.array_equal(v[untouched], (0.25 * vel[untouched].astype(np.float64)).astype(np.float32))
+    assert np.array_equal(w[untouched], (omega[untouched].astype(np.float64)
+                                         - eta * 0.25 * vel[untouched].astype(np.float64))
+                          .astype(np.float32))
+
+
+def test_momentum_update_f32_variant_is_close_and_uses_the_stored_velocity():
+    rng = np.random.default_rng(82)
+    d, n, k = 400, 5, 60
+    idx = np.stack([np.sort(rng.choice(d, k, replace=False)) for _ in range(n)]).astype(np.uint32)
+    val = (rng.standard_normal((n, k)) * 10.0 ** rng.uniform(-3, 1, (n, k))).astype(np.float32)
+    omega = rng.standard_normal(d).astype(np.float32)
+    vel = rng.standard_normal(d).astype(np.float32)
+    eta, scale, mu = float(np.float32(0.05)), float(np.float32(2.5)), float(np.float32(0.9))
+    w64, v64 = oracle.aggregate_update_momentum(idx, val, n, d, eta, scale, mu, omega, vel)
+    w32, v32 = oracle.aggregate_update_momentum_f32(idx, val, n, d, eta, scale, mu, omega, vel)
+    dense = np.zeros(d)
+    np.add.at(dense, idx.reshape(-1).astype(np.int64), np.abs(val.reshape(-1).astype(np.float64)) / n)
+    size_v = mu * np.abs(vel.astype(np.float64)) + scale * dense
+    assert np.all(np.abs(v32.astype(np.float64) - v64) <= 1e-6 * size_v + 1e-30)
+    assert np.all(np.abs(w32.astype(np.float64) - w64)
+                  <= 1e-6 * (np.abs(omega.astype(np.float64)) + eta * size_v) + 1e-30)
+    # the weight step uses the velocity as stored (rounded to binary32)
+    want_w = np.array([np.float32(float(omega[i]) - eta * float(v32[i])) for i in range(d)])
+    assert np.all(np.abs(w32.astype(np.float64) - want_w) <= 6e-8 * (np.abs(want_w) + 1e-30) + 1e-37)
+
+
+def test_momentum_update_f32_uses_one_rounding_per_fused_step():
+    x = np.float32(1.0 + 2.0 ** -12)      # x * x = 1 + 2^-11 + 2^-24 needs 25 bits
+    one_idx, one_val = np.array([0], np.uint32), np.array([-1.0], np.float32)
+    # velocity step: mu * v + u with mu = v = x, u = -1 -> 2^-11 + 2^-24 exactly when fused
+    w, v = oracle.aggregate_update_momentum_f32(one_idx, one_val, 1, 1, 0.0, 1.0, float(x),
+                                                np.array([5.0], np.float32), np.array([x]))
+    assert float(v[0]) == 2.0 ** -11 + 2.0 ** -24 and float(w[0]) == 5.0
+    # weight step: w - eta * v' with eta = v' = x (mu = 0, the message is x), w = 1
+    w, v = oracle.aggregate_update_momentum_f32(one_idx, np.array([x]), 1, 1, float(x), 1.0, 0.0,
+                                                np.array([1.0], np.float32), np.array([9.0], np.float32))
+    assert float(v[0]) == float(x) and float(w[0]) == -(2.0 ** -11 + 2.0 ** -24)
