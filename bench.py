@@ -272,7 +272,18 @@ def main() -> int:
     upd[1].record(stream)
     torch.cuda.synchronize()
     upd_ms_call = upd[0].elapsed_time(upd[1]) / upd_calls
-    del omegas
+    # ... and with momentum (a dense pass over weights and velocity)
+    vels = [torch.zeros(d, dtype=torch.float32, device=dev) for _ in range(len(omegas))]
+    for om, ve in zip(omegas, vels):
+        rt.aggregate_update_momentum(idx, val, n, k, 0.1, r / k, 0.9, om, ve, stream)
+    upd[0].record(stream)
+    for c in range(upd_calls):
+        rt.aggregate_update_momentum(idx, val, n, k, 0.1, r / k, 0.9, omegas[c % len(omegas)],
+                                     vels[c % len(omegas)], stream)
+    upd[1].record(stream)
+    torch.cuda.synchronize()
+    mom_ms_call = upd[0].elapsed_time(upd[1]) / upd_calls
+    del omegas, vels
 
     if args.copy_calibration > 0:
         src = grads[0][0]
@@ -313,6 +324,8 @@ def main() -> int:
         "aggregate_GBps": round(4.0 * d / (agg_ms_call * 1e-3) / 1e9, 2),
         "aggregate_ms_per_call": round(agg_ms_call, 4),
         "aggregate_update_ms_per_call": round(upd_ms_call, 4),
+        "aggregate_update_momentum_ms_per_call": round(mom_ms_call, 4),
+        "aggregate_update_momentum_GBps": round(16.0 * d / (mom_ms_call * 1e-3) / 1e9, 2),
         "per_call": per_call,
         "wall_ms_per_step": round((t_wall1 - t_wall0) * 1e3 / K, 4),
         "last_encode": {"path": stats["path"], "superset": stats["superset_size"],

@@ -161,6 +161,30 @@ int rtopk_aggregate_update(const uint32_t *idx, const float *val,
                            void *workspace, uint64_t workspace_bytes, void *stream);
 
 /*
+ * The master's update with momentum, the optimiser the experiments section
+ * uses (momentum SGD; the paper prints no formula, this is the common one):
+ *     ghat = (1/n) * sum_{w<n} message_w
+ *     velocity[i] <- mu * velocity[i] + scale * ghat[i]
+ *     omega[i]    <- omega[i] - eta * velocity[i]
+ * for every i: the velocity decays where nothing was sent, so this is a dense
+ * pass over both arrays (16 bytes per coordinate plus the messages). mu = 0
+ * moves the weights as rtopk_aggregate_update does.
+ *
+ * Arithmetic, all binary32: the average exactly as in rtopk_aggregate;
+ * u = scale * average (one rounding); velocity = fma(mu, velocity, u);
+ * omega = fma(-eta, velocity, omega) with the rounded new velocity.
+ * Reproducible bit for bit; no atomics, no workspace.
+ *
+ * idx, val, n, k, d   as for rtopk_aggregate
+ * omega, velocity     device, [d] binary32 each, updated in place; they must
+ *                     not overlap each other, idx or val
+ */
+int rtopk_aggregate_update_momentum(const uint32_t *idx, const float *val,
+                                    uint32_t n, uint64_t k, uint64_t d,
+                                    float eta, float scale, float mu,
+                                    float *omega, float *velocity, void *stream);
+
+/*
  * Diagnostics of the most recent rtopk_encode that used `workspace`.
  * Synchronises `stream`, then copies a few counters to the host. Not part of
  * the hot path; tests and profiling use it.

@@ -16,6 +16,7 @@ _LIB: Optional[ctypes.CDLL] = None
 EXPORTS = ("rtopk_encode_workspace_bytes", "rtopk_aggregate_workspace_bytes", "rtopk_encode",
            "rtopk_encode_batch",
            "rtopk_aggregate", "rtopk_aggregate_update", "rtopk_aggregate_update_workspace_bytes",
+           "rtopk_aggregate_update_momentum",
            "rtopk_encode_stats", "rtopk_trace_next_encode",
            "rtopk_force_next_encode", "rtopk_strerror", "rtopk_version")
 
@@ -63,6 +64,9 @@ def load_library() -> ctypes.CDLL:
     L.rtopk_aggregate_update.argtypes = [vp, vp, u32, u64, u64, ctypes.c_float, ctypes.c_float,
                                          vp, vp, u64, vp]
     L.rtopk_aggregate_update.restype = ctypes.c_int
+    L.rtopk_aggregate_update_momentum.argtypes = [vp, vp, u32, u64, u64, ctypes.c_float,
+                                                  ctypes.c_float, ctypes.c_float, vp, vp, vp]
+    L.rtopk_aggregate_update_momentum.restype = ctypes.c_int
     L.rtopk_encode_stats.argtypes = [vp, vp, ctypes.POINTER(EncodeStats)]
     L.rtopk_encode_stats.restype = ctypes.c_int
     L.rtopk_trace_next_encode.argtypes = [ctypes.c_int, vp, vp]
@@ -207,6 +211,24 @@ def aggregate_update(idx: torch.Tensor, val: torch.Tensor, n: int, k: int, eta: 
                                                _stream_handle(stream))
     if rc:
         raise RtopkError(rc, "rtopk_aggregate_update")
+
+
+def aggregate_update_momentum(idx: torch.Tensor, val: torch.Tensor, n: int, k: int, eta: float,
+                              scale: float, mu: float, omega: torch.Tensor,
+                              velocity: torch.Tensor, stream=None) -> None:
+    """rtopk_aggregate_update_momentum: enqueue velocity = mu * velocity + scale *
+    (average of the n messages); omega -= eta * velocity, both in place."""
+    _need(idx, torch.int32, "idx")
+    _need(val, torch.float32, "val")
+    _need(omega, torch.float32, "omega")
+    _need(velocity, torch.float32, "velocity")
+    if idx.numel() < n * k or val.numel() < n * k or velocity.numel() != omega.numel():
+        raise ValueError("idx/val must hold n*k entries; omega and velocity the same d")
+    rc = load_library().rtopk_aggregate_update_momentum(
+        _ptr(idx), _ptr(val), n, k, omega.numel(), eta, scale, mu, _ptr(omega), _ptr(velocity),
+        _stream_handle(stream))
+    if rc:
+        raise RtopkError(rc, "rtopk_aggregate_update_momentum")
 
 
 STAGES = {"prepare": 1, "fused": 2, "classify": 3, "finalize": 4, "emit": 5, "all": 100}

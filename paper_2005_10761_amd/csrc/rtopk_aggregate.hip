@@ -94,9 +94,20 @@ __device__ __forceinline__ u64 wave_lower_bounds(const u32 *__restrict__ idx, u3
     return ((u64)lo_hi << 32) | lo_lo;
 }
 
+// What the momentum form of the kernel does with the average of a coordinate:
+// u = scale * average, v <- fma(mu, v, u), w <- fma(neg_eta, v, w) with the
+// rounded new velocity.
+struct Momentum {
+    float scale, mu, neg_eta;
+    float *velocity;
+};
+
+// kMomentum == false: out[i] = average[i].
+// kMomentum == true:  out is the weight vector w; see Momentum.
+template <bool kMomentum>
 __global__ void __launch_bounds__(kAggThreads)
 k_aggregate(const u32 *__restrict__ idx, const float *__restrict__ val, u32 n, u64 k, u64 d,
-            u64 tiles, u32 tiles_per_wave, float *__restrict__ out)
+            u64 tiles, u32 tiles_per_wave, float *__restrict__ out, Momentum mom)
 {
     __shared__ float tile_s[kAggWaves][kAggTile];
     const u32 lane = lane_id(), wave = threadIdx.x / kWave;
@@ -110,7 +121,13 @@ k_aggregate(const u32 *__restrict__ idx, const float *__restrict__ val, u32 n, u
     const float fn = (float)n;
     const bool n_pow2 = (n & (n - 1u)) == 0u;
     const float rn = 1.0f / fn;
-    const bool out_vec = ((uintptr_t)out & 15u) == 0;
+    const bool out_vec =
+        (((uintptr_t)out | (kMomentum ? (uintptr_t)mom.velocity : (uintptr_t)0)) & 15u) == 0;
+    auto step = [&](float avg, float &v, float &w) {
+        const float u = mom.scale * avg;
+        v = fmaf(mom.mu, v, u);
+        w = fmaf(mom.neg_eta, v, w);
+    };
     const u32 groups = (n + kWave - 1) / kWave;    // workers are taken 64 at a time
     // lane w: where the current tile starts in the message of worker w (first group only;
     // with more than 64 workers the position is searched again for every tile)
@@ -181,15 +198,55 @@ k_aggregate(const u32 *__restrict__ idx, const float *__restrict__ val, u32 n, u
         }
         if (out_vec && tile_base + kAggTile <= d) {
             float4 *o4 = reinterpret_cast<float4 *>(out + tile_base);
-            for (int i = lane; i < kAggTile / 4; i += kWave) {
+            constexpr int kVecs = kAggTile / 4 / kWave;
+            // weights and velocity are read once and written once, in place: both
+            // carry the streaming hint (as in the encoder's streaming kernel, where
+            // the hint on load and store together is worth 15%)
+            typedef float f32x4 __attribute__((ext_vector_type(4)));
+            f32x4 vel[kMomentum ? kVecs : 1], wgt[kMomentum ? kVecs : 1];
+            f32x4 *v4 = nullptr, *w4 = reinterpret_cast<f32x4 *>(o4);
+            if (kMomentum) {
+                v4 = reinterpret_cast<f32x4 *>(mom.velocity + tile_base);
+#pragma unroll
+                for (int q = 0; q < kVecs; ++q) {
+                    vel[q] = __builtin_nontemporal_load(v4 + q * kWave + lane);
+                    wgt[q] = __builtin_nontemporal_load(w4 + q * kWave + lane);
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < kVecs; ++q) {
+                const int i = q * kWave + lane;
                 float4 v = reinterpret_cast<const float4 *>(tile)[i];
                 if (n_pow2) { v.x *= rn; v.y *= rn; v.z *= rn; v.w *= rn; }
                 else { v.x /= fn; v.y /= fn; v.z /= fn; v.w /= fn; }
-                o4[i] = v;
+                if (kMomentum) {
+                    const int m = kMomentum ? q : 0;
+                    const float avg[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        float ve = vel[m][c], we = wgt[m][c];
+                        step(avg[c], ve, we);
+                        vel[m][c] = ve;
+                        wgt[m][c] = we;
+                    }
+                    __builtin_nontemporal_store(vel[m], v4 + i);
+                    __builtin_nontemporal_store(wgt[m], w4 + i);
+                } else {
+                    o4[i] = v;
+                }
             }
         } else {
-            for (u64 i = lane; tile_base + i < tile_end; i += kWave)
-                out[tile_base + i] = tile[i] / fn;
+            for (u64 i = lane; tile_base + i < tile_end; i += kWave) {
+                const float avg = tile[i] / fn;
+                if (kMomentum) {
+                    float v = mom.velocity[tile_base + i], w = out[tile_base + i];
+                    step(avg, v, w);
+                    mom.velocity[tile_base + i] = v;
+                    out[tile_base + i] = w;
+                } else {
+                    out[tile_base + i] = avg;
+                }
+            }
         }
     }
 }
@@ -464,7 +521,30 @@ extern "C" int rtopk_aggregate(const uint32_t *idx, const float *val, uint32_t n
     const u32 tiles_per_wave = (u32)((tiles + kAggMaxWaves - 1) / kAggMaxWaves);
     const u64 waves = (tiles + tiles_per_wave - 1) / tiles_per_wave;
     const unsigned grid = (unsigned)((waves + kAggWaves - 1) / kAggWaves);
-    k_aggregate<<<grid, kAggThreads, 0, stream>>>(idx, val, n, k, d, tiles, tiles_per_wave, out);
+    k_aggregate<false><<<grid, kAggThreads, 0, stream>>>(idx, val, n, k, d, tiles, tiles_per_wave,
+                                                         out, Momentum{});
+    if (hipGetLastError() != hipSuccess) return RTOPK_EHIP;
+    return RTOPK_OK;
+}
+
+extern "C" int rtopk_aggregate_update_momentum(const uint32_t *idx, const float *val, uint32_t n,
+                                               uint64_t k, uint64_t d, float eta, float scale,
+                                               float mu, float *omega, float *velocity,
+                                               void *stream_v)
+{
+    if (!idx || !val || !omega || !velocity || n < 1 || k < 1 || d < 1 || d > 0xFFFFFFFFull)
+        return RTOPK_EINVAL;
+    {
+        const uintptr_t w0 = (uintptr_t)omega, v0 = (uintptr_t)velocity;
+        if (w0 < v0 + d * 4 && v0 < w0 + d * 4) return RTOPK_EINVAL;
+    }
+    hipStream_t stream = (hipStream_t)stream_v;
+    const u64 tiles = (d + kAggTile - 1) / kAggTile;
+    const u32 tiles_per_wave = (u32)((tiles + kAggMaxWaves - 1) / kAggMaxWaves);
+    const u64 waves = (tiles + tiles_per_wave - 1) / tiles_per_wave;
+    const unsigned grid = (unsigned)((waves + kAggWaves - 1) / kAggWaves);
+    k_aggregate<true><<<grid, kAggThreads, 0, stream>>>(idx, val, n, k, d, tiles, tiles_per_wave,
+                                                        omega, Momentum{scale, mu, -eta, velocity});
     if (hipGetLastError() != hipSuccess) return RTOPK_EHIP;
     return RTOPK_OK;
 }

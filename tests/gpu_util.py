@@ -88,6 +88,23 @@ def gpu_aggregate_update(idx: np.ndarray, val: np.ndarray, n: int, d: int, eta: 
     return tw.cpu().numpy()
 
 
+def gpu_aggregate_update_momentum(idx, val, n, d, eta, scale, mu, omega, velocity, offset=0):
+    """``offset`` (in elements) shifts omega and velocity off their 16-byte alignment."""
+    idx = np.ascontiguousarray(idx, np.uint32).reshape(-1)
+    val = np.ascontiguousarray(val, np.float32).reshape(-1)
+    k = idx.size // n
+    ti = torch.from_numpy(idx.view(np.int32)).to(DEV)
+    tv = torch.from_numpy(val).to(DEV)
+    wbuf = torch.zeros(d + offset, dtype=torch.float32, device=DEV)
+    vbuf = torch.zeros(d + offset, dtype=torch.float32, device=DEV)
+    tw, tvel = wbuf[offset:], vbuf[offset:]
+    tw.copy_(torch.from_numpy(np.ascontiguousarray(omega, np.float32)))
+    tvel.copy_(torch.from_numpy(np.ascontiguousarray(velocity, np.float32)))
+    rt.aggregate_update_momentum(ti, tv, n, k, eta, scale, mu, tw, tvel)
+    torch.cuda.synchronize()
+    return tw.cpu().numpy(), tvel.cpu().numpy()
+
+
 def assert_update_close(got, idx, val, n, d, eta, scale, omega, want64):
     """|gpu - ref| <= 1e-6 * (|omega| + |eta scale| sum_w |v_w| / n)."""
     size = np.zeros(d)

@@ -533,3 +533,71 @@ def test_batch_rejects_bad_arguments():
         rt.encode_batch([g], [g], r, k, [1], 0, [oi], [ov], ws)
     with pytest.raises(ValueError):
         rt.encode_batch([g], [m], r, k, [1, 2], 0, [oi], [ov], ws)
+
+
+# --------------------------------------------------------------------------
+# master with momentum: velocity = mu velocity + scale average; omega -= eta velocity
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("d,n,k,offset", [(5000, 3, 100, 0), (4096 * 5 + 3, 16, 700, 0),
+                                          (1_000_003, 8, 10_000, 0), (300_007, 5, 300, 1),
+                                          (70, 70, 5, 0), (100_000, 130, 50, 0), (1, 1, 1, 0),
+                                          (2048, 2, 2048, 0)])
+def test_momentum_update_random_messages(d, n, k, offset):
+    u = _u()
+    rng = np.random.default_rng(3 * d + n)
+    idx = np.stack([np.sort(rng.choice(d, k, replace=False)) for _ in range(n)]).astype(np.uint32)
+    val = (rng.standard_normal((n, k)) * 10.0 ** rng.uniform(-3, 1, (n, k))).astype(np.float32)
+    omega = rng.standard_normal(d).astype(np.float32)
+    vel = (rng.standard_normal(d) * 0.1).astype(np.float32)
+    eta, scale, mu = float(np.float32(0.05)), float(np.float32(n)), float(np.float32(0.9))
+    print(f"momentum d={d} n={n} k={k} offset={offset}", flush=True)
+    gw, gv = u.gpu_aggregate_update_momentum(idx, val, n, d, eta, scale, mu, omega, vel, offset)
+    ww, wv = oracle.aggregate_update_momentum_f32(idx, val, n, d, eta, scale, mu, omega, vel)
+    assert np.array_equal(u.bits(gv), u.bits(wv)) and np.array_equal(u.bits(gw), u.bits(ww))
+    w64, v64 = oracle.aggregate_update_momentum(idx, val, n, d, eta, scale, mu, omega, vel)
+    dense = np.zeros(d)
+    np.add.at(dense, idx.reshape(-1).astype(np.int64), np.abs(val.reshape(-1).astype(np.float64)) / n)
+    size_v = mu * np.abs(vel.astype(np.float64)) + scale * dense
+    assert np.all(np.abs(gv.astype(np.float64) - v64) <= 1e-6 * size_v + 1e-30)
+    assert np.all(np.abs(gw.astype(np.float64) - w64)
+                  <= 1e-6 * (np.abs(omega.astype(np.float64)) + eta * size_v) + 1e-30)
+
+
+def test_momentum_update_special_cases():
+    u = _u()
+    x = np.float32(1.0 + 2.0 ** -12)
+    one_idx = np.array([2], np.uint32)
+    # the single-rounding cases of the oracle's pins, at coordinate 2 of 5
+    w0, v0 = np.full(5, 5.0, np.float32), np.full(5, x, np.float32)
+    gw, gv = u.gpu_aggregate_update_momentum(one_idx, np.array([-1.0], np.float32), 1, 5, 0.0, 1.0,
+                                             float(x), w0, v0)
+    assert float(gv[2]) == 2.0 ** -11 + 2.0 ** -24 and np.all(gw == 5.0)
+    gw, gv = u.gpu_aggregate_update_momentum(one_idx, np.array([x]), 1, 5, float(x), 1.0, 0.0,
+                                             np.ones(5, np.float32), np.full(5, 9.0, np.float32))
+    assert float(gv[2]) == float(x) and float(gw[2]) == -(2.0 ** -11 + 2.0 ** -24)
+    assert np.all(gv[[0, 1, 3, 4]] == 0.0) and np.all(gw[[0, 1, 3, 4]] == 1.0)
+
+
+def test_momentum_training_loop_on_the_device_matches_the_oracle():
+    u = _u()
+    d, r, k, n = 150_001, 1500, 300, 4
+    rng = np.random.default_rng(29)
+    w_gpu = rng.standard_normal(d).astype(np.float32)
+    v_gpu = np.zeros(d, np.float32)
+    w_ref, v_ref = w_gpu.copy(), v_gpu.copy()
+    workers = [u.GpuWorker(d, r, k) for _ in range(n)]
+    res = [np.zeros(d, np.float32) for _ in range(n)]
+    for t in range(3):
+        mi, mv = [], []
+        for w in range(n):
+            g = (rng.standard_normal(d) * 0.01 + 0.001 * w_ref).astype(np.float32)
+            gi, gv, _ = workers[w].encode(g, 42 + w, t)
+            oi, ov, res[w] = oracle.encode(g, res[w], r, k, 42 + w, t)
+            assert np.array_equal(gi, oi) and np.array_equal(u.bits(gv), u.bits(ov))
+            mi.append(oi)
+            mv.append(ov)
+        ai, av = np.stack(mi), np.stack(mv)
+        w_gpu, v_gpu = u.gpu_aggregate_update_momentum(ai, av, n, d, 0.1, 1.0, 0.9, w_gpu, v_gpu)
+        w_ref, v_ref = oracle.aggregate_update_momentum_f32(ai, av, n, d, 0.1, 1.0, 0.9, w_ref, v_ref)
+        assert np.array_equal(u.bits(w_gpu), u.bits(w_ref))
+        assert np.array_equal(u.bits(v_gpu), u.bits(v_ref))
