@@ -110,7 +110,8 @@ def assert_update_close(got, idx, val, n, d, eta, scale, omega, want64):
     size = np.zeros(d)
     np.add.at(size, np.asarray(idx).reshape(-1).astype(np.int64),
               np.abs(np.asarray(val, np.float64).reshape(-1)) / n)
-    size = np.abs(omega.astype(np.float64)) + abs(eta * scale) * size
+    with np.errstate(invalid="ignore"):             # not-a-number weights are compared below
+        size = np.abs(omega.astype(np.float64)) + abs(eta * scale) * size
     fin = np.isfinite(omega) & np.isfinite(want64)   # the rest is compared bit for bit elsewhere
     assert np.all(np.abs(got[fin].astype(np.float64) - want64[fin].astype(np.float64))
                   <= 1e-6 * size[fin])
