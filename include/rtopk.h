@@ -64,7 +64,9 @@ int rtopk_aggregate_workspace_bytes(uint64_t d, uint32_t n, uint64_t k, uint64_t
  *
  * grad       device, [d] binary32, read only
  * residual   device, [d] binary32, in: m_t, out: m_{t+1}; must not overlap grad
- * d, r, k    1 <= k <= r <= d < 2^32
+ * d, r, k    1 <= k <= r <= d < 2^32. r == k is the top-k operator (no key is
+ *            ever computed), r == d the random-k operator (no magnitude is
+ *            ever compared: no estimate, no histogram, no threshold)
  * seed,step  select the random subset; a fresh `step` gives a fresh subset,
  *            distinct `seed`s give independent workers
  * out_idx    device, [k] uint32, the set U in strictly ascending order
@@ -195,7 +197,9 @@ typedef struct rtopk_encode_stats {
     uint32_t path;               /* 0: both cut points came from the short lists; bit 0: at least one
                                     came from the slow selection over all candidates; bit 1: the
                                     sampled estimate failed and the vector itself was walked */
-    uint32_t threshold_bits;     /* magnitude pattern of the r-th largest |a_i| */
+    uint32_t threshold_bits;     /* magnitude pattern of the r-th largest |a_i|. With r == d no
+                                    magnitude is looked at: threshold_bits and count_greater
+                                    are reported as 0 and ties_taken as r */
     uint32_t boundary_list_size; /* candidates that shared the deciding histogram bin */
     uint64_t count_greater;      /* #{i : mag(a_i) > threshold} */
     uint64_t ties_taken;         /* r - count_greater, taken from the lowest indices */

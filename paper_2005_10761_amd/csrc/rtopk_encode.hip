@@ -157,6 +157,7 @@ struct Geom {
     u32 nfine;          // linear histogram bins
     u32 force_dense;    // diagnostics: make the estimate keep nothing, as if the sample had misled it
     u32 take_all;       // k == r: every member is sent, keys are never looked at
+    u32 all_members;    // r == d: every coordinate is a member, magnitudes are never looked at
     u32 k_nlz;          // leading zeros of K_hi - K_lo
     u64 K_lo, K_hi;     // key window
 };
@@ -188,6 +189,7 @@ static Geom make_geom(u64 d, u64 r, u64 k)
     g.nfine = 256;
     while (g.nfine < kMaxFineBins && (u64)g.nfine * 256 < r) g.nfine *= 2;
     g.take_all = (k == r) ? 1u : 0u;
+    g.all_members = (r == d) ? 1u : 0u;
     // The number of members with key below x * 2^64 is Binomial(r, x). The
     // window keeps 7 standard deviations plus a constant (for small k, where
     // the normal approximation is poor) on both sides of k; a miss is still
@@ -533,17 +535,29 @@ __device__ __forceinline__ void append_hits(const u32 (&bits)[4], const bool (&h
 constexpr u32 kFusedThreads = 512;
 constexpr u32 kFusedWaves = kFusedThreads / kWave;
 
-template <bool kVec4>
+// kAll (r == d, the random-k operator): no magnitude decides anything. An
+// element is kept when its sampling key lies at or below the upper end of the
+// a-priori window (all of them when k == r as well); no histogram is made and
+// the control block, which no earlier kernel has touched, is cleared here.
+template <bool kVec4, bool kAll>
 __device__ __forceinline__ void
-fused_body(const float *__restrict__ grad, float *__restrict__ residual, Geom g,
-        const EncodeCtl *__restrict__ ctl, u32 *__restrict__ partials,
+fused_body(const float *__restrict__ grad, float *__restrict__ residual, Geom g, PhiloxSeed seed,
+        EncodeCtl *__restrict__ ctl, u32 *__restrict__ partials,
         u32 *__restrict__ seg_count, uint2 *__restrict__ s_ent)
 {
-    __shared__ u32 h[kMaxBins];
-    const Bins bins = ctl->bins;
-    const u32 nbins = bins.nfine + kCoarseBins;
-    for (u32 b = threadIdx.x; b < nbins; b += kFusedThreads) h[b] = 0u;
-    __syncthreads();
+    __shared__ u32 h[kAll ? 1 : kMaxBins];
+    Bins bins{};
+    u32 nbins = 0;
+    if (kAll) {
+        if (blockIdx.x == 0)
+            for (u32 i = threadIdx.x; i < sizeof(EncodeCtl) / 4; i += kFusedThreads)
+                reinterpret_cast<u32 *>(ctl)[i] = 0u;
+    } else {
+        bins = ctl->bins;
+        nbins = bins.nfine + kCoarseBins;
+        for (u32 b = threadIdx.x; b < nbins; b += kFusedThreads) h[b] = 0u;
+        __syncthreads();
+    }
 
     const u32 wave_stride = gridDim.x * kFusedWaves;
     for (u32 w = blockIdx.x * kFusedWaves + threadIdx.x / kWave; w < g.W; w += wave_stride) {
@@ -555,9 +569,15 @@ fused_body(const float *__restrict__ grad, float *__restrict__ residual, Geom g,
             bool hit[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const u32 m = mag_of(bits[e]);
-                hit[e] = valid[e] && m >= bins.t_lo;
-                if (hit[e]) atomicAdd(&h[bin_of(bins, m)], 1u);
+                if (kAll) {
+                    hit[e] = valid[e] &&
+                             (g.take_all != 0u ||
+                              sample_key((u32)elem_index<kVec4>(base, e), seed) <= g.K_hi);
+                } else {
+                    const u32 m = mag_of(bits[e]);
+                    hit[e] = valid[e] && m >= bins.t_lo;
+                    if (hit[e]) atomicAdd(&h[bin_of(bins, m)], 1u);
+                }
             }
             append_hits<kVec4>(bits, hit, base, run, my_ent);
         };
@@ -627,6 +647,7 @@ fused_body(const float *__restrict__ grad, float *__restrict__ residual, Geom g,
         }
         if (lane_id() == 0) seg_count[chunk_slot(w, g.U)] = run;
     }
+    if (kAll) return;
     __syncthreads();
     // The workgroup's histogram goes out as one dense row with plain stores:
     // device-wide atomics here, however few, slow the whole stream down.
@@ -857,7 +878,7 @@ classify_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ s
     walk.for_each(cand, [&](bool valid, u32 i, u32 idx, u32 bits, u32, u32) {
         if (!valid) return;
         const u32 m = mag_of(bits);
-        if (m > bd_hi) {
+        if (g.all_members != 0u || m > bd_hi) {
             bool sure = g.take_all != 0u;
             if (!sure) {
                 const u64 key = sample_key(idx, seed);
@@ -1019,7 +1040,7 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
     const u32 tid = threadIdx.x;
     const u32 wave = tid / kWave, lane = lane_id();
     const bool dense = ctl->dense != 0u;
-    const Candidates cand{seg_count, s_ent, a, g.d, g.C, g.U, dense};
+    Candidates cand{seg_count, s_ent, a, g.d, g.C, g.U, dense};
     // every candidate, split wavefront by chunk; f(index, pattern, chunk)
     auto each_s = [&](auto &&f) {
         for (u32 s = wave; s < g.W; s += kFinWaves) {
@@ -1052,7 +1073,13 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
     u32 T = 0, I_star = 0, J_star = 0xFFFFFFFFu, n_mm = 0;
     u64 K_star = ~0ull, count_greater = 0;
 
-    if (!dense && !overflow && c_def < g.r && need2 <= n_bd) {
+    if (g.all_members) {
+        // r == d: the "threshold" is the whole vector; only the key cut is found
+        have_t = true;
+        T = 0u;
+        I_star = 0xFFFFFFFFu;
+    }
+    if (!dense && !overflow && (g.all_members || (c_def < g.r && need2 <= n_bd))) {
         // ---- both short lists, each thread copying the entries of its own
         //      classify workgroup (a handful), all loads in one round --------
         const bool b_lds = n_bd <= kStageB;
@@ -1083,11 +1110,15 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
         auto each_b = [&](auto &&f) {
             for (u32 p = tid; p < n_bd; p += kFinThreads) f(bk[p], bi[p]);
         };
-        const Pair96 tb = block_select96(each_b, need2, (64 - (int)bd_bits) / 8, h, scratch, &ok);
+        Pair96 tb{0ull, 0u};
+        if (!g.all_members)
+            tb = block_select96(each_b, need2, (64 - (int)bd_bits) / 8, h, scratch, &ok);
         if (ok) {
             have_t = true;
-            T = bd_hi - (u32)tb.hi;
-            I_star = tb.lo;
+            if (!g.all_members) {
+                T = bd_hi - (u32)tb.hi;
+                I_star = tb.lo;
+            }
             // ---- members of the deciding bin join the key lists; the atomics
             //      on the chunk counters are left in flight --------------------
             u32 my_gt = 0;
@@ -1132,6 +1163,13 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
         }
     }
 
+    if (g.all_members && !have_k) {
+        // r == d and the key window missed (or a short list overflowed): the
+        // candidates are only the coordinates inside the window, so the exact
+        // selection below walks the vector itself, and so does the emit kernel
+        cand.dense = true;
+        if (tid == 0) ctl->dense = 1u;
+    }
     if (!have_t) {
         // ---- exact threshold by selection over all candidates -----------
         path = 1;
@@ -1349,12 +1387,12 @@ __global__ void __launch_bounds__(kEstThreads) k_estimate(Batch B, Geom g, Encod
     estimate_body(m.at<u32>(L.samples), g, m.at<EncodeCtl>(L.ctl));
 }
 
-template <bool kVec4>
+template <bool kVec4, bool kAll>
 __global__ void __launch_bounds__(kFusedThreads) k_fused(Batch B, Geom g, EncodeLayout L)
 {
     const Member m(B);
-    fused_body<kVec4>(m.grad, m.residual, g, m.at<EncodeCtl>(L.ctl), m.at<u32>(L.partials),
-                      m.at<u32>(L.seg_count), m.at<uint2>(L.s_ent));
+    fused_body<kVec4, kAll>(m.grad, m.residual, g, m.seed, m.at<EncodeCtl>(L.ctl),
+                            m.at<u32>(L.partials), m.at<u32>(L.seg_count), m.at<uint2>(L.s_ent));
 }
 
 __global__ void __launch_bounds__(kReduceThreads) k_reduce(Batch B, u32 n_rows, EncodeLayout L)
@@ -1462,9 +1500,9 @@ int fused_grid_limit(unsigned *out)
     if (g_fused_grid[dev] == 0) {
         int cus = 0, fit_t = 0, fit_f = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&fit_t, k_fused<true>,
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&fit_t, k_fused<true, false>,
                                                          (int)kFusedThreads, 0) != hipSuccess ||
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&fit_f, k_fused<false>,
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&fit_f, k_fused<false, true>,
                                                          (int)kFusedThreads, 0) != hipSuccess)
             return RTOPK_EHIP;
         int per_cu = fit_t < fit_f ? fit_t : fit_f;
@@ -1521,6 +1559,9 @@ extern "C" int rtopk_encode_batch(uint32_t n, const float *const *grad, float *c
         return RTOPK_EWORKSPACE;
     const unsigned force = g_force;
     g_force = 0;
+    // a forced estimate miss belongs to the general path; a forced window miss is
+    // honoured on the r == d path too (it then walks the vector itself)
+    if (force & RTOPK_FORCE_ESTIMATE_MISS) g.all_members = 0u;
     if (force & RTOPK_FORCE_ESTIMATE_MISS) g.force_dense = 1u;
     if ((force & RTOPK_FORCE_KEY_WINDOW_MISS) && !g.take_all) {
         g.K_lo = g.K_hi = 0;       // a window that holds no key: the exact selection must run
@@ -1552,20 +1593,30 @@ extern "C" int rtopk_encode_batch(uint32_t n, const float *const *grad, float *c
         B.step_hi = (u32)(step >> 32);
         B.ws = (char *)workspace + (u64)first * L.total;
         B.ws_stride = L.total;
-        {
-            StageScope sc(trace, RTOPK_STAGE_PREPARE, stream);
-            k_sample<<<dim3(kSampleLoc / kSampleThreads, 1, nb), kSampleThreads, 0, stream>>>(B, g, L);
+        const dim3 fg(fgrid, 1, nb);
+        if (g.all_members) {
+            // r == d (random-k): no estimate, no histogram, no threshold
+            StageScope sc(trace, RTOPK_STAGE_FUSED, stream);
+            if (vec4)
+                k_fused<true, true><<<fg, kFusedThreads, 0, stream>>>(B, g, L);
+            else
+                k_fused<false, true><<<fg, kFusedThreads, 0, stream>>>(B, g, L);
             RTOPK_LAUNCH_CHECK();
-            k_estimate<<<dim3(1, 1, nb), kEstThreads, 0, stream>>>(B, g, L);
-            RTOPK_LAUNCH_CHECK();
-        }
-        {
+        } else {
+            {
+                StageScope sc(trace, RTOPK_STAGE_PREPARE, stream);
+                k_sample<<<dim3(kSampleLoc / kSampleThreads, 1, nb), kSampleThreads, 0, stream>>>(
+                    B, g, L);
+                RTOPK_LAUNCH_CHECK();
+                k_estimate<<<dim3(1, 1, nb), kEstThreads, 0, stream>>>(B, g, L);
+                RTOPK_LAUNCH_CHECK();
+            }
             {
                 StageScope sc(trace, RTOPK_STAGE_FUSED, stream);
                 if (vec4)
-                    k_fused<true><<<dim3(fgrid, 1, nb), kFusedThreads, 0, stream>>>(B, g, L);
+                    k_fused<true, false><<<fg, kFusedThreads, 0, stream>>>(B, g, L);
                 else
-                    k_fused<false><<<dim3(fgrid, 1, nb), kFusedThreads, 0, stream>>>(B, g, L);
+                    k_fused<false, false><<<fg, kFusedThreads, 0, stream>>>(B, g, L);
                 RTOPK_LAUNCH_CHECK();
             }
             const dim3 rgrid((g.nfine + kCoarseBins + kReduceThreads - 1) / kReduceThreads,
@@ -1575,8 +1626,10 @@ extern "C" int rtopk_encode_batch(uint32_t n, const float *const *grad, float *c
         }
         {
             StageScope sc(trace, RTOPK_STAGE_CLASSIFY, stream);
-            k_pick<<<dim3(1, 1, nb), kPickThreads, 0, stream>>>(B, g, L);
-            RTOPK_LAUNCH_CHECK();
+            if (!g.all_members) {
+                k_pick<<<dim3(1, 1, nb), kPickThreads, 0, stream>>>(B, g, L);
+                RTOPK_LAUNCH_CHECK();
+            }
             k_classify<<<dim3(g.G3, 1, nb), kWalkThreads, 0, stream>>>(B, g, L);
             RTOPK_LAUNCH_CHECK();
         }

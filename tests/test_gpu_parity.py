@@ -601,3 +601,38 @@ def test_momentum_training_loop_on_the_device_matches_the_oracle():
         w_ref, v_ref = oracle.aggregate_update_momentum_f32(ai, av, n, d, 0.1, 1.0, 0.9, w_ref, v_ref)
         assert np.array_equal(u.bits(w_gpu), u.bits(w_ref))
         assert np.array_equal(u.bits(v_gpu), u.bits(v_ref))
+
+
+# --------------------------------------------------------------------------
+# r = d (the random-k operator): no magnitude decides anything
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("d,k,offset,force", [(300_003, 300, 0, 0), (300_003, 1, 0, 0),
+                                              (300_003, 30_000, 1, 0), (70_001, 70_001, 0, 0),
+                                              (5, 2, 0, 0), (1_048_576, 1049, 0, 0),
+                                              (120_000, 1200, 0, 2), (120_000, 1200, 3, 1),
+                                              (120_000, 1200, 0, 3)])
+def test_random_k_is_the_r_equals_d_case(d, k, offset, force):
+    u = _u()
+    rng = np.random.default_rng(d + k)
+    g1 = (rng.standard_normal(d) * 10.0 ** rng.uniform(-4, 0, d)).astype(np.float32)
+    g1[rng.random(d) < 0.3] = 0.0                       # magnitudes must not matter, zeros included
+    m0 = (rng.standard_normal(d) * 1e-3).astype(np.float32)
+    print(f"random-k d={d} k={k} offset={offset} force={force}", flush=True)
+    w = u.GpuWorker(d, d, k, residual=m0, offset=offset)
+    res = m0
+    for t in range(2):
+        g = g1 if t == 0 else (g1 * np.float32(0.5))
+        got = w.encode(g, 77, t, force=force if t == 0 else 0)
+        oi, ov, res = oracle.encode(g, res, d, k, 77, t)
+        u.assert_encode_equal(got, (oi, ov, res), f"random-k t={t}")
+        st = w.stats
+        if t == 0 and force & 2 and k < d:
+            assert st["path"] & 2, st                   # the window missed: the vector itself was walked
+        if not force or t == 1:
+            assert st["path"] == 0, st
+        # the k-subset is a uniform one: it does not follow the magnitudes
+    mags = np.abs(g1 + m0)
+    sent = np.zeros(d, bool)
+    sent[oi] = True
+    if 100 <= k <= d // 10:
+        assert abs(np.median(mags[sent]) - np.median(mags)) <= 0.5 * np.median(mags) + 1e-3
