@@ -41,6 +41,16 @@
 //   emit       entries of S that are members and winners -> the message in
 //              index order, starting at the chunk's prefix; residual at the
 //              sent positions <- a - a
+// Two special cases of Definition 3 take shortcuts: with k == r (top-k) no
+// sampling key is ever computed, and with r == d (random-k) no magnitude is
+// ever compared: the streaming kernel then keeps the elements whose key lies
+// at or below the upper end of the a-priori window, and sample, estimate,
+// reduce and pick are not launched at all.
+//
+// Every kernel serves up to 16 independent vectors of equal sizes per launch
+// (blockIdx.z is the member; rtopk_encode_batch), each with its own slice of
+// the workspace and computed exactly as if it were alone.
+//
 // If the sample misleads the estimate so far that S holds fewer than r
 // entries, the histogram shows it; pick then raises a flag and classify,
 // finalize and emit walk the vector a itself instead of S (slow, exact).
