@@ -115,7 +115,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=3, help="workload configuration (1-5)")
+    ap.add_argument("--config", type=int, default=3, help="workload configuration (1-5; 6 = the federated update vector)")
     ap.add_argument("--workers", type=int, default=0, help="override the workload's worker count")
     ap.add_argument("--sequential", action="store_true",
                     help="the timed steps call rtopk_encode once per worker instead of "

@@ -604,6 +604,33 @@ def test_momentum_training_loop_on_the_device_matches_the_oracle():
 
 
 # --------------------------------------------------------------------------
+# the federated setting's update vector: dense, smooth, r = 5% and k = 1% of d
+# --------------------------------------------------------------------------
+def test_federated_update_vector_five_nodes():
+    u = _u()
+    wl = Workload(6, d=400_009)
+    d, r, k, n = wl.d, wl.r, wl.k, wl.n_workers
+    assert n == 5 and abs(r - n * k) < n                      # k / r = 1 / n up to the ceilings
+    gw = [u.GpuWorker(d, r, k) for _ in range(n)]
+    res = [np.zeros(d, np.float32) for _ in range(n)]
+    omega = np.zeros(d, np.float32)
+    for t in range(3):
+        mi, mv = [], []
+        for w in range(n):
+            g = wl.gradient(w, t)
+            got = gw[w].encode(g, philox_seed_for_worker(w), t)
+            oi, ov, res[w] = oracle.encode(g, res[w], r, k, philox_seed_for_worker(w), t)
+            u.assert_encode_equal(got, (oi, ov, res[w]), f"federated w={w} t={t}")
+            assert gw[w].stats["path"] == 0
+            mi.append(oi)
+            mv.append(ov)
+        ai, av = np.stack(mi), np.stack(mv)
+        got_w = u.gpu_aggregate_update(ai, av, n, d, 1.0, 1.0, omega)
+        omega = oracle.aggregate_update_f32(ai, av, n, d, 1.0, 1.0, omega)
+        assert np.array_equal(u.bits(got_w), u.bits(omega))
+
+
+# --------------------------------------------------------------------------
 # r = d (the random-k operator): no magnitude decides anything
 # --------------------------------------------------------------------------
 @pytest.mark.parametrize("d,k,offset,force", [(300_003, 300, 0, 0), (300_003, 1, 0, 0),

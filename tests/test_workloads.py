@@ -18,7 +18,7 @@ def test_counts_follow_the_printed_configuration():
 
 
 def test_streams_are_seeded_and_distinct():
-    for cfg in (1, 2, 3, 4, 5):
+    for cfg in (1, 2, 3, 4, 5, 6):
         w = Workload(cfg, d=40_000)
         a = w.gradient(0, 0)
         assert a.dtype == np.float32 and a.shape == (40_000,)

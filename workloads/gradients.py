@@ -69,6 +69,14 @@ CONFIGS = {
               "10k x 1500 embedding with 5% nonzero rows N(0,1e-2); rest N(0,1e-3)"),
     5: Config(5, "cfg5-stress-student-t", 1 << 28, (1, 1000), (1, 10000), 16, 3,
               "Student-t(nu=3) times 1e-3; the sweep over k/d and r/k is applied by the caller"),
+    # Not one of the five benchmark configurations: the update vector of the
+    # federated setting (the change of the weights over one local epoch rather
+    # than one minibatch gradient; Section IV), which is dense and smooth, at the
+    # ResNet-18 size, with the sizes the experiments use for five nodes at 99%
+    # compression: k = 1% of d and k / r = 1 / 5.
+    6: Config(6, "cfg6-federated-delta-resnet18-sized", 11_173_962, (5, 100), (1, 100), 5, 5,
+              "62 segments, per-segment scale log-uniform [1e-4,1e-2] times N(0,1); no zeros, "
+              "no outliers"),
 }
 
 # k/d and r/k points of the stress sweep.
@@ -153,9 +161,9 @@ class Workload:
 
             _fill_chunks(scale, fn)
             self._scale = scale
-        elif cfg in (2, 3):
+        elif cfg in (2, 3, 6):
             rng = _rng(cfg, _TAG_STRUCT)
-            nseg, lo_e, hi_e = (62, -4.0, -1.0) if cfg == 2 else (161, -5.0, -2.0)
+            nseg, lo_e, hi_e = {2: (62, -4.0, -1.0), 3: (161, -5.0, -2.0), 6: (62, -4.0, -2.0)}[cfg]
             sizes = _segment_sizes(rng, d, nseg, 0.3)
             seg_scale = np.power(10.0, lo_e + (hi_e - lo_e) * rng.random(sizes.shape[0]))
             scale = np.repeat(seg_scale, sizes).astype(np.float64)
@@ -186,7 +194,7 @@ class Workload:
         """The float32 gradient of simulated worker ``worker`` at ``step``."""
         cfg, d = self.cfg, self.d
         out = np.empty(d, dtype=np.float32)
-        if cfg in (1, 2):
+        if cfg in (1, 2, 6):
             scale = self._scale
 
             def fn(c, lo, hi):
