@@ -23,8 +23,8 @@
 //              dominant kernel); entries with magnitude >= t_lo -> S, and
 //              into the workgroup's own histogram row: up to 2048 linear bins
 //              over the fine range, 256 exponent bins above it
-//   reduce     the workgroups' histogram rows -> 32 rows
-//   pick       one workgroup: sum of the 32 rows, and the bin that holds the
+//   reduce     the workgroups' histogram rows -> 16 rows
+//   pick       one workgroup: sum of the 16 rows, and the bin that holds the
 //              r-th largest magnitude (the deciding bin)
 //   classify   entries of S above the deciding bin are certain members of
 //              the top-r set: their Philox key is compared with an a-priori
