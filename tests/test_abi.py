@@ -64,3 +64,41 @@ def test_encode_rejects_bad_arguments_before_launching():
     # aggregate
     assert lib.rtopk_aggregate(None, fake, 2, 3, 10, fake, None, u64(0), None) == -1
     assert lib.rtopk_aggregate(fake, fake, 0, 3, 10, fake, None, u64(0), None) == -1
+
+
+def test_master_updates_and_batch_reject_bad_arguments_before_launching():
+    lib = rt.load_library()
+    u64 = ctypes.c_uint64
+    fake = ctypes.c_void_p(0x1000)          # never dereferenced: checks fail first
+    fake2 = ctypes.c_void_p(0x100000)
+    big = u64(1 << 30)
+    # fused weight step: null pointers, no workers, workspace missing / small / misaligned
+    assert lib.rtopk_aggregate_update(None, fake, 2, 3, 10, 0.1, 1.0, fake, fake, big, None) == -1
+    assert lib.rtopk_aggregate_update(fake, fake, 0, 3, 10, 0.1, 1.0, fake, fake, big, None) == -1
+    assert lib.rtopk_aggregate_update(fake, fake, 2, 3, 10, 0.1, 1.0, fake2, None, big, None) == -2
+    assert lib.rtopk_aggregate_update(fake, fake, 2, 3, 10, 0.1, 1.0, fake2, fake, u64(8), None) == -2
+    assert lib.rtopk_aggregate_update(fake, fake, 2, 3, 10, 0.1, 1.0, fake2,
+                                      ctypes.c_void_p(0x1010), big, None) == -2
+    assert rt.aggregate_update_workspace_bytes(10_000, 4, 10) == 256     # 4 workers x 6 rows x 4 B
+    with pytest.raises(rt.RtopkError):
+        rt.aggregate_update_workspace_bytes(10_000, 0, 10)
+    # with momentum: null pointers, weights and velocity in one buffer
+    assert lib.rtopk_aggregate_update_momentum(fake, fake, 2, 3, 10, 0.1, 1.0, 0.9, None, fake2,
+                                               None) == -1
+    assert lib.rtopk_aggregate_update_momentum(fake, fake, 2, 3, 10, 0.1, 1.0, 0.9, fake2, fake2,
+                                               None) == -1
+    # batched encode: no members, a null member pointer, overlap inside a member, workspace
+    # that holds one member instead of two
+    one = rt.encode_workspace_bytes(8, 4, 2)
+    vp2 = ctypes.c_void_p * 2
+    seeds = (u64 * 2)(1, 2)
+    ok_g, ok_m = vp2(0x1000, 0x3000), vp2(0x100000, 0x300000)
+    outs = vp2(0x5000, 0x7000)
+    assert lib.rtopk_encode_batch(0, ok_g, ok_m, 8, 4, 2, seeds, 0, outs, outs, fake, big, None) == -1
+    assert lib.rtopk_encode_batch(2, vp2(0x1000, None), ok_m, 8, 4, 2, seeds, 0, outs, outs, fake,
+                                  big, None) == -1
+    assert lib.rtopk_encode_batch(2, ok_g, vp2(0x100000, 0x3000), 8, 4, 2, seeds, 0, outs, outs,
+                                  fake, big, None) == -1
+    assert lib.rtopk_encode_batch(2, ok_g, ok_m, 8, 4, 2, seeds, 0, outs, outs, fake, u64(one),
+                                  None) == -2
+    assert lib.rtopk_encode_batch(2, ok_g, ok_m, 8, 5, 6, seeds, 0, outs, outs, fake, big, None) == -1
