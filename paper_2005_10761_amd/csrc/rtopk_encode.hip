@@ -701,17 +701,22 @@ struct Candidates {
 // wave-wide operations; (index, pattern) is the lane's entry, i the ordinal of
 // its chunk among the wavefront's chunks, first the flat position of the
 // chunk's first entry and p0 the flat position lane 0 holds.
-struct UnitWalk {
+// The same walk serves the slow exact paths of the finalize kernel, where a
+// wavefront takes kWave consecutive chunks at a time (kChunks = kWave,
+// stride 1).
+template <u32 kChunks>
+struct ChunkWalk {
     u32 u, stride, excl, inc, total;
 
-    __device__ __forceinline__ UnitWalk(const Candidates &cand, const Geom &g, u32 unit)
+    // chunks first, first + step, ..., at most kChunks of them and only those below n_chunks
+    __device__ __forceinline__ ChunkWalk(const Candidates &cand, u32 first, u32 step, u32 n_chunks)
     {
-        static_assert(kUnitChunks <= kWave, "one lane per chunk");
+        static_assert(kChunks <= kWave && (kChunks & (kChunks - 1)) == 0, "one lane per chunk");
         const u32 lane = lane_id();
-        u = unit;
-        stride = g.U;
-        const u32 s = unit + lane * g.U;
-        const u32 cnt = (unit < g.U && lane < kUnitChunks && s < g.W) ? cand.count(s) : 0u;
+        u = first;
+        stride = step;
+        const u64 s = (u64)first + (u64)lane * step;
+        const u32 cnt = (lane < kChunks && s < n_chunks) ? cand.count((u32)s) : 0u;
         inc = wave_inclusive_sum(cnt);
         excl = inc - cnt;
         total = __shfl(inc, kWave - 1, kWave);
@@ -723,11 +728,11 @@ struct UnitWalk {
         // number of chunks that end at or before position p = ordinal of p's chunk
         u32 c = 0;
 #pragma unroll
-        for (u32 step = kUnitChunks / 2; step > 0; step >>= 1) {
+        for (u32 step = kChunks / 2; step > 0; step >>= 1) {
             const u32 end_of = __shfl(inc, c + step - 1, kWave);
             if (end_of <= p) c += step;
         }
-        c &= kUnitChunks - 1;
+        c &= kChunks - 1;
         *ordinal = c;
         *first = __shfl(excl, c, kWave);
     }
@@ -760,6 +765,8 @@ struct UnitWalk {
         }
     }
 };
+
+using UnitWalk = ChunkWalk<kUnitChunks>;     // classify / emit: chunks u, u + U, u + 2U, ...
 
 // ---------------------------------------------------------------------------
 // reduce: the rows the streaming workgroups stored -> kHistRows rows.
@@ -877,7 +884,7 @@ classify_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ s
         return;
     }
     const Candidates cand{seg_count, s_ent, nullptr, g.d, g.C, g.U, false};
-    const UnitWalk walk(cand, g, u);
+    const UnitWalk walk(cand, u < g.U ? u : g.W, g.U, g.W);
     if (threadIdx.x == 0) { cnt_m = 0u; cnt_b = 0u; cnt_sure = 0u; }
     if (lane < kUnitChunks) per_chunk[wave][lane] = 0u;
     __syncthreads();
@@ -1053,13 +1060,13 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
     Candidates cand{seg_count, s_ent, a, g.d, g.C, g.U, dense};
     // every candidate, split wavefront by chunk; f(index, pattern, chunk)
     auto each_s = [&](auto &&f) {
-        for (u32 s = wave; s < g.W; s += kFinWaves) {
-            const u32 n = cand.count(s);
-            for (u32 j = lane; j < n; j += kWave) {
-                u32 idx, bits;
-                cand.entry(s, j, &idx, &bits);
-                f(idx, bits, s);
-            }
+        // kWave consecutive chunks per wavefront at a time: their sizes in one round of
+        // loads, then their entries as one flat sequence, four iterations fetched together
+        for (u32 first = wave * kWave; first < g.W; first += kFinWaves * kWave) {
+            const ChunkWalk<kWave> walk(cand, first, 1u, g.W);
+            walk.for_each(cand, [&](bool valid, u32 i, u32 idx, u32 bits, u32, u32) {
+                if (valid) f(idx, bits, first + i);
+            });
         }
     };
 
@@ -1308,7 +1315,7 @@ emit_body(Geom g, PhiloxSeed seed, const EncodeCtl *__restrict__ ctl,
     if (u >= g.U) return;
     const u32 lane = lane_id();
     const Candidates cand{seg_count, s_ent, residual, g.d, g.C, g.U, ctl->dense != 0u};
-    const UnitWalk walk(cand, g, u);
+    const UnitWalk walk(cand, u < g.U ? u : g.W, g.U, g.W);
     const u32 my_chunk = u + lane * g.U;
     const u32 my_base = (lane < kUnitChunks && my_chunk < g.W) ? chunk_base[my_chunk] : 0u;
     const u32 T = ctl->T, I_star = ctl->I_star;
