@@ -140,11 +140,12 @@ struct EncodeCtl {
     // written by k_estimate
     Bins bins;
     u32 n_samples;
-    // written by workgroup 0 of k_classify
+    // written by k_pick (dense also by k_finalize when r == d and the key window missed)
     u32 dense;          // S holds fewer than r entries: walk the vector itself
     u32 bd_lo, bd_hi;   // pattern range of the deciding bin
     u32 bd_bits;        // bit width of bd_hi - bd_lo
     u64 c_def;          // entries above bd_hi
+    // written by k_classify
     u32 overflow;       // a short-list region of some classify workgroup was full
     u32 pad0;
     // written by k_finalize
