@@ -663,3 +663,70 @@ def test_random_k_is_the_r_equals_d_case(d, k, offset, force):
     sent[oi] = True
     if 100 <= k <= d // 10:
         assert abs(np.median(mags[sent]) - np.median(mags)) <= 0.5 * np.median(mags) + 1e-3
+
+
+# --------------------------------------------------------------------------
+# seeded random sweep over sizes and value patterns, all entry points
+# --------------------------------------------------------------------------
+def test_seeded_random_sweep_of_sizes_and_value_patterns():
+    import torch
+    u = _u()
+    rt = u.rt
+    dev = u.DEV
+    rng = np.random.default_rng(20240607)
+    for case in range(120):
+        d = int(rng.choice([1, 2, 3, 7, 64, 65, 255, 256, 257, 1000, 1023, 1025, 4095, 4097, 9000]))
+        r = int(rng.integers(1, d + 1))
+        k = int(rng.integers(1, r + 1))
+        if case % 7 == 0:
+            r = d
+        if case % 11 == 0:
+            k = r
+        n = int(rng.integers(1, 5))
+        pattern = case % 5
+        gs, ms = [], []
+        for i in range(n):
+            if pattern == 0:
+                g = rng.standard_normal(d)
+            elif pattern == 1:                      # few distinct magnitudes: ties everywhere
+                g = rng.choice([-2.0, -1.0, 0.0, 1.0, 2.0], d)
+            elif pattern == 2:                      # mostly zero
+                g = rng.standard_normal(d) * (rng.random(d) < 0.1)
+            elif pattern == 3:                      # wide dynamic range with denormals
+                g = rng.standard_normal(d) * 10.0 ** rng.uniform(-44, 3, d)
+            else:                                   # one value
+                g = np.full(d, 0.75)
+            gs.append(g.astype(np.float32))
+            ms.append((rng.standard_normal(d) * (0.0 if pattern in (1, 4) else 1e-3)).astype(np.float32))
+        seeds = [int(rng.integers(0, 2 ** 63)) for _ in range(n)]
+        step = int(rng.integers(0, 2 ** 40))
+        stride = rt.encode_workspace_bytes(d, r, k)
+        ws = torch.empty(n * stride, dtype=torch.uint8, device=dev)
+        grads = [torch.from_numpy(g).to(dev) for g in gs]
+        resid = [torch.from_numpy(m).to(dev) for m in ms]
+        idx = torch.full((n * k,), -1, dtype=torch.int32, device=dev)
+        val = torch.full((n * k,), float("nan"), dtype=torch.float32, device=dev)
+        out_i = [idx[i * k:(i + 1) * k] for i in range(n)]
+        out_v = [val[i * k:(i + 1) * k] for i in range(n)]
+        what = f"case {case}: d={d} r={r} k={k} n={n} pattern={pattern}"
+        print(what, flush=True)
+        rt.encode_batch(grads, resid, r, k, seeds, step, out_i, out_v, ws)
+        torch.cuda.synchronize()
+        for i in range(n):
+            st = rt.encode_stats(ws[i * stride:(i + 1) * stride])
+            assert st["error_flags"] == 0, (what, i, st)
+            want = oracle.encode(gs[i], ms[i], r, k, seeds[i], step)
+            got = (out_i[i].cpu().numpy().view(np.uint32), out_v[i].cpu().numpy(),
+                   resid[i].cpu().numpy())
+            u.assert_encode_equal(got, want, f"{what} member {i}")
+        ai = idx.cpu().numpy().view(np.uint32)
+        av = val.cpu().numpy()
+        out = u.gpu_aggregate(ai, av, n, d)
+        assert np.array_equal(u.bits(out), u.bits(oracle.aggregate_f32(ai, av, n, d))), what
+        omega = rng.standard_normal(d).astype(np.float32)
+        vel = rng.standard_normal(d).astype(np.float32)
+        gw = u.gpu_aggregate_update(ai, av, n, d, 0.125, 2.0, omega)
+        assert np.array_equal(u.bits(gw), u.bits(oracle.aggregate_update_f32(ai, av, n, d, 0.125, 2.0, omega))), what
+        gw, gv = u.gpu_aggregate_update_momentum(ai, av, n, d, 0.125, 2.0, 0.5, omega, vel)
+        ww, wv = oracle.aggregate_update_momentum_f32(ai, av, n, d, 0.125, 2.0, 0.5, omega, vel)
+        assert np.array_equal(u.bits(gw), u.bits(ww)) and np.array_equal(u.bits(gv), u.bits(wv)), what
