@@ -23,7 +23,12 @@
  *     a static description. Argument checks are made on the host before
  *     anything is launched; a failed check launches nothing.
  *   - Results are a pure function of the argument values and buffer contents:
- *     they do not depend on grid size, stream or run.
+ *     they do not depend on grid size, stream or run. Against another
+ *     implementation of the same arithmetic they agree bit for bit, with one
+ *     exception IEEE 754 leaves open: when an addition meets two not-a-number
+ *     operands with different payloads (two workers sending NaN for one
+ *     coordinate; a NaN gradient entry on a NaN residual entry), the result is
+ *     a NaN whose payload is the hardware's choice.
  */
 #ifndef RTOPK_H
 #define RTOPK_H
