@@ -81,6 +81,28 @@ __device__ __forceinline__ u32 wave_sum(u32 v)
     return (u32)__builtin_amdgcn_readlane((int)wave_inclusive_sum(v), kWave - 1);
 }
 
+// smallest / largest value over the wavefront, in every lane (rare paths only:
+// six exchanges through the LDS crossbar)
+__device__ __forceinline__ u32 wave_min(u32 v)
+{
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) {
+        const u32 w = (u32)__shfl_xor((int)v, o, kWave);
+        v = w < v ? w : v;
+    }
+    return v;
+}
+
+__device__ __forceinline__ u32 wave_max(u32 v)
+{
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) {
+        const u32 w = (u32)__shfl_xor((int)v, o, kWave);
+        v = w > v ? w : v;
+    }
+    return v;
+}
+
 __host__ __device__ constexpr u64 align_up(u64 x, u64 a) { return (x + a - 1) / a * a; }
 
 }  // namespace rtopk

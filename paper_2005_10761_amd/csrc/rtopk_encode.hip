@@ -136,7 +136,8 @@ __device__ __forceinline__ void bin_range(const Bins &b, u32 bin, u32 *lo, u32 *
 
 struct EncodeCtl {
     u32 err;
-    u32 path;           // 0: short lists; 1: some quantity came from selection over all candidates
+    u32 path;           // 0: short lists; bit 0: some quantity came from selection over all
+                        // candidates; bit 2: the threshold lies in a long run of equal magnitudes
     // written by k_estimate
     Bins bins;
     u32 n_samples;
@@ -147,7 +148,7 @@ struct EncodeCtl {
     u64 c_def;          // entries above bd_hi
     // written by k_classify
     u32 overflow;       // a short-list region of some classify workgroup was full
-    u32 pad0;
+    u32 overflow_m;     // ... and it was a region of the key list M
     // written by k_finalize
     u32 T, I_star;      // last member of the top-r set in (magnitude desc, index asc) order
     u64 K_star;         // last winner in (key asc, index asc) order
@@ -175,7 +176,7 @@ struct Geom {
 
 struct EncodeLayout {
     u64 ctl, zero_bytes, partials, hist;
-    u64 samples, seg_count, win_cnt, chunk_base, blk_sure, n_m, n_b;
+    u64 samples, seg_count, win_cnt, bd_cnt, chunk_base, blk_sure, n_m, n_b, blk_bmin, blk_bmax;
     u64 m_key, m_idx, b_mag, b_idx;
     u64 dm_key, dm_idx, db_key, db_idx;
     u64 s_ent;
@@ -229,10 +230,13 @@ static EncodeLayout make_layout(const Geom &g)
     L.samples = take((u64)kSampleLoc * 16);
     L.seg_count = take((u64)kTargetChunks * 4);      // fixed size: its offset depends on nothing
     L.win_cnt = take((u64)kTargetChunks * 4);
+    L.bd_cnt = take((u64)kTargetChunks * 4);
     L.chunk_base = take((u64)kTargetChunks * 4);
     L.blk_sure = take((u64)g.G3 * 4);
     L.n_m = take((u64)g.G3 * 4);
     L.n_b = take((u64)g.G3 * 4);
+    L.blk_bmin = take((u64)g.G3 * 4);
+    L.blk_bmax = take((u64)g.G3 * 4);
     const u64 slots = (u64)g.G3 * kListCap;
     L.m_key = take(slots * 8);
     L.m_idx = take(slots * 4);
@@ -865,30 +869,41 @@ pick_body(const u32 *__restrict__ hist, Geom g, EncodeCtl *ctl)
 
 // ---------------------------------------------------------------------------
 // classify: walk S; certain members are keyed against the window, entries
-// of the deciding bin go to the short list B.
+// of the deciding bin go to the short list B. Of the deciding bin it also
+// leaves the number of entries per chunk and the smallest and largest
+// magnitude per workgroup: when the bin turns out to be one long run of equal
+// magnitudes (a vector of zeros, of signs, of a few quantisation levels), the
+// short list cannot hold it, but the last member is then simply the entry of
+// a known rank in index order, which those counts locate.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ void
 classify_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ seg_count,
            const uint2 *__restrict__ s_ent,
-           u32 *__restrict__ win_cnt, u32 *__restrict__ blk_sure, u32 *__restrict__ n_m,
-           u32 *__restrict__ n_b, u64 *__restrict__ m_key, u32 *__restrict__ m_idx,
+           u32 *__restrict__ win_cnt, u32 *__restrict__ bd_cnt, u32 *__restrict__ blk_sure,
+           u32 *__restrict__ n_m, u32 *__restrict__ n_b, u32 *__restrict__ blk_bmin,
+           u32 *__restrict__ blk_bmax, u64 *__restrict__ m_key, u32 *__restrict__ m_idx,
            u32 *__restrict__ b_mag, u32 *__restrict__ b_idx)
 {
-    __shared__ u32 cnt_m, cnt_b, cnt_sure;
+    __shared__ u32 cnt_m, cnt_b, cnt_sure, bmin_s, bmax_s;
     __shared__ u32 per_chunk[kWalkWaves][kUnitChunks];
+    __shared__ u32 per_chunk_b[kWalkWaves][kUnitChunks];
     const u32 wave = threadIdx.x / kWave, lane = lane_id();
     const u32 u = blockIdx.x * kWalkWaves + wave;
     const bool dense = ctl->dense != 0u;
     const u32 bd_lo = ctl->bd_lo, bd_hi = ctl->bd_hi;
     if (dense) {
-        if (threadIdx.x == 0) { blk_sure[blockIdx.x] = 0u; n_m[blockIdx.x] = 0u; n_b[blockIdx.x] = 0u; }
+        if (threadIdx.x == 0) {
+            blk_sure[blockIdx.x] = 0u; n_m[blockIdx.x] = 0u; n_b[blockIdx.x] = 0u;
+            blk_bmin[blockIdx.x] = 0xFFFFFFFFu; blk_bmax[blockIdx.x] = 0u;
+        }
         return;
     }
     const Candidates cand{seg_count, s_ent, nullptr, g.d, g.C, g.U, false};
     const UnitWalk walk(cand, u < g.U ? u : g.W, g.U, g.W);
-    if (threadIdx.x == 0) { cnt_m = 0u; cnt_b = 0u; cnt_sure = 0u; }
-    if (lane < kUnitChunks) per_chunk[wave][lane] = 0u;
+    if (threadIdx.x == 0) { cnt_m = 0u; cnt_b = 0u; cnt_sure = 0u; bmin_s = 0xFFFFFFFFu; bmax_s = 0u; }
+    if (lane < kUnitChunks) { per_chunk[wave][lane] = 0u; per_chunk_b[wave][lane] = 0u; }
     __syncthreads();
+    u32 lane_bmin = 0xFFFFFFFFu, lane_bmax = 0u;      // what this lane has already reported
 
     // entry p of this workgroup's short lists lives at [p][workgroup]: the
     // finalize kernel reads entry p of all workgroups with one coalesced load
@@ -911,16 +926,20 @@ classify_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ s
         } else if (m >= bd_lo) {
             const u32 p = atomicAdd(&cnt_b, 1u);
             if (p < kListCap) { b_mag[slot(p)] = m; b_idx[slot(p)] = idx; }
+            atomicAdd(&per_chunk_b[wave][i], 1u);
+            if (m < lane_bmin) { lane_bmin = m; atomicMin(&bmin_s, m); }
+            if (m > lane_bmax) { lane_bmax = m; atomicMax(&bmax_s, m); }
         }
     });
     __builtin_amdgcn_wave_barrier();
-    // certain winners of each of the wavefront's chunks
+    // certain winners, and entries of the deciding bin, of each of the wavefront's chunks
     u32 mine = 0;
     if (u < g.U && lane < kUnitChunks) {
         const u32 s = u + lane * g.U;
         if (s < g.W) {
             mine = per_chunk[wave][lane];
             win_cnt[s] = mine;
+            bd_cnt[s] = per_chunk_b[wave][lane];
         }
     }
     mine = wave_sum(mine);
@@ -930,7 +949,10 @@ classify_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ s
         blk_sure[blockIdx.x] = cnt_sure;
         n_m[blockIdx.x] = cnt_m < kListCap ? cnt_m : kListCap;
         n_b[blockIdx.x] = cnt_b < kListCap ? cnt_b : kListCap;
+        blk_bmin[blockIdx.x] = bmin_s;
+        blk_bmax[blockIdx.x] = bmax_s;
         if (cnt_m > kListCap || cnt_b > kListCap) ctl->overflow = 1u;
+        if (cnt_m > kListCap) ctl->overflow_m = 1u;
     }
 }
 
@@ -1038,8 +1060,9 @@ __device__ __forceinline__ bool pair_le(u64 hi, u32 lo, const Pair96 &p)
 __device__ __forceinline__ void
 finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__ a,
            const u32 *__restrict__ seg_count, const uint2 *__restrict__ s_ent,
-           u32 *win_cnt, const u32 *__restrict__ blk_sure,
+           u32 *win_cnt, const u32 *__restrict__ bd_cnt, const u32 *__restrict__ blk_sure,
            const u32 *__restrict__ n_m, const u32 *__restrict__ n_b,
+           const u32 *__restrict__ blk_bmin, const u32 *__restrict__ blk_bmax,
            const u64 *__restrict__ m_key, const u32 *__restrict__ m_idx,
            const u32 *__restrict__ b_mag, const u32 *__restrict__ b_idx, u64 *dm_key,
            u32 *dm_idx, u64 *db_key, u32 *db_idx, u32 *__restrict__ chunk_base)
@@ -1054,6 +1077,7 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
     __shared__ u32 st_m_idx[kStageM];
     __shared__ u32 extra_m, sure_extra;
     __shared__ unsigned long long gt_extra;
+    __shared__ u32 run_chunk, run_before, run_index, run_found;
 
     const u32 tid = threadIdx.x;
     const u32 wave = tid / kWave, lane = lane_id();
@@ -1075,10 +1099,11 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
     const bool in_grid = tid < g.G3;
     const u32 vm = in_grid ? n_m[tid] : 0u, vb = in_grid ? n_b[tid] : 0u;
     const u32 vs = in_grid ? blk_sure[tid] : 0u;
-    const u32 bd_hi = ctl->bd_hi, bd_bits = ctl->bd_bits;
+    const u32 vmin = in_grid ? blk_bmin[tid] : 0xFFFFFFFFu, vmax = in_grid ? blk_bmax[tid] : 0u;
+    const u32 bd_lo = ctl->bd_lo, bd_hi = ctl->bd_hi, bd_bits = ctl->bd_bits;
     const u64 c_def = ctl->c_def;
-    const bool overflow = ctl->overflow != 0u;
-    if (tid == 0) { extra_m = 0u; sure_extra = 0u; gt_extra = 0ull; }
+    const bool overflow = ctl->overflow != 0u, overflow_m = ctl->overflow_m != 0u;
+    if (tid == 0) { extra_m = 0u; sure_extra = 0u; gt_extra = 0ull; run_found = 0u; }
     const u32 em = block_exclusive_sum(vm, scan32);
     const u32 n_m0 = scan32[kFinWaves];
     const u32 eb = block_exclusive_sum(vb, scan32);
@@ -1097,23 +1122,40 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
         T = 0u;
         I_star = 0xFFFFFFFFu;
     }
-    if (!dense && !overflow && (g.all_members || (c_def < g.r && need2 <= n_bd))) {
+    const bool lists = !dense && !overflow && (g.all_members || (c_def < g.r && need2 <= n_bd));
+    // The list B overflowed but M did not, and every entry of the deciding bin has
+    // the same magnitude: the last member is the need2-th of them in index order.
+    bool tie_run = false;
+    if (!dense && overflow && !overflow_m && !g.all_members && c_def < g.r) {
+        const u32 lo = wave_min(vmin), hi = wave_max(vmax);
+        if (lane == 0) { scan32[wave] = lo; scan32[kFinWaves + wave] = hi; }
+        lds_barrier();
+        const u32 all_lo = wave_min(lane < kFinWaves ? scan32[lane] : 0xFFFFFFFFu);
+        const u32 all_hi = wave_max(lane < kFinWaves ? scan32[kFinWaves + lane] : 0u);
+        lds_barrier();
+        tie_run = all_lo == all_hi;
+        if (tie_run) T = all_lo;
+    }
+    if (lists || tie_run) {
         // ---- both short lists, each thread copying the entries of its own
         //      classify workgroup (a handful), all loads in one round --------
-        const bool b_lds = n_bd <= kStageB;
+        const u32 n_b_use = lists ? n_bd : 0u;
+        const bool b_lds = n_b_use <= kStageB;
         u64 *bk = b_lds ? st_b_key : db_key;
         u32 *bi = b_lds ? st_b_idx : db_idx;
-        const bool m_lds = n_m0 + n_bd <= kStageM;
+        // (a run of equal magnitudes may add any number of keys: the large array then)
+        const bool m_lds = lists && n_m0 + n_b_use <= kStageM;
         u64 *mk = m_lds ? st_m_key : dm_key;
         u32 *mi = m_lds ? st_m_idx : dm_idx;
+        const u32 m_cap = m_lds ? kStageM : 2u * g.G3 * kListCap;
         // Entry j of classify workgroup t lives at [j][t]. First every thread
         // notes where the entries of its workgroup are (no memory latency in
         // that loop), then the entries are fetched position by position, all
         // loads of a thread in flight together.
-        for (u32 j = 0; j < vb; ++j) bi[eb + j] = j * g.G3 + tid;
+        if (lists) for (u32 j = 0; j < vb; ++j) bi[eb + j] = j * g.G3 + tid;
         for (u32 j = 0; j < vm; ++j) mi[em + j] = j * g.G3 + tid;
         if (b_lds && m_lds) lds_barrier(); else __syncthreads();
-        for (u32 p = tid; p < n_bd; p += kFinThreads) {
+        for (u32 p = tid; p < n_b_use; p += kFinThreads) {
             const u32 at = bi[p];
             bk[p] = (u64)(bd_hi - b_mag[at]);
             bi[p] = b_idx[at];
@@ -1124,27 +1166,80 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
             mi[p] = m_idx[at];
         }
         if (b_lds && m_lds) lds_barrier(); else __syncthreads();
-        // ---- exact threshold inside the deciding bin --------------------
-        auto each_b = [&](auto &&f) {
-            for (u32 p = tid; p < n_bd; p += kFinThreads) f(bk[p], bi[p]);
-        };
         Pair96 tb{0ull, 0u};
-        if (!g.all_members)
+        if (tie_run) {
+            // ---- the chunk that holds the need2-th entry of the run: thread t
+            //      adds up the counts of chunks 32t .. 32t+31 ---------------------
+            path = 4;
+            constexpr u32 kPer = kTargetChunks / kFinThreads;
+            static_assert(kPer % 4 == 0, "whole 16-byte groups of counters per thread");
+            u32 mine = 0;
+#pragma unroll
+            for (u32 q = 0; q < kPer / 4; ++q) {
+                const u32 s = tid * kPer + 4u * q;
+                uint4 v = make_uint4(0u, 0u, 0u, 0u);
+                if (s < g.W) v = reinterpret_cast<const uint4 *>(bd_cnt)[s / 4];
+                mine += v.x + (s + 1 < g.W ? v.y : 0u) + (s + 2 < g.W ? v.z : 0u) +
+                        (s + 3 < g.W ? v.w : 0u);
+            }
+            // (the entries of the bin number at most d < 2^32)
+            const u32 before = block_exclusive_sum(mine, scan32);
+            if ((u64)before < need2 && need2 <= (u64)before + mine) {
+                // one thread: its counters again, one by one
+                u32 run = before;
+                for (u32 s = tid * kPer; s < g.W; ++s) {
+                    const u32 c = bd_cnt[s];
+                    if ((u64)run + c >= need2) {
+                        run_chunk = s;
+                        run_before = run;
+                        run_found = 1u;
+                        break;
+                    }
+                    run += c;
+                }
+            }
+            lds_barrier();
+            ok = run_found != 0u;
+            if (ok) {
+                // ---- the entry of that rank inside the chunk, 1024 entries a round
+                const u32 sc = run_chunk;
+                const u32 want = (u32)(need2 - run_before);      // 1-based, among the chunk's
+                const u32 n_e = cand.count(sc);
+                lds_barrier();
+                if (tid == 0) run_found = 0u;
+                u32 seen = 0;
+                for (u32 j0 = 0; j0 < n_e && seen < want; j0 += kFinThreads) {
+                    const u32 j = j0 + tid;
+                    u32 idx = 0, bits = 0;
+                    if (j < n_e) cand.entry(sc, j, &idx, &bits);
+                    const u32 m = mag_of(bits);
+                    const u32 flag = (j < n_e && m >= bd_lo && m <= bd_hi) ? 1u : 0u;
+                    const u32 excl = block_exclusive_sum(flag, scan32);
+                    const u32 round_total = scan32[kFinWaves];
+                    if (flag && seen + excl + 1u == want) { run_index = idx; run_found = 1u; }
+                    seen += round_total;
+                    lds_barrier();
+                }
+                ok = run_found != 0u;
+                I_star = run_index;
+            }
+            if (!ok) { T = 0; path = 0; }
+        } else if (!g.all_members) {
+            // ---- exact threshold inside the deciding bin --------------------
+            auto each_b = [&](auto &&f) {
+                for (u32 p = tid; p < n_bd; p += kFinThreads) f(bk[p], bi[p]);
+            };
             tb = block_select96(each_b, need2, (64 - (int)bd_bits) / 8, h, scratch, &ok);
+        }
         if (ok) {
             have_t = true;
-            if (!g.all_members) {
+            if (lists && !g.all_members) {
                 T = bd_hi - (u32)tb.hi;
                 I_star = tb.lo;
             }
             // ---- members of the deciding bin join the key lists; the atomics
             //      on the chunk counters are left in flight --------------------
-            u32 my_gt = 0;
-            for (u32 p = tid; p < n_bd; p += kFinThreads) {
-                const u64 hi = bk[p];
-                const u32 idx = bi[p];
-                if (hi < tb.hi) ++my_gt;
-                if (!pair_le(hi, idx, tb)) continue;
+            auto join = [&](u32 idx) {
                 bool sure = g.take_all != 0u;
                 if (!sure) {
                     const u64 key = sample_key(idx, seed);
@@ -1152,11 +1247,32 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
                         sure = true;
                     } else if (key <= g.K_hi) {
                         const u32 q = atomicAdd(&extra_m, 1u);
-                        mk[n_m0 + q] = (key - g.K_lo) << g.k_nlz;
-                        mi[n_m0 + q] = idx;
+                        if (n_m0 + q < m_cap) {
+                            mk[n_m0 + q] = (key - g.K_lo) << g.k_nlz;
+                            mi[n_m0 + q] = idx;
+                        }
                     }
                 }
                 if (sure) { atomicAdd(&win_cnt[idx / g.C], 1u); atomicAdd(&sure_extra, 1u); }
+            };
+            u32 my_gt = 0;
+            if (lists) {
+                for (u32 p = tid; p < n_bd; p += kFinThreads) {
+                    const u64 hi = bk[p];
+                    const u32 idx = bi[p];
+                    if (hi < tb.hi) ++my_gt;
+                    if (pair_le(hi, idx, tb)) join(idx);
+                }
+            } else {
+                // the run's members: its entries up to index I*, all in chunks 0 .. run_chunk
+                const u32 s_end = run_chunk + 1u;
+                for (u32 first = wave * kUnitChunks; first < s_end; first += kFinWaves * kUnitChunks) {
+                    const UnitWalk walk(cand, first, 1u, s_end);
+                    walk.for_each(cand, [&](bool valid, u32, u32 idx, u32 bits, u32, u32) {
+                        const u32 m = mag_of(bits);
+                        if (valid && m >= bd_lo && m <= bd_hi && idx <= I_star) join(idx);
+                    });
+                }
             }
             if (my_gt) atomicAdd(&gt_extra, (unsigned long long)my_gt);
             if (m_lds) lds_barrier(); else __syncthreads();
@@ -1165,7 +1281,7 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
             const u64 c_klo = sure_walk + sure_extra;
             if (g.take_all) {
                 have_k = true;
-            } else if (c_klo < g.k && g.k - c_klo <= n_mm) {
+            } else if (n_mm <= m_cap && c_klo < g.k && g.k - c_klo <= n_mm) {
                 auto each_m = [&](auto &&f) {
                     for (u32 p = tid; p < n_mm; p += kFinThreads) f(mk[p], mi[p]);
                 };
@@ -1190,7 +1306,7 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
     }
     if (!have_t) {
         // ---- exact threshold by selection over all candidates -----------
-        path = 1;
+        path |= 1u;
         auto each_mag = [&](auto &&f) {
             each_s([&](u32 idx, u32 bits, u32) { f((u64)(0x7FFFFFFFu - mag_of(bits)), idx); });
         };
@@ -1208,7 +1324,7 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
     };
     if (!have_k) {
         // ---- exact key cut and winners per chunk by selection over all candidates
-        path = 1;
+        path |= 1u;
         __syncthreads();
         for (u32 s = tid; s < g.W; s += kFinThreads) win_cnt[s] = 0u;
         if (!g.take_all) {
@@ -1429,8 +1545,9 @@ __global__ void __launch_bounds__(kWalkThreads) k_classify(Batch B, Geom g, Enco
 {
     const Member m(B);
     classify_body(g, m.seed, m.at<EncodeCtl>(L.ctl), m.at<u32>(L.seg_count),
-                  m.at<uint2>(L.s_ent), m.at<u32>(L.win_cnt), m.at<u32>(L.blk_sure),
-                  m.at<u32>(L.n_m), m.at<u32>(L.n_b), m.at<u64>(L.m_key), m.at<u32>(L.m_idx),
+                  m.at<uint2>(L.s_ent), m.at<u32>(L.win_cnt), m.at<u32>(L.bd_cnt),
+                  m.at<u32>(L.blk_sure), m.at<u32>(L.n_m), m.at<u32>(L.n_b), m.at<u32>(L.blk_bmin),
+                  m.at<u32>(L.blk_bmax), m.at<u64>(L.m_key), m.at<u32>(L.m_idx),
                   m.at<u32>(L.b_mag), m.at<u32>(L.b_idx));
 }
 
@@ -1438,8 +1555,9 @@ __global__ void __launch_bounds__(kFinThreads) k_finalize(Batch B, Geom g, Encod
 {
     const Member m(B);
     finalize_body(g, m.seed, m.at<EncodeCtl>(L.ctl), m.residual, m.at<u32>(L.seg_count),
-                  m.at<uint2>(L.s_ent), m.at<u32>(L.win_cnt),
-                  m.at<u32>(L.blk_sure), m.at<u32>(L.n_m), m.at<u32>(L.n_b), m.at<u64>(L.m_key),
+                  m.at<uint2>(L.s_ent), m.at<u32>(L.win_cnt), m.at<u32>(L.bd_cnt),
+                  m.at<u32>(L.blk_sure), m.at<u32>(L.n_m), m.at<u32>(L.n_b),
+                  m.at<u32>(L.blk_bmin), m.at<u32>(L.blk_bmax), m.at<u64>(L.m_key),
                   m.at<u32>(L.m_idx), m.at<u32>(L.b_mag), m.at<u32>(L.b_idx), m.at<u64>(L.dm_key),
                   m.at<u32>(L.dm_idx), m.at<u64>(L.db_key), m.at<u32>(L.db_idx),
                   m.at<u32>(L.chunk_base));

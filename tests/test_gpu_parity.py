@@ -85,15 +85,57 @@ def test_ties_straddling_the_threshold_take_lowest_indices():
     _check(g, m, 1100, 300, 1, 1)
 
 
-def test_huge_tie_bucket_uses_the_full_vector_path():
+def test_long_run_of_equal_magnitudes_at_the_threshold():
+    """The threshold lies in a run of equal magnitudes far longer than the short
+    list of the deciding bin: the last member is found from per-chunk counts
+    (path bit 2), not by the slow selection over all candidates (bit 0)."""
     d = 300_000
     g = np.full(d, -2.5, np.float32)
     g[::1000] = 3.0
     m = np.zeros(d, np.float32)
     st = _check(g, m, 5000, 500, 9, 9)
-    assert st["path"] & 1 and st["count_greater"] == 300 and st["ties_taken"] == 4700
+    assert st["path"] == 4 and st["count_greater"] == 300 and st["ties_taken"] == 4700
     st = _check(np.zeros(d, np.float32), m, 1000, 10, 9, 9)
-    assert st["path"] & 1
+    assert st["path"] == 4
+    rng = np.random.default_rng(31)
+    for case, (g, r, k) in enumerate((
+            (rng.integers(-1, 2, d).astype(np.float32), 9_000, 900),            # ternary
+            ((rng.integers(0, 2, d) * 2 - 1).astype(np.float32) * 0.125, d // 2, d // 8),  # signs
+            (np.where(rng.random(d) < 0.01, rng.standard_normal(d), 0.0).astype(np.float32),
+             10_000, 2_500),                                                     # fewer nonzeros than r
+            (np.round(rng.standard_normal(d) * 1.5).astype(np.float32), 30_000, 30_000),  # few levels, r = k
+            (np.round(rng.standard_normal(d) * 1.5).astype(np.float32), 250_000, 1),
+    )):
+        st = _check(g, np.zeros(d, np.float32), r, k, 77, case)
+        assert st["path"] == 4, (case, st)
+    # error feedback on top: the residual of step 0 moves the run's members out of the run
+    g = np.full(d, 0.5, np.float32)
+    m = np.zeros(d, np.float32)
+    for t in range(3):
+        want = oracle.encode(g, m, 2_000, 400, 5, t)
+        got = _u().gpu_encode_once(g, m, 2_000, 400, 5, t)
+        _u().assert_encode_equal(got, want, f"t={t}")
+        assert got[3]["path"] == 4, (t, got[3])
+        m = want[2]
+    # the run ends in the very last chunk, and in the very first entry
+    g = np.zeros(d, np.float32)
+    st = _check(g, m * 0, d - 1, 7, 3, 3)
+    assert st["path"] == 4 and st["ties_taken"] == d - 1
+    st = _check(g, m * 0, 1, 1, 3, 3)
+    assert st["ties_taken"] == 1
+
+
+def test_crowded_deciding_bin_with_two_magnitudes_takes_the_slow_selection():
+    """Two neighbouring patterns share the deciding bin and fill it beyond the
+    short list: no run of equal magnitudes, the exact selection over all
+    candidates decides (path bit 0)."""
+    d = 200_000
+    rng = np.random.default_rng(8)
+    one = np.float32(1.0)
+    g = np.where(rng.random(d) < 0.5, one, np.nextafter(one, np.float32(2.0))).astype(np.float32)
+    g *= rng.choice(np.array([-1.0, 1.0], np.float32), d)
+    st = _check(g, np.zeros(d, np.float32), 120_000, 20_000, 4, 4)
+    assert st["path"] & 1 and not st["path"] & 4, st
 
 
 def test_special_cases_top_k_and_random_k():
