@@ -908,10 +908,12 @@ classify_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ s
     // entry p of this workgroup's short lists lives at [p][workgroup]: the
     // finalize kernel reads entry p of all workgroups with one coalesced load
     auto slot = [&](u32 p) { return (u64)p * g.G3 + blockIdx.x; };
+    const u64 below = lanes_below();
     walk.for_each(cand, [&](bool valid, u32 i, u32 idx, u32 bits, u32, u32) {
-        if (!valid) return;
         const u32 m = mag_of(bits);
-        if (g.all_members != 0u || m > bd_hi) {
+        const bool member = valid && (g.all_members != 0u || m > bd_hi);
+        const bool in_bin = valid && !member && m >= bd_lo;
+        if (member) {
             bool sure = g.take_all != 0u;
             if (!sure) {
                 const u64 key = sample_key(idx, seed);
@@ -923,8 +925,15 @@ classify_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ s
                 }
             }
             if (sure) atomicAdd(&per_chunk[wave][i], 1u);
-        } else if (m >= bd_lo) {
-            const u32 p = atomicAdd(&cnt_b, 1u);
+        }
+        if (in_bin) {
+            // Entries of the deciding bin are few, or nearly all there is (a run of equal
+            // magnitudes): the lanes that are here take their list slots with one addition.
+            const u64 here = __ballot(true);
+            u32 base = 0;
+            if ((here & below) == 0ull) base = atomicAdd(&cnt_b, popc64(here));
+            base = (u32)__builtin_amdgcn_readfirstlane((int)base);
+            const u32 p = base + popc64(here & below);
             if (p < kListCap) { b_mag[slot(p)] = m; b_idx[slot(p)] = idx; }
             atomicAdd(&per_chunk_b[wave][i], 1u);
             if (m < lane_bmin) { lane_bmin = m; atomicMin(&bmin_s, m); }
@@ -1078,6 +1087,7 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
     __shared__ u32 extra_m, sure_extra;
     __shared__ unsigned long long gt_extra;
     __shared__ u32 run_chunk, run_before, run_index, run_found;
+    __shared__ u32 run_sure[kFinWaves][kUnitChunks];
 
     const u32 tid = threadIdx.x;
     const u32 wave = tid / kWave, lane = lane_id();
@@ -1099,7 +1109,6 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
     const bool in_grid = tid < g.G3;
     const u32 vm = in_grid ? n_m[tid] : 0u, vb = in_grid ? n_b[tid] : 0u;
     const u32 vs = in_grid ? blk_sure[tid] : 0u;
-    const u32 vmin = in_grid ? blk_bmin[tid] : 0xFFFFFFFFu, vmax = in_grid ? blk_bmax[tid] : 0u;
     const u32 bd_lo = ctl->bd_lo, bd_hi = ctl->bd_hi, bd_bits = ctl->bd_bits;
     const u64 c_def = ctl->c_def;
     const bool overflow = ctl->overflow != 0u, overflow_m = ctl->overflow_m != 0u;
@@ -1126,7 +1135,8 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
     // The list B overflowed but M did not, and every entry of the deciding bin has
     // the same magnitude: the last member is the need2-th of them in index order.
     bool tie_run = false;
-    if (!dense && overflow && !overflow_m && !g.all_members && c_def < g.r) {
+    if (__builtin_expect(!dense && overflow && !overflow_m && !g.all_members && c_def < g.r, 0)) {
+        const u32 vmin = in_grid ? blk_bmin[tid] : 0xFFFFFFFFu, vmax = in_grid ? blk_bmax[tid] : 0u;
         const u32 lo = wave_min(vmin), hi = wave_max(vmax);
         if (lane == 0) { scan32[wave] = lo; scan32[kFinWaves + wave] = hi; }
         lds_barrier();
@@ -1167,7 +1177,7 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
         }
         if (b_lds && m_lds) lds_barrier(); else __syncthreads();
         Pair96 tb{0ull, 0u};
-        if (tie_run) {
+        if (__builtin_expect(tie_run, 0)) {
             // ---- the chunk that holds the need2-th entry of the run: thread t
             //      adds up the counts of chunks 32t .. 32t+31 ---------------------
             path = 4;
@@ -1185,17 +1195,21 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
             // (the entries of the bin number at most d < 2^32)
             const u32 before = block_exclusive_sum(mine, scan32);
             if ((u64)before < need2 && need2 <= (u64)before + mine) {
-                // one thread: its counters again, one by one
-                u32 run = before;
-                for (u32 s = tid * kPer; s < g.W; ++s) {
-                    const u32 c = bd_cnt[s];
-                    if ((u64)run + c >= need2) {
-                        run_chunk = s;
-                        run_before = run;
-                        run_found = 1u;
-                        break;
-                    }
-                    run += c;
+                run_chunk = tid * kPer;          // first of the kPer chunks that hold it
+                run_before = before;
+                run_found = 1u;
+            }
+            lds_barrier();
+            if (wave == 0 && run_found != 0u) {
+                // the counters of those chunks again, one per lane
+                static_assert(kPer <= kWave, "one lane per counter");
+                const u32 s0 = run_chunk, b0 = run_before;
+                const u32 s = s0 + lane;
+                const u32 c = (lane < kPer && s < g.W) ? bd_cnt[s] : 0u;
+                const u32 inc = wave_inclusive_sum(c);
+                if ((u64)b0 + (inc - c) < need2 && need2 <= (u64)b0 + inc) {
+                    run_chunk = s;
+                    run_before = b0 + (inc - c);
                 }
             }
             lds_barrier();
@@ -1239,45 +1253,64 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
             }
             // ---- members of the deciding bin join the key lists; the atomics
             //      on the chunk counters are left in flight --------------------
-            auto join = [&](u32 idx) {
-                bool sure = g.take_all != 0u;
-                if (!sure) {
-                    const u64 key = sample_key(idx, seed);
-                    if (key < g.K_lo) {
-                        sure = true;
-                    } else if (key <= g.K_hi) {
-                        const u32 q = atomicAdd(&extra_m, 1u);
-                        if (n_m0 + q < m_cap) {
-                            mk[n_m0 + q] = (key - g.K_lo) << g.k_nlz;
-                            mi[n_m0 + q] = idx;
-                        }
+            // join(idx, on_sure): idx is a member; its key decides between "certain
+            // winner" (on_sure is called), the key list M, or nothing
+            auto join = [&](u32 idx, auto &&on_sure) {
+                if (g.take_all != 0u) { on_sure(); return; }
+                const u64 key = sample_key(idx, seed);
+                if (key < g.K_lo) {
+                    on_sure();
+                } else if (key <= g.K_hi) {
+                    const u32 q = atomicAdd(&extra_m, 1u);
+                    if (n_m0 + q < m_cap) {
+                        mk[n_m0 + q] = (key - g.K_lo) << g.k_nlz;
+                        mi[n_m0 + q] = idx;
                     }
                 }
-                if (sure) { atomicAdd(&win_cnt[idx / g.C], 1u); atomicAdd(&sure_extra, 1u); }
             };
             u32 my_gt = 0;
-            if (lists) {
+            if (__builtin_expect(lists, 1)) {
                 for (u32 p = tid; p < n_bd; p += kFinThreads) {
                     const u64 hi = bk[p];
                     const u32 idx = bi[p];
                     if (hi < tb.hi) ++my_gt;
-                    if (pair_le(hi, idx, tb)) join(idx);
+                    if (pair_le(hi, idx, tb))
+                        join(idx, [&] { atomicAdd(&win_cnt[idx / g.C], 1u); atomicAdd(&sure_extra, 1u); });
                 }
             } else {
-                // the run's members: its entries up to index I*, all in chunks 0 .. run_chunk
+                // the run's members: its entries up to index I*, all in chunks 0 .. run_chunk.
+                // They may be many per chunk: certain winners are counted per chunk in LDS
+                // and reach the chunk's counter as one addition.
                 const u32 s_end = run_chunk + 1u;
+                u32 my_sure = 0;
                 for (u32 first = wave * kUnitChunks; first < s_end; first += kFinWaves * kUnitChunks) {
+                    if (lane < kUnitChunks) run_sure[wave][lane] = 0u;
+                    __builtin_amdgcn_wave_barrier();
                     const UnitWalk walk(cand, first, 1u, s_end);
-                    walk.for_each(cand, [&](bool valid, u32, u32 idx, u32 bits, u32, u32) {
+                    walk.for_each(cand, [&](bool valid, u32 i, u32 idx, u32 bits, u32, u32) {
                         const u32 m = mag_of(bits);
-                        if (valid && m >= bd_lo && m <= bd_hi && idx <= I_star) join(idx);
+                        if (valid && m >= bd_lo && m <= bd_hi && idx <= I_star)
+                            join(idx, [&] { atomicAdd(&run_sure[wave][i], 1u); ++my_sure; });
                     });
+                    __builtin_amdgcn_wave_barrier();
+                    if (lane < kUnitChunks && first + lane < s_end && run_sure[wave][lane])
+                        atomicAdd(&win_cnt[first + lane], run_sure[wave][lane]);
+                    __builtin_amdgcn_wave_barrier();
                 }
+                my_sure = wave_sum(my_sure);
+                if (lane == 0 && my_sure) atomicAdd(&sure_extra, my_sure);
             }
             if (my_gt) atomicAdd(&gt_extra, (unsigned long long)my_gt);
             if (m_lds) lds_barrier(); else __syncthreads();
             count_greater = c_def + gt_extra;
             n_mm = n_m0 + extra_m;
+            if (__builtin_expect(tie_run && n_mm <= kStageM && n_mm <= m_cap, 0)) {
+                // short after all: the selection below reads it several times, from LDS then
+                for (u32 p = tid; p < n_mm; p += kFinThreads) { st_m_key[p] = mk[p]; st_m_idx[p] = mi[p]; }
+                mk = st_m_key;
+                mi = st_m_idx;
+                lds_barrier();
+            }
             const u64 c_klo = sure_walk + sure_extra;
             if (g.take_all) {
                 have_k = true;
