@@ -118,3 +118,25 @@ def test_full_size_batched_step_as_the_benchmark_launches_it(cfg, second_step_me
         torch.cuda.synchronize()
         ai, av = idx.cpu().numpy().view(np.uint32), val.cpu().numpy()
         assert np.array_equal(u.bits(out.cpu().numpy()), u.bits(oracle.aggregate_f32(ai, av, n, d)))
+
+
+def test_full_size_run_of_equal_magnitudes_at_the_threshold():
+    """cfg3's sizes, but the vector is a frozen tensor's (all zeros) and then a
+    ternary one: the threshold lies in a run of millions of equal magnitudes.
+    Bit-exact against the oracle, over two steps with error feedback, and
+    resolved from the per-chunk counts (path bit 2), not by the slow selection."""
+    u = _u()
+    wl = Workload(3)
+    d, r, k = wl.d, wl.r, wl.k
+    rng = np.random.default_rng(17)
+    for name, g in (("zeros", np.zeros(d, np.float32)),
+                    ("ternary", rng.integers(-1, 2, d).astype(np.float32))):
+        w = u.GpuWorker(d, r, k)
+        res = np.zeros(d, np.float32)
+        for t in range(2):
+            print(f"{name} d={d} step={t}", flush=True)
+            got = w.encode(g, 5, t)
+            oi, ov, res = oracle.encode(g, res, r, k, 5, t)
+            u.assert_encode_equal(got, (oi, ov, res), f"{name} t={t}")
+            assert w.stats["path"] == 4 and w.stats["error_flags"] == 0, w.stats
+        del w
