@@ -10,8 +10,10 @@
 // and worker the wavefront then reads the next 64 (index, value) pairs of the
 // message with one coalesced load (eight workers' loads in flight together),
 // adds the pairs that fall below the tile's end into the LDS tile and moves
-// the worker's position on by their number; a slice that fills all 64 lanes
-// simply continues with the next 64. No search is needed from tile to tile.
+// the worker's position on by their number; when a slice fills all 64 lanes
+// (the message is crowded in this tile: the top coordinates of one layer) the
+// next eight groups of 64 are fetched together and added in order. No search
+// is needed from tile to tile.
 // Workers are taken in order 0, 1, ... and a wavefront's LDS accesses execute
 // in program order, so the order of the binary32 additions is fixed: +0, then
 // worker 0, 1, ... The tile is finally divided by n and written with 16-byte
@@ -41,6 +43,7 @@ constexpr int kAggThreads = 256;
 constexpr int kAggWaves = kAggThreads / kWave;
 constexpr int kAggTile = 2048;
 constexpr int kAggAhead = 8;              // workers whose next pairs are fetched together
+constexpr int kAggMore = 8;               // further slices of one crowded message fetched together
 constexpr unsigned kAggMaxWaves = 4096;
 
 __device__ __forceinline__ u32 popc_mask(u64 m) { return (u32)__popcll((unsigned long long)m); }
@@ -166,9 +169,8 @@ k_aggregate(const u32 *__restrict__ idx, const float *__restrict__ val, u32 n, u
                     const u32 *si = idx + (u64)(w0 + w) * k;
                     const float *sv = val + (u64)(w0 + w) * k;
                     u64 at = from[q];
-                    u32 i = ri[q];
-                    float v = rv[q];
-                    while (true) {
+                    // 64 pairs into the tile; returns how many of them lay inside it
+                    auto add_slice = [&](u32 i, float v) -> u32 {
                         const bool inside = (u64)i < tile_end;     // 0xFFFFFFFF marks "no entry"
                         const u64 mask = __ballot(inside);         // a prefix of the lanes: sorted
                         // repeated indices inside one message (never produced by the
@@ -183,12 +185,30 @@ k_aggregate(const u32 *__restrict__ idx, const float *__restrict__ val, u32 n, u
                                 if ((int)lane == src) tile[i - tile_base] += v;
                             }
                         }
-                        const u32 took = popc_mask(mask);
-                        at += took;
-                        if (took < (u32)kWave) break;              // the slice ended inside these 64
-                        const u64 j = at + lane;
-                        i = j < k ? si[j] : 0xFFFFFFFFu;
-                        v = j < k ? sv[j] : 0.0f;
+                        return popc_mask(mask);
+                    };
+                    u32 took = add_slice(ri[q], rv[q]);
+                    at += took;
+                    // The slice filled all 64 lanes: the message is crowded here (its
+                    // entries cluster in a few tiles). The next kAggMore slices are
+                    // fetched together and added in order up to the first that ends
+                    // inside the tile.
+                    while (took == (u32)kWave) {
+                        u32 mi[kAggMore];
+                        float mv[kAggMore];
+#pragma unroll
+                        for (int s2 = 0; s2 < kAggMore; ++s2) {
+                            const u64 j = at + (u64)s2 * kWave + lane;
+                            mi[s2] = j < k ? si[j] : 0xFFFFFFFFu;
+                            mv[s2] = j < k ? sv[j] : 0.0f;
+                        }
+#pragma unroll
+                        for (int s2 = 0; s2 < kAggMore; ++s2) {
+                            if (took == (u32)kWave) {
+                                took = add_slice(mi[s2], mv[s2]);
+                                at += took;
+                            }
+                        }
                     }
                     // the new position of worker w goes back into lane w
                     if (lane == w) lo = at;

@@ -324,6 +324,39 @@ def test_aggregate_random_messages(d, n, k):
     assert np.array_equal(u.bits(out), u.bits(oracle.aggregate_f32(idx, val, n, d)))
 
 
+def test_aggregate_crowded_messages():
+    """Messages whose entries cluster in a few tiles (the top coordinates of one
+    layer): one worker's slice of a tile runs to hundreds or thousands of pairs,
+    fetched several 64-pair groups at a time. Contiguous runs, a run that ends
+    exactly at a group boundary, a run up to the very end of the list, repeated
+    indices inside a long run; dense aggregate and the momentum form."""
+    u = _u()
+    rng = np.random.default_rng(41)
+    d = 300_000
+    cases = []
+    for n, k, lo, span in ((3, 5000, 10_000, 5000),        # contiguous: 2048 pairs per tile and worker
+                           (8, 4000, 123_456, 9000),       # ~900 per tile
+                           (2, 64 * 9, 4096, 64 * 9),      # 1 + 8 groups exactly
+                           (2, 64 * 17, 2048 * 7, 2048),   # repeated indices: longer than the tile is wide
+                           (5, 3000, d - 3500, 3500)):     # up to the end of the vector and of the list
+        if span >= k:
+            idx = np.stack([np.sort(rng.choice(span, k, replace=False)) + lo for _ in range(n)])
+        else:
+            idx = np.stack([np.sort(rng.integers(0, span, k)) + lo for _ in range(n)])
+        val = rng.standard_normal((n, k)).astype(np.float32)
+        cases.append((idx.astype(np.uint32), val, n))
+    for idx, val, n in cases:
+        out = u.gpu_aggregate(idx, val, n, d)
+        assert np.array_equal(u.bits(out), u.bits(oracle.aggregate_f32(idx, val, n, d)))
+        omega = rng.standard_normal(d).astype(np.float32)
+        vel = rng.standard_normal(d).astype(np.float32)
+        gw, gv = u.gpu_aggregate_update_momentum(idx, val, n, d, 0.25, 1.5, 0.9, omega, vel, 0)
+        ww, wv = oracle.aggregate_update_momentum_f32(idx, val, n, d, 0.25, 1.5, 0.9, omega, vel)
+        assert np.array_equal(u.bits(gw), u.bits(ww)) and np.array_equal(u.bits(gv), u.bits(wv))
+        got = u.gpu_aggregate_update(idx, val, n, d, 0.25, 1.5, omega)
+        assert np.array_equal(u.bits(got), u.bits(oracle.aggregate_update_f32(idx, val, n, d, 0.25, 1.5, omega)))
+
+
 def test_aggregate_repeated_index_inside_one_message_is_added_again():
     u = _u()
     d, n = 9000, 2
