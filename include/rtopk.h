@@ -17,6 +17,10 @@
  *     NULL for the default stream) and the call returns at once. The caller
  *     owns all buffers, workspace included, and must keep them alive until the
  *     stream has drained.
+ *   - The hot-path calls only launch kernels (what must start at zero is
+ *     cleared by those kernels, not by memset nodes): they may be issued on a
+ *     stream that is being captured into a HIP graph and replayed. The stats,
+ *     trace and force hooks are for eager use.
  *   - Two calls may run concurrently only with distinct workspaces, residuals
  *     and outputs.
  *   - Return value: RTOPK_OK or a negative error code; rtopk_strerror() gives

@@ -810,3 +810,78 @@ def test_seeded_random_sweep_of_sizes_and_value_patterns():
         gw, gv = u.gpu_aggregate_update_momentum(ai, av, n, d, 0.125, 2.0, 0.5, omega, vel)
         ww, wv = oracle.aggregate_update_momentum_f32(ai, av, n, d, 0.125, 2.0, 0.5, omega, vel)
         assert u.same_floats(gw, ww) and u.same_floats(gv, wv), what
+
+
+# --------------------------------------------------------------------------
+# the whole step inside a captured HIP graph
+# --------------------------------------------------------------------------
+def test_step_captured_in_a_hip_graph_replays_bit_exactly():
+    """The library allocates nothing, clears what it needs with its own kernels
+    and never synchronises: a step (batched encode + aggregate + fused update)
+    can be captured into a HIP graph. Every replay, with eager work and
+    synchronisations in between, must give the oracle's result again."""
+    import torch
+    import paper_2005_10761_amd as rt
+    u = _u()
+    dev = u.DEV
+    n, d = 3, 200_003
+    wl = Workload(2, d=d)
+    r, k = wl.r, wl.k
+    gs = [wl.gradient(w, 0) for w in range(n)]
+    m0 = [(np.random.default_rng(w).standard_normal(d) * 1e-3).astype(np.float32) for w in range(n)]
+    seeds = [philox_seed_for_worker(w) for w in range(n)]
+    want = [oracle.encode(gs[w], m0[w], r, k, seeds[w], 11) for w in range(n)]
+    wi = np.concatenate([w_[0] for w_ in want])
+    wv = np.concatenate([w_[1] for w_ in want])
+    omega0 = np.random.default_rng(99).standard_normal(d).astype(np.float32)
+
+    stride = rt.encode_workspace_bytes(d, r, k)
+    ws = torch.empty(n * stride, dtype=torch.uint8, device=dev)
+    wsu = torch.empty(rt.aggregate_update_workspace_bytes(d, n, k), dtype=torch.uint8, device=dev)
+    g = [torch.from_numpy(x).to(dev) for x in gs]
+    m = [torch.from_numpy(x).to(dev) for x in m0]
+    m_init = [t.clone() for t in m]
+    idx = torch.empty(n * k, dtype=torch.int32, device=dev)
+    val = torch.empty(n * k, dtype=torch.float32, device=dev)
+    oi = [idx[i * k:(i + 1) * k] for i in range(n)]
+    ov = [val[i * k:(i + 1) * k] for i in range(n)]
+    out = torch.empty(d, dtype=torch.float32, device=dev)
+    omega = torch.from_numpy(omega0).to(dev)
+    omega_init = omega.clone()
+
+    def step():
+        rt.encode_batch(g, m, r, k, seeds, 11, oi, ov, ws)
+        rt.aggregate(idx, val, n, k, out)
+        rt.aggregate_update(idx, val, n, k, 0.5, 1.0, omega, wsu)
+
+    def reset():
+        for t, t0 in zip(m, m_init):
+            t.copy_(t0)
+        omega.copy_(omega_init)
+        idx.fill_(-1)
+        val.fill_(float("nan"))
+        out.fill_(float("nan"))
+        ws.fill_(0x5A)
+
+    def check(what):
+        torch.cuda.synchronize()
+        for w in range(n):
+            got = (oi[w].cpu().numpy().view(np.uint32), ov[w].cpu().numpy(), m[w].cpu().numpy())
+            u.assert_encode_equal(got, want[w], f"{what} worker {w}")
+        assert np.array_equal(u.bits(out.cpu().numpy()), u.bits(oracle.aggregate_f32(wi, wv, n, d))), what
+        assert np.array_equal(u.bits(omega.cpu().numpy()),
+                              u.bits(oracle.aggregate_update_f32(wi, wv, n, d, 0.5, 1.0, omega0))), what
+
+    reset()
+    step()                                        # eager, also the first call on this device
+    check("eager")
+    reset()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        reset()                                   # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        check(f"replay {rep}")
