@@ -45,6 +45,7 @@ constexpr int kAggTile = 2048;
 constexpr int kAggAhead = 8;              // workers whose next pairs are fetched together
 constexpr int kAggMore = 8;               // further slices of one crowded message fetched together
 constexpr unsigned kAggMaxWaves = 4096;
+constexpr unsigned kMomentumLdsClaim = 30u * 1024u;   // with the 32 KB of tiles: two workgroups per unit
 
 __device__ __forceinline__ u32 popc_mask(u64 m) { return (u32)__popcll((unsigned long long)m); }
 
@@ -563,8 +564,11 @@ extern "C" int rtopk_aggregate_update_momentum(const uint32_t *idx, const float 
     const u32 tiles_per_wave = (u32)((tiles + kAggMaxWaves - 1) / kAggMaxWaves);
     const u64 waves = (tiles + tiles_per_wave - 1) / tiles_per_wave;
     const unsigned grid = (unsigned)((waves + kAggWaves - 1) / kAggWaves);
-    k_aggregate<true><<<grid, kAggThreads, 0, stream>>>(idx, val, n, k, d, tiles, tiles_per_wave,
-                                                        omega, Momentum{scale, mu, -eta, velocity});
+    // This form streams 16 bytes per coordinate and is bound by HBM alone: two
+    // workgroups per compute unit (eight wavefronts) stream 6% faster than the five
+    // that fit, so each workgroup also claims LDS it does not use.
+    k_aggregate<true><<<grid, kAggThreads, kMomentumLdsClaim, stream>>>(
+        idx, val, n, k, d, tiles, tiles_per_wave, omega, Momentum{scale, mu, -eta, velocity});
     if (hipGetLastError() != hipSuccess) return RTOPK_EHIP;
     return RTOPK_OK;
 }
