@@ -85,7 +85,7 @@ constexpr u32 kEstThreads = 1024;
 constexpr u32 kNoSample = 0xFFFFFFFFu;
 
 constexpr u32 kChunkQuantum = 256;            // one wavefront iteration: 64 lanes x 4 elements
-constexpr u32 kChunkAlign = 4 * kChunkQuantum; // chunks are whole groups of four iterations
+constexpr u32 kMinChunk = 4 * kChunkQuantum;  // short vectors: chunks of four iterations
 constexpr u32 kTargetChunks = 32768;          // short chunks, dealt round-robin to the wavefronts
 constexpr u32 kMaxUnits = 4096;               // wavefronts of classify / emit
 constexpr u32 kUnitChunks = kTargetChunks / kMaxUnits;   // chunks one of them walks, at most
@@ -161,7 +161,7 @@ struct EncodeCtl {
 // Geometry and sampling window: a pure function of (d, r, k), computed on the host.
 struct Geom {
     u64 d, r, k;
-    u32 C;              // elements per chunk (multiple of 1024)
+    u32 C;              // elements per chunk (multiple of 256, at least 1024)
     u32 W;              // chunks
     u32 U;              // wavefronts of classify / emit; wavefront u walks chunks u, u + U, ...
     u32 G3;             // classify / emit workgroups
@@ -188,7 +188,13 @@ static Geom make_geom(u64 d, u64 r, u64 k)
     Geom g{};
     g.d = d; g.r = r; g.k = k;
     u64 per = (d + kTargetChunks - 1) / kTargetChunks;
-    per = (per + kChunkAlign - 1) / kChunkAlign * kChunkAlign;
+    per = (per + kChunkQuantum - 1) / kChunkQuantum * kChunkQuantum;
+    if (per < kMinChunk) per = kMinChunk;
+    // Measured with a plain streaming add over 66 M and 268 M elements: when every
+    // wavefront's piece starts a multiple of 8 KB after its neighbour's (chunks of
+    // 2048, 3072, 4096 elements) the stream runs 5-9% slower than with 1024, 2304,
+    // 2560 or 8192 elements; a quarter of a kilobyte more staggers the starting points.
+    if (per > kMinChunk && per % 1024 == 0 && per % 8192 != 0) per += kChunkQuantum;
     g.C = (u32)per;
     g.W = (u32)((d + per - 1) / per);
     g.U = g.W < kMaxUnits ? g.W : kMaxUnits;
