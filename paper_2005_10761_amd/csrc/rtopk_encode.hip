@@ -31,13 +31,17 @@
 //              window [K_lo, K_hi] around the k-th smallest of r uniform
 //              keys - below: certain winner (counted per chunk), inside:
 //              copied to the short list M. Entries inside the deciding bin
-//              are copied to the short list B
+//              are copied to the short list B and counted per chunk
 //   finalize   one workgroup: exact r-th largest (magnitude, lower index
 //              first) inside B -> (T, I*); members of B join the key lists;
 //              exact (k - #certain)-th smallest (key, index) in M -> (K*, J*);
-//              prefix sum of the winners per chunk. Whenever a short list
-//              overflowed or the key window missed, the same quantities are
-//              found by radix selection over all of S instead (slow, exact)
+//              prefix sum of the winners per chunk. When B overflowed because
+//              the deciding bin is one long run of equal magnitudes (zeros,
+//              signs, a few levels), the last member is the entry of a known
+//              rank in index order and is located from the per-chunk counts.
+//              When a short list overflowed otherwise or the key window
+//              missed, the same quantities are found by radix selection over
+//              all of S instead (slow, exact)
 //   emit       entries of S that are members and winners -> the message in
 //              index order, starting at the chunk's prefix; residual at the
 //              sent positions <- a - a
