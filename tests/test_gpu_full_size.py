@@ -140,3 +140,75 @@ def test_full_size_run_of_equal_magnitudes_at_the_threshold():
             u.assert_encode_equal(got, (oi, ov, res), f"{name} t={t}")
             assert w.stats["path"] == 4 and w.stats["error_flags"] == 0, w.stats
         del w
+
+
+def test_largest_vector_the_index_type_allows():
+    """d = 2^32 - 1, the largest length a 32-bit index addresses (chunks of
+    131072 elements, 51 GB streamed). Inputs are drawn on the device; what the
+    definition fixes is checked with plain torch reductions over the whole
+    vector, and the k-subset itself with the oracle's Philox keys of the r
+    members: the threshold is the r-th largest magnitude, the message is the k
+    members with the smallest (key, index) in index order with the values of
+    a = g + m, and the residual is a with exactly those k positions cleared.
+    The aggregate of that one message (n = 1) is the message scattered."""
+    import torch
+    import paper_2005_10761_amd as rt
+    u = _u()
+    dev = u.DEV
+    d = 2 ** 32 - 1
+    r, k = 200_000, 20_000
+    seed, step = 0x9E3779B97F4A7C15, 2 ** 40 + 7
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(2005_10761)
+    print(f"largest d={d}: inputs", flush=True)
+    g = torch.randn(d, device=dev, generator=gen)
+    g.mul_(g.abs()).mul_(1e-3)                               # heavier tail than a normal
+    m = torch.randn(d, device=dev, generator=gen).mul_(1e-3)
+    a = g + m                                                # one binary32 add per coordinate
+    ws = torch.empty(rt.encode_workspace_bytes(d, r, k), dtype=torch.uint8, device=dev)
+    oi = torch.empty(k, dtype=torch.int32, device=dev)
+    ov = torch.empty(k, dtype=torch.float32, device=dev)
+    print("largest: encode", flush=True)
+    rt.encode(g, m, r, k, seed, step, oi, ov, ws)
+    torch.cuda.synchronize()
+    st = rt.encode_stats(ws)
+    assert st["error_flags"] == 0 and st["path"] == 0, st
+    del ws, g
+    idx = oi.to(torch.int64) & 0xFFFFFFFF
+    assert bool((idx[1:] > idx[:-1]).all()) and int(idx[-1]) < d
+    assert torch.equal(ov.view(torch.int32), a[idx].view(torch.int32))
+
+    print("largest: threshold and members", flush=True)
+    T = st["threshold_bits"]
+    piece = 2 ** 30
+    c_gt = c_ge = 0
+    above, ties = [], []
+    for lo in range(0, d, piece):
+        mag = a[lo:lo + piece].view(torch.int32) & 0x7FFFFFFF
+        gt, eq = mag > T, mag == T
+        c_gt += int(gt.sum())
+        c_ge += int(gt.sum()) + int(eq.sum())
+        above.append(torch.nonzero(gt).flatten() + lo)
+        ties.append(torch.nonzero(eq).flatten() + lo)
+        del mag, gt, eq
+    assert c_gt == st["count_greater"] and c_gt < r <= c_ge, (c_gt, c_ge, st)
+    members = torch.cat(above + [torch.cat(ties)[:r - c_gt]]).cpu().numpy()
+    assert members.size == r
+    keys = np.array([oracle.key64(seed, step, int(i)) for i in members], dtype=np.uint64)
+    order = np.lexsort((members, keys))
+    want_idx = np.sort(members[order[:k]])
+    assert np.array_equal(idx.cpu().numpy(), want_idx)
+
+    print("largest: residual", flush=True)
+    a[idx] = 0.0                                             # a - a = +0 for the finite values sent
+    for lo in range(0, d, piece):
+        assert torch.equal(a[lo:lo + piece].view(torch.int32), m[lo:lo + piece].view(torch.int32)), lo
+    del a
+
+    print("largest: aggregate of the one message", flush=True)
+    rt.aggregate(oi, ov, 1, k, m)                            # m reused as the dense output
+    torch.cuda.synchronize()
+    assert torch.equal(m[idx].view(torch.int32), ov.view(torch.int32))
+    m[idx] = 0.0
+    for lo in range(0, d, piece):
+        assert int(torch.count_nonzero(m[lo:lo + piece].view(torch.int32))) == 0, lo
