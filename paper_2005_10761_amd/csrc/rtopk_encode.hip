@@ -1,5 +1,5 @@
 // rtopk_encode: one node-side step of Algorithm 1 (error compensation, the
-// rTop-k operator of Definition 3, residual write-back) as a chain of eight
+// rTop-k operator of Definition 3, residual write-back) as a chain of seven
 // gfx950 kernels that stream the gradient and the residual exactly once
 // (12d bytes). All cross-kernel state lives in the caller's workspace.
 //
@@ -23,9 +23,10 @@
 //              dominant kernel); entries with magnitude >= t_lo -> S, and
 //              into the workgroup's own histogram row: up to 2048 linear bins
 //              over the fine range, 256 exponent bins above it
-//   reduce     the workgroups' histogram rows -> 16 rows
-//   pick       one workgroup: sum of the 16 rows, and the bin that holds the
-//              r-th largest magnitude (the deciding bin)
+//              (every row also carries the sums over groups of 64 bins)
+//   pick       one workgroup: the group sums of all rows -> the group that
+//              holds the r-th largest magnitude; that group's bins of all
+//              rows -> the bin that holds it (the deciding bin)
 //   classify   entries of S above the deciding bin are certain members of
 //              the top-r set: their Philox key is compared with an a-priori
 //              window [K_lo, K_hi] around the k-th smallest of r uniform
@@ -49,7 +50,7 @@
 // sampling key is ever computed, and with r == d (random-k) no magnitude is
 // ever compared: the streaming kernel then keeps the elements whose key lies
 // at or below the upper end of the a-priori window, and sample, estimate,
-// reduce and pick are not launched at all.
+// and pick are not launched at all.
 //
 // Every kernel serves up to 16 independent vectors of equal sizes per launch
 // (blockIdx.z is the member; rtopk_encode_batch), each with its own slice of
@@ -81,7 +82,9 @@ constexpr u32 kCoarseShift = 23;              // coarse bins above them: the 8 e
 constexpr u32 kCoarseBins = 256;
 constexpr u32 kMaxBins = kMaxFineBins + kCoarseBins;
 constexpr u32 kMaxFusedBlocks = 1024;         // rows of per-workgroup histograms
-constexpr u32 kHistRows = 16;                 // rows left after the first reduction step
+constexpr u32 kCoarseSpan = 64;               // bins per group: every row also carries its group sums
+constexpr u32 kMaxGroups = kMaxBins / kCoarseSpan;
+static_assert(kMaxBins % kCoarseSpan == 0 && kCoarseSpan == 64, "one lane per bin of a group");
 
 constexpr u32 kSampleLoc = 16384;             // sampled locations, 4 consecutive elements each
 constexpr u32 kSampleThreads = 256;
@@ -179,7 +182,7 @@ struct Geom {
 };
 
 struct EncodeLayout {
-    u64 ctl, zero_bytes, partials, hist;
+    u64 ctl, zero_bytes, partials, group_sums;
     u64 samples, seg_count, win_cnt, bd_cnt, chunk_base, blk_sure, n_m, n_b, blk_bmin, blk_bmax;
     u64 m_key, m_idx, b_mag, b_idx;
     u64 dm_key, dm_idx, db_key, db_idx;
@@ -236,7 +239,7 @@ static EncodeLayout make_layout(const Geom &g)
     L.ctl = take(sizeof(EncodeCtl));
     L.zero_bytes = o;
     L.partials = take((u64)kMaxFusedBlocks * kMaxBins * 4);
-    L.hist = take((u64)kHistRows * kMaxBins * 4);
+    L.group_sums = take((u64)kMaxFusedBlocks * kMaxGroups * 4);
     L.samples = take((u64)kSampleLoc * 16);
     L.seg_count = take((u64)kTargetChunks * 4);      // fixed size: its offset depends on nothing
     L.win_cnt = take((u64)kTargetChunks * 4);
@@ -567,7 +570,7 @@ constexpr u32 kFusedWaves = kFusedThreads / kWave;
 template <bool kVec4, bool kAll>
 __device__ __forceinline__ void
 fused_body(const float *__restrict__ grad, float *__restrict__ residual, Geom g, PhiloxSeed seed,
-        EncodeCtl *__restrict__ ctl, u32 *__restrict__ partials,
+        EncodeCtl *__restrict__ ctl, u32 *__restrict__ partials, u32 *__restrict__ group_sums,
         u32 *__restrict__ seg_count, uint2 *__restrict__ s_ent)
 {
     __shared__ u32 h[kAll ? 1 : kMaxBins];
@@ -675,9 +678,18 @@ fused_body(const float *__restrict__ grad, float *__restrict__ residual, Geom g,
     if (kAll) return;
     __syncthreads();
     // The workgroup's histogram goes out as one dense row with plain stores:
-    // device-wide atomics here, however few, slow the whole stream down.
+    // device-wide atomics here, however few, slow the whole stream down. With
+    // it go the sums over groups of kCoarseSpan bins: the pick kernel first adds
+    // up those (a sixty-fourth of the data), finds the group that holds the
+    // r-th largest magnitude and then only needs that group's bins of every row.
     u32 *row = partials + (u64)blockIdx.x * nbins;
     for (u32 b = threadIdx.x; b < nbins; b += kFusedThreads) row[b] = h[b];
+    const u32 ngroups = (nbins + kCoarseSpan - 1) / kCoarseSpan;
+    for (u32 c = threadIdx.x / kWave; c < ngroups; c += kFusedWaves) {
+        const u32 b = c * kCoarseSpan + lane_id();
+        const u32 sum = wave_sum(b < nbins ? h[b] : 0u);
+        if (lane_id() == 0) group_sums[(u64)blockIdx.x * kMaxGroups + c] = sum;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -784,89 +796,116 @@ struct ChunkWalk {
 using UnitWalk = ChunkWalk<kUnitChunks>;     // classify / emit: chunks u, u + U, u + 2U, ...
 
 // ---------------------------------------------------------------------------
-// reduce: the rows the streaming workgroups stored -> kHistRows rows.
-// Workgroup (x, y): bins 256x .. 256x+255 of rows y, y + kHistRows, ...
-// ---------------------------------------------------------------------------
-constexpr u32 kReduceThreads = 256;
-
-__device__ __forceinline__ void
-reduce_body(const u32 *__restrict__ partials, u32 n_rows, const EncodeCtl *__restrict__ ctl,
-         u32 *__restrict__ hist)
-{
-    const u32 nbins = ctl->bins.nfine + kCoarseBins;
-    const u32 bin = blockIdx.x * kReduceThreads + threadIdx.x;
-    if (bin >= nbins) return;
-    u32 sum = 0;
-#pragma unroll 8
-    for (u32 row = blockIdx.y; row < n_rows; row += kHistRows) sum += partials[(u64)row * nbins + bin];
-    hist[blockIdx.y * nbins + bin] = sum;
-}
-
-// ---------------------------------------------------------------------------
-// pick: one workgroup adds the remaining rows up, walks the histogram from
-// the top and finds the bin that holds the r-th largest magnitude.
+// pick: one workgroup finds the bin that holds the r-th largest magnitude
+// from the rows the streaming workgroups stored, in two rounds of loads:
+// the group sums of all rows (which group holds it, and how many entries lie
+// above that group), then that group's bins of all rows.
 // ---------------------------------------------------------------------------
 constexpr u32 kPickThreads = 1024;
-constexpr u32 kPickPer = (kMaxBins + kPickThreads - 1) / kPickThreads;
+
+// lane l holds the count of the l-th position from the top (0 beyond the
+// last): the position p with #(above p) < need <= #(above p) + count(p), and
+// #(above p); found is false when all positions together do not reach need
+__device__ __forceinline__ void wave_pick_desc(u32 count, u64 need, u64 above_all, bool *found,
+                                               u32 *pos, u64 *above)
+{
+    const u32 inc = wave_inclusive_sum(count);
+    const u64 before = above_all + (inc - count);
+    const u64 owner = __ballot(before < need && need <= before + count);
+    *found = owner != 0ull;
+    const int src = *found ? __ffsll((unsigned long long)owner) - 1 : 0;
+    *pos = (u32)src;
+    const u32 b_lo = (u32)__builtin_amdgcn_readlane((int)(u32)before, src);
+    const u32 b_hi = (u32)__builtin_amdgcn_readlane((int)(u32)(before >> 32), src);
+    *above = ((u64)b_hi << 32) | b_lo;
+}
 
 __device__ __forceinline__ void
-pick_body(const u32 *__restrict__ hist, Geom g, EncodeCtl *ctl)
+pick_body(const u32 *__restrict__ partials, const u32 *__restrict__ group_sums, u32 n_rows, Geom g,
+          EncodeCtl *ctl)
 {
-    __shared__ u32 scan_lds[kPickThreads / kWave + 1];
-    __shared__ u32 bin_s;
-    __shared__ u32 before_s;
-    __shared__ u32 total[kMaxBins];
+    __shared__ u32 gtot[kMaxGroups];
+    __shared__ u32 btot[kCoarseSpan];
+    __shared__ u32 sel_group, sel_found;
+    __shared__ u64 sel_above;
     const Bins bins = ctl->bins;
     const u32 nbins = bins.nfine + kCoarseBins;
-    // the rows are added up in LDS: consecutive threads read consecutive words of the
-    // row-major array, every thread a few of them, all loads in flight together
-    for (u32 b = threadIdx.x; b < nbins; b += kPickThreads) total[b] = 0u;
-    if (threadIdx.x == 0) { bin_s = kMaxBins; before_s = 0u; }
+    const u32 ngroups = (nbins + kCoarseSpan - 1) / kCoarseSpan;
+    const u32 tid = threadIdx.x, lane = lane_id();
+    if (tid < kMaxGroups) gtot[tid] = 0u;
+    if (tid < kCoarseSpan) btot[tid] = 0u;
     lds_barrier();
-    const u32 words = nbins * kHistRows;
-    constexpr u32 kAhead = 8;
-    for (u32 i0 = threadIdx.x; i0 < words; i0 += kAhead * kPickThreads) {
-        u32 v[kAhead];
+    // ---- the group sums of every row, four loads per thread in flight together
+    //      (256 rows of 12 groups: one round)
+    {
+        constexpr u32 kAhead = 4;
+        const u32 words = n_rows * ngroups;
+        for (u32 i0 = tid; i0 < words; i0 += kAhead * kPickThreads) {
+            u32 v[kAhead];
 #pragma unroll
-        for (u32 q = 0; q < kAhead; ++q) {
-            const u32 i = i0 + q * kPickThreads;
-            v[q] = i < words ? hist[i] : 0u;
-        }
-#pragma unroll
-        for (u32 q = 0; q < kAhead; ++q) {
-            const u32 i = i0 + q * kPickThreads;
-            if (i < words && v[q]) atomicAdd(&total[i % nbins], v[q]);
-        }
-    }
-    __syncthreads();
-    // thread t owns the bins at walking positions kPickPer*t .. (bin nbins-1 comes first)
-    const u32 first = threadIdx.x * kPickPer;
-    u32 c[kPickPer];
-    u32 mine = 0;
-#pragma unroll
-    for (u32 q = 0; q < kPickPer; ++q) {
-        const u32 pos = first + q;
-        c[q] = pos < nbins ? total[nbins - 1u - pos] : 0u;
-        mine += c[q];
-    }
-    const u32 before = block_exclusive_sum(mine, scan_lds);   // candidates number less than 2^32
-    const u64 need = g.r;
-    if ((u64)before < need && need <= (u64)before + mine) {
-        u32 run = before;
-        bool done = false;
-#pragma unroll
-        for (u32 q = 0; q < kPickPer; ++q) {
-            if (!done && (u64)run + c[q] >= need) {
-                bin_s = nbins - 1u - (first + q);
-                before_s = run;
-                done = true;
+            for (u32 q = 0; q < kAhead; ++q) {
+                const u32 i = i0 + q * kPickThreads;
+                v[q] = i < words ? group_sums[(u64)(i / ngroups) * kMaxGroups + i % ngroups] : 0u;
             }
-            run += c[q];
+#pragma unroll
+            for (u32 q = 0; q < kAhead; ++q) {
+                const u32 i = i0 + q * kPickThreads;
+                if (v[q]) atomicAdd(&gtot[i % ngroups], v[q]);
+            }
         }
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        const bool dense = bin_s == kMaxBins;     // the histogram holds fewer than r entries
+    if (tid < kWave) {
+        // groups number at most 36: lane l looks at group ngroups - 1 - l
+        static_assert(kMaxGroups <= kWave, "one lane per group");
+        const u32 cnt = lane < ngroups ? gtot[ngroups - 1u - lane] : 0u;
+        bool found;
+        u32 pos;
+        u64 above;
+        wave_pick_desc(cnt, g.r, 0ull, &found, &pos, &above);
+        if (lane == 0) {
+            sel_found = found ? 1u : 0u;
+            sel_group = found ? ngroups - 1u - pos : 0u;
+            sel_above = above;
+        }
+    }
+    lds_barrier();
+    bool dense = sel_found == 0u;                  // all rows together hold fewer than r entries
+    u32 bin_s = 0;
+    u64 before_s = 0;
+    if (!dense) {
+        // ---- that group's bins of every row: 64 consecutive words per row, sixteen
+        //      loads per thread in flight together (256 rows: one round)
+        const u32 first_bin = sel_group * kCoarseSpan;
+        constexpr u32 kAhead = 16;
+        const u32 words = n_rows * kCoarseSpan;
+        for (u32 i0 = tid; i0 < words; i0 += kAhead * kPickThreads) {
+            u32 v[kAhead];
+#pragma unroll
+            for (u32 q = 0; q < kAhead; ++q) {
+                const u32 i = i0 + q * kPickThreads;
+                const u32 b = first_bin + i % kCoarseSpan;
+                v[q] = (i < words && b < nbins) ? partials[(u64)(i / kCoarseSpan) * nbins + b] : 0u;
+            }
+#pragma unroll
+            for (u32 q = 0; q < kAhead; ++q) {
+                const u32 i = i0 + q * kPickThreads;
+                if (v[q]) atomicAdd(&btot[i % kCoarseSpan], v[q]);
+            }
+        }
+        __syncthreads();
+        if (tid < kWave) {
+            const u32 cnt = btot[kCoarseSpan - 1u - lane];     // bins past nbins stayed 0
+            bool found;
+            u32 pos;
+            u64 above;
+            wave_pick_desc(cnt, g.r, sel_above, &found, &pos, &above);
+            bin_s = first_bin + (kCoarseSpan - 1u - pos);
+            before_s = above;
+            if (!found || bin_s >= nbins) dense = true;     // (the group's sum promised otherwise)
+        }
+    }
+    if (tid == 0) {
         u32 bd_lo = 0, bd_hi = 0;
         if (!dense) bin_range(bins, bin_s, &bd_lo, &bd_hi);
         ctl->dense = dense ? 1u : 0u;
@@ -1569,19 +1608,14 @@ __global__ void __launch_bounds__(kFusedThreads) k_fused(Batch B, Geom g, Encode
 {
     const Member m(B);
     fused_body<kVec4, kAll>(m.grad, m.residual, g, m.seed, m.at<EncodeCtl>(L.ctl),
-                            m.at<u32>(L.partials), m.at<u32>(L.seg_count), m.at<uint2>(L.s_ent));
+                            m.at<u32>(L.partials), m.at<u32>(L.group_sums), m.at<u32>(L.seg_count),
+                            m.at<uint2>(L.s_ent));
 }
 
-__global__ void __launch_bounds__(kReduceThreads) k_reduce(Batch B, u32 n_rows, EncodeLayout L)
+__global__ void __launch_bounds__(kPickThreads) k_pick(Batch B, u32 n_rows, Geom g, EncodeLayout L)
 {
     const Member m(B);
-    reduce_body(m.at<u32>(L.partials), n_rows, m.at<EncodeCtl>(L.ctl), m.at<u32>(L.hist));
-}
-
-__global__ void __launch_bounds__(kPickThreads) k_pick(Batch B, Geom g, EncodeLayout L)
-{
-    const Member m(B);
-    pick_body(m.at<u32>(L.hist), g, m.at<EncodeCtl>(L.ctl));
+    pick_body(m.at<u32>(L.partials), m.at<u32>(L.group_sums), n_rows, g, m.at<EncodeCtl>(L.ctl));
 }
 
 __global__ void __launch_bounds__(kWalkThreads) k_classify(Batch B, Geom g, EncodeLayout L)
@@ -1664,7 +1698,7 @@ struct StageScope {
 // together and share the chunks evenly, so none waits for a slot). Eight
 // wavefronts per compute unit with 8 x 16 bytes in flight per lane saturate
 // HBM; two or three workgroups per unit stream no faster, leave three times
-// the histogram rows to reduce and less room for kernels of other streams.
+// the histogram rows to add up and less room for kernels of other streams.
 // The count of units is looked up at the first call on the device.
 constexpr int kMaxDevices = 64;
 constexpr int kFusedBlocksPerCU = 1;
@@ -1818,15 +1852,11 @@ extern "C" int rtopk_encode_batch(uint32_t n, const float *const *grad, float *c
                     k_fused<false, false><<<fg, kFusedThreads, kFusedLdsClaim, stream>>>(B, g, L);
                 RTOPK_LAUNCH_CHECK();
             }
-            const dim3 rgrid((g.nfine + kCoarseBins + kReduceThreads - 1) / kReduceThreads,
-                             kHistRows, nb);
-            k_reduce<<<rgrid, kReduceThreads, 0, stream>>>(B, fgrid, L);
-            RTOPK_LAUNCH_CHECK();
         }
         {
             StageScope sc(trace, RTOPK_STAGE_CLASSIFY, stream);
             if (!g.all_members) {
-                k_pick<<<dim3(1, 1, nb), kPickThreads, 0, stream>>>(B, g, L);
+                k_pick<<<dim3(1, 1, nb), kPickThreads, 0, stream>>>(B, fgrid, g, L);
                 RTOPK_LAUNCH_CHECK();
             }
             k_classify<<<dim3(g.G3, 1, nb), kWalkThreads, 0, stream>>>(B, g, L);
