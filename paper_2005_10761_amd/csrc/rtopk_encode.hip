@@ -109,7 +109,7 @@ constexpr u32 kListCap = 512;                 // short-list slots per classify w
 constexpr int kFinThreads = 1024;
 constexpr u32 kFinWaves = kFinThreads / kWave;
 constexpr u32 kSlabs = kTargetChunks / (4 * kFinThreads);  // 16-byte groups of chunk counters per thread
-constexpr u32 kStageB = 2048, kStageM = 2304; // short lists that fit are selected in LDS
+constexpr u32 kStageB = 2048, kStageM = 4096; // short lists that fit are selected in LDS (cfg3: 600 and 2,700 entries)
 
 constexpr u32 kErrSelect = 2u;                // a selection found no element of the requested rank
 constexpr u32 kErrCount = 4u;                 // the winners did not add up to k
@@ -1195,36 +1195,60 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
         tie_run = all_lo == all_hi;
         if (tie_run) T = all_lo;
     }
-    if (lists || tie_run) {
-        // ---- both short lists, each thread copying the entries of its own
-        //      classify workgroup (a handful), all loads in one round --------
+    // The short-list path. It is compiled twice: once with both lists in LDS
+    // (the usual case; the compiler then knows the address space of every list
+    // access and overlaps the loads that fill the lists) and once with the
+    // lists wherever they fit.
+    auto short_lists = [&](u64 *bk, u32 *bi, u64 *mk, u32 *mi, auto all_lds_tag) {
+        constexpr bool kAllLds = decltype(all_lds_tag)::value;
         const u32 n_b_use = lists ? n_bd : 0u;
-        const bool b_lds = n_b_use <= kStageB;
-        u64 *bk = b_lds ? st_b_key : db_key;
-        u32 *bi = b_lds ? st_b_idx : db_idx;
-        // (a run of equal magnitudes may add any number of keys: the large array then)
-        const bool m_lds = lists && n_m0 + n_b_use <= kStageM;
-        u64 *mk = m_lds ? st_m_key : dm_key;
-        u32 *mi = m_lds ? st_m_idx : dm_idx;
+        const bool m_lds = kAllLds || (lists && n_m0 + n_b_use <= kStageM);
         const u32 m_cap = m_lds ? kStageM : 2u * g.G3 * kListCap;
+        auto barrier = [&] { if (kAllLds) lds_barrier(); else __syncthreads(); };
         // Entry j of classify workgroup t lives at [j][t]. First every thread
         // notes where the entries of its workgroup are (no memory latency in
         // that loop), then the entries are fetched position by position, all
         // loads of a thread in flight together.
         if (lists) for (u32 j = 0; j < vb; ++j) bi[eb + j] = j * g.G3 + tid;
         for (u32 j = 0; j < vm; ++j) mi[em + j] = j * g.G3 + tid;
-        if (b_lds && m_lds) lds_barrier(); else __syncthreads();
-        for (u32 p = tid; p < n_b_use; p += kFinThreads) {
-            const u32 at = bi[p];
-            bk[p] = (u64)(bd_hi - b_mag[at]);
-            bi[p] = b_idx[at];
+        barrier();
+        if (kAllLds) {
+            constexpr u32 kB = kStageB / kFinThreads, kM = kStageM / kFinThreads;
+            u32 b_m[kB], b_i[kB], m_i[kM];
+            u64 m_k[kM];
+#pragma unroll
+            for (u32 q = 0; q < kB; ++q) {
+                const u32 p = q * kFinThreads + tid;
+                if (p < n_b_use) { const u32 at = bi[p]; b_m[q] = b_mag[at]; b_i[q] = b_idx[at]; }
+            }
+#pragma unroll
+            for (u32 q = 0; q < kM; ++q) {
+                const u32 p = q * kFinThreads + tid;
+                if (p < n_m0) { const u32 at = mi[p]; m_k[q] = m_key[at]; m_i[q] = m_idx[at]; }
+            }
+#pragma unroll
+            for (u32 q = 0; q < kB; ++q) {
+                const u32 p = q * kFinThreads + tid;
+                if (p < n_b_use) { bk[p] = (u64)(bd_hi - b_m[q]); bi[p] = b_i[q]; }
+            }
+#pragma unroll
+            for (u32 q = 0; q < kM; ++q) {
+                const u32 p = q * kFinThreads + tid;
+                if (p < n_m0) { mk[p] = (m_k[q] - g.K_lo) << g.k_nlz; mi[p] = m_i[q]; }
+            }
+        } else {
+            for (u32 p = tid; p < n_b_use; p += kFinThreads) {
+                const u32 at = bi[p];
+                bk[p] = (u64)(bd_hi - b_mag[at]);
+                bi[p] = b_idx[at];
+            }
+            for (u32 p = tid; p < n_m0; p += kFinThreads) {
+                const u32 at = mi[p];
+                mk[p] = (m_key[at] - g.K_lo) << g.k_nlz;
+                mi[p] = m_idx[at];
+            }
         }
-        for (u32 p = tid; p < n_m0; p += kFinThreads) {
-            const u32 at = mi[p];
-            mk[p] = (m_key[at] - g.K_lo) << g.k_nlz;
-            mi[p] = m_idx[at];
-        }
-        if (b_lds && m_lds) lds_barrier(); else __syncthreads();
+        barrier();
         Pair96 tb{0ull, 0u};
         if (__builtin_expect(tie_run, 0)) {
             // ---- the chunk that holds the need2-th entry of the run: thread t
@@ -1350,7 +1374,7 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
                 if (lane == 0 && my_sure) atomicAdd(&sure_extra, my_sure);
             }
             if (my_gt) atomicAdd(&gt_extra, (unsigned long long)my_gt);
-            if (m_lds) lds_barrier(); else __syncthreads();
+            barrier();
             count_greater = c_def + gt_extra;
             n_mm = n_m0 + extra_m;
             if (__builtin_expect(tie_run && n_mm <= kStageM && n_mm <= m_cap, 0)) {
@@ -1377,6 +1401,17 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
                 }
             }
         }
+    };
+    if (lists || tie_run) {
+        const u32 n_b_use = lists ? n_bd : 0u;
+        const bool b_lds = n_b_use <= kStageB;
+        // (a run of equal magnitudes may add any number of keys: the large array then)
+        const bool m_lds = lists && n_m0 + n_b_use <= kStageM;
+        if (b_lds && m_lds)
+            short_lists(st_b_key, st_b_idx, st_m_key, st_m_idx, std::true_type{});
+        else
+            short_lists(b_lds ? st_b_key : db_key, b_lds ? st_b_idx : db_idx,
+                        m_lds ? st_m_key : dm_key, m_lds ? st_m_idx : dm_idx, std::false_type{});
     }
 
     if (g.all_members && !have_k) {
