@@ -1249,6 +1249,27 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
             }
         }
         barrier();
+        // (in LDS a thread's entries, two at most, stay in registers over the rounds)
+        constexpr u32 kB = kAllLds ? kStageB / kFinThreads : 1u;
+        u64 rb_k[kB];
+        u32 rb_i[kB];
+        if (kAllLds) {
+#pragma unroll
+            for (u32 q = 0; q < kB; ++q) {
+                const u32 p = q * kFinThreads + tid;
+                rb_k[q] = p < n_bd ? bk[p] : 0ull;
+                rb_i[q] = p < n_bd ? bi[p] : 0u;
+            }
+        }
+        auto each_b = [&](auto &&f) {
+            if (kAllLds) {
+#pragma unroll
+                for (u32 q = 0; q < kB; ++q)
+                    if (q * kFinThreads + tid < n_bd) f(rb_k[q], rb_i[q]);
+            } else {
+                for (u32 p = tid; p < n_bd; p += kFinThreads) f(bk[p], bi[p]);
+            }
+        };
         Pair96 tb{0ull, 0u};
         if (__builtin_expect(tie_run, 0)) {
             // ---- the chunk that holds the need2-th entry of the run: thread t
@@ -1313,9 +1334,6 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
             if (!ok) { T = 0; path = 0; }
         } else if (!g.all_members) {
             // ---- exact threshold inside the deciding bin --------------------
-            auto each_b = [&](auto &&f) {
-                for (u32 p = tid; p < n_bd; p += kFinThreads) f(bk[p], bi[p]);
-            };
             tb = block_select96(each_b, need2, (64 - (int)bd_bits) / 8, h, scratch, &ok);
         }
         if (ok) {
@@ -1343,13 +1361,11 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
             };
             u32 my_gt = 0;
             if (__builtin_expect(lists, 1)) {
-                for (u32 p = tid; p < n_bd; p += kFinThreads) {
-                    const u64 hi = bk[p];
-                    const u32 idx = bi[p];
+                each_b([&](u64 hi, u32 idx) {
                     if (hi < tb.hi) ++my_gt;
                     if (pair_le(hi, idx, tb))
                         join(idx, [&] { atomicAdd(&win_cnt[idx / g.C], 1u); atomicAdd(&sure_extra, 1u); });
-                }
+                });
             } else {
                 // the run's members: its entries up to index I*, all in chunks 0 .. run_chunk.
                 // They may be many per chunk: certain winners are counted per chunk in LDS
@@ -1388,16 +1404,35 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
             if (g.take_all) {
                 have_k = true;
             } else if (n_mm <= m_cap && c_klo < g.k && g.k - c_klo <= n_mm) {
+                // (in LDS a thread's entries, four at most, stay in registers over the rounds)
+                constexpr u32 kM = kAllLds ? kStageM / kFinThreads : 1u;
+                u64 rm_k[kM];
+                u32 rm_i[kM];
+                if (kAllLds) {
+#pragma unroll
+                    for (u32 q = 0; q < kM; ++q) {
+                        const u32 p = q * kFinThreads + tid;
+                        rm_k[q] = p < n_mm ? mk[p] : 0ull;
+                        rm_i[q] = p < n_mm ? mi[p] : 0u;
+                    }
+                }
                 auto each_m = [&](auto &&f) {
-                    for (u32 p = tid; p < n_mm; p += kFinThreads) f(mk[p], mi[p]);
+                    if (kAllLds) {
+#pragma unroll
+                        for (u32 q = 0; q < kM; ++q)
+                            if (q * kFinThreads + tid < n_mm) f(rm_k[q], rm_i[q]);
+                    } else {
+                        for (u32 p = tid; p < n_mm; p += kFinThreads) f(mk[p], mi[p]);
+                    }
                 };
                 const Pair96 kb = block_select96(each_m, g.k - c_klo, 0, h, scratch, &ok);
                 if (ok) {
                     have_k = true;
                     K_star = (kb.hi >> g.k_nlz) + g.K_lo;
                     J_star = kb.lo;
-                    for (u32 p = tid; p < n_mm; p += kFinThreads)
-                        if (pair_le(mk[p], mi[p], kb)) atomicAdd(&win_cnt[mi[p] / g.C], 1u);
+                    each_m([&](u64 key, u32 idx) {
+                        if (pair_le(key, idx, kb)) atomicAdd(&win_cnt[idx / g.C], 1u);
+                    });
                 }
             }
         }
