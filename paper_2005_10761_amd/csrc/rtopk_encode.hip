@@ -1048,7 +1048,7 @@ __device__ __forceinline__ bool pair_matches(u64 hi, u32 lo, u64 phi, u32 plo, i
 
 template <class ForEach>
 __device__ __forceinline__ Pair96 block_select96(ForEach &&for_each, u64 rank, int first_byte,
-                                                 u32 (*h)[256] /* 3 buffers */,
+                                                 u32 (*h)[256] /* 4 buffers */,
                                                  u64 *scratch /* 2 */, bool *ok)
 {
     u64 phi = 0;
@@ -1067,26 +1067,36 @@ __device__ __forceinline__ Pair96 block_select96(ForEach &&for_each, u64 rank, i
             if (pair_matches(hi, lo, phi, plo, j)) atomicAdd(&h[cur][pair_byte(hi, lo, j)], 1u);
         });
         lds_barrier();
-        // every wavefront: lane l owns bins 4l .. 4l+3
+        // the first wavefront walks the bins, lane l owning bins 4l .. 4l+3, and leaves
+        // the outcome in the fourth buffer for the others (sixteen wavefronts walking
+        // them side by side take twice as long as one walk and one more barrier)
         // (the strings number fewer than 2^32, so 32-bit counts do)
-        u32 c[4];
-        u32 mine = 0;
+        if (threadIdx.x < kWave) {
+            u32 c[4];
+            u32 mine = 0;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) { c[q] = h[cur][4 * lane + q]; mine += c[q]; }
-        const u32 inc = wave_inclusive_sum(mine);
-        u32 run = inc - mine;
-        const u64 owner = __ballot((u64)run < need && need <= (u64)inc);
-        if (owner == 0ull) { *ok = false; return Pair96{0, 0}; }
-        u32 bin = 0, in_bin = 0, before = 0;
+            for (int q = 0; q < 4; ++q) { c[q] = h[cur][4 * lane + q]; mine += c[q]; }
+            const u32 inc = wave_inclusive_sum(mine);
+            u32 run = inc - mine;
+            const bool mine_it = (u64)run < need && need <= (u64)inc;
+            const u64 owner = __ballot(mine_it);
+            if (owner == 0ull && lane == 0) h[3][3] = 0u;
+            if (mine_it) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            if ((u64)run < need && need <= (u64)run + c[q]) { bin = 4 * lane + q; before = run; in_bin = c[q]; }
-            run += c[q];
+                for (int q = 0; q < 4; ++q) {
+                    if ((u64)run < need && need <= (u64)run + c[q]) {
+                        h[3][0] = 4 * lane + q;
+                        h[3][1] = c[q];
+                        h[3][2] = run;
+                        h[3][3] = 1u;
+                    }
+                    run += c[q];
+                }
+            }
         }
-        const int src = __ffsll((unsigned long long)owner) - 1;
-        bin = (u32)__builtin_amdgcn_readlane((int)bin, src);
-        in_bin = (u32)__builtin_amdgcn_readlane((int)in_bin, src);
-        before = (u32)__builtin_amdgcn_readlane((int)before, src);
+        lds_barrier();
+        if (h[3][3] == 0u) { *ok = false; return Pair96{0, 0}; }
+        const u32 bin = h[3][0], in_bin = h[3][1], before = h[3][2];
         need -= before;
         if (j < 8) phi |= (u64)bin << (56 - 8 * j);
         else plo |= bin << (24 - 8 * (j - 8));
@@ -1126,7 +1136,7 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
            u32 *dm_idx, u64 *db_key, u32 *db_idx, u32 *__restrict__ chunk_base)
 {
     static_assert(kMaxWalkBlocks <= (u32)kFinThreads, "one thread per classify workgroup");
-    __shared__ u32 h[3][256];
+    __shared__ u32 h[4][256];
     __shared__ u32 scan32[kSlabs * kFinWaves + 1];
     __shared__ u64 scratch[2];
     __shared__ u64 st_b_key[kStageB];
