@@ -1021,9 +1021,10 @@ classify_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ s
 // workgroup in a way that does not change between calls). Returns the
 // rank-th smallest string (rank is 1-based). Bytes before first_byte are
 // known to be zero in every string. *ok is cleared when fewer than `rank`
-// strings exist. One barrier per byte: the 256-bin histogram rotates through
-// three buffers (the next one is cleared while the current one is filled)
-// and every wavefront repeats the walk over the bins for itself. The barriers
+// strings exist. Two barriers per byte: the 256-bin histogram rotates through
+// three buffers (the next one is cleared while the current one is filled),
+// the first wavefront walks the bins and leaves the outcome in a fourth
+// buffer for the others. The barriers
 // order LDS only; for_each may read global memory but must not depend on
 // global writes made by other threads since the last full barrier.
 // ---------------------------------------------------------------------------
