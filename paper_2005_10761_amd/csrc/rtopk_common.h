@@ -75,6 +75,22 @@ __device__ __forceinline__ u32 wave_inclusive_sum(u32 v)
     return x;
 }
 
+// largest value over the wavefront, in every lane: the same seven DPP steps
+// with max in place of +, 0 (what a missing source lane reads as) being neutral
+__device__ __forceinline__ u32 wave_max_dpp(u32 v)
+{
+    auto mx = [](u32 a, u32 b) { return a > b ? a : b; };
+    u32 x = v;
+    x = mx(x, dpp_or_zero<0x111, 0xF, 0xF>(v));
+    x = mx(x, dpp_or_zero<0x112, 0xF, 0xF>(v));
+    x = mx(x, dpp_or_zero<0x113, 0xF, 0xF>(v));
+    x = mx(x, dpp_or_zero<0x114, 0xF, 0xE>(x));
+    x = mx(x, dpp_or_zero<0x118, 0xF, 0xC>(x));
+    x = mx(x, dpp_or_zero<0x142, 0xA, 0xF>(x));
+    x = mx(x, dpp_or_zero<0x143, 0xC, 0xF>(x));
+    return (u32)__builtin_amdgcn_readlane((int)x, kWave - 1);
+}
+
 // sum over the wavefront, in every lane
 __device__ __forceinline__ u32 wave_sum(u32 v)
 {

@@ -313,41 +313,6 @@ __device__ __forceinline__ u32 block_sum(u32 v, u32 *lds /* >= waves words */)
     return total;
 }
 
-// Whole workgroup: walking NBINS = PER * blockDim.x bins (in LDS) from the
-// top, find for each of NRANKS ranks the bin b with #(bins above b) < need <=
-// #(bins >= b). Stores b and the population above it; stores nothing for a
-// rank that all bins together do not reach. The caller presets the outputs
-// and synchronises before reading them.
-template <int PER, int NRANKS>
-__device__ __forceinline__ void block_pick_desc(const u32 *hist, const u32 (&need)[NRANKS],
-                                                u32 *out_bin /* NRANKS */,
-                                                u32 *out_before /* NRANKS */, u32 *lds)
-{
-    const int nbins = PER * (int)blockDim.x;
-    const int first = (int)threadIdx.x * PER;      // position in walking order
-    u32 c[PER];
-    u32 mine = 0;
-#pragma unroll
-    for (int q = 0; q < PER; ++q) { c[q] = hist[nbins - 1 - (first + q)]; mine += c[q]; }
-    const u32 before = block_exclusive_sum(mine, lds);
-#pragma unroll
-    for (int k = 0; k < NRANKS; ++k) {
-        if (before < need[k] && need[k] <= before + mine) {
-            u32 run = before;
-            bool done = false;
-#pragma unroll
-            for (int q = 0; q < PER; ++q) {
-                if (!done && run + c[q] >= need[k]) {
-                    out_bin[k] = (u32)(nbins - 1 - (first + q));
-                    out_before[k] = run;
-                    done = true;
-                }
-                run += c[q];
-            }
-        }
-    }
-}
-
 // ---------------------------------------------------------------------------
 // sample: magnitudes of a = g + m at g.L locations, one per stratum of the
 // vector, at a hashed offset inside the stratum, four consecutive elements
@@ -413,6 +378,53 @@ sample_body(const float *__restrict__ grad, const float *__restrict__ residual, 
 // that holds the sample of rank np - 6 sd - 8 (fewer than r entries lie
 // above it).
 // ---------------------------------------------------------------------------
+// One wavefront: walking 4096 buckets (in LDS) downwards from the bucket
+// `top` (nothing lies above it), 256 buckets at a time, find for each of
+// NRANKS ranks the bucket b with #(buckets above b) < need <= #(buckets >= b).
+// Stores b and the population above it; stores nothing for a rank that all
+// buckets together do not reach. The samples that matter sit in the few
+// buckets under the largest one: one or two steps instead of a walk over all.
+template <int NRANKS>
+__device__ __forceinline__ void wave_pick_from_top(const u32 *hist, u32 top, const u32 (&need)[NRANKS],
+                                                   u32 *out_bin, u32 *out_before)
+{
+    const u32 lane = lane_id();
+    u32 above = 0;
+    bool pending[NRANKS];
+#pragma unroll
+    for (int k = 0; k < NRANKS; ++k) pending[k] = true;
+    for (int hi = (int)(top | 255u); hi >= 0; hi -= 256) {
+        u32 c[4];
+        u32 mine = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { c[q] = hist[hi - 4 * (int)lane - q]; mine += c[q]; }
+        const u32 inc = wave_inclusive_sum(mine);
+        const u32 before = above + inc - mine;
+        bool any = false;
+#pragma unroll
+        for (int k = 0; k < NRANKS; ++k) {
+            const bool here = pending[k] && before < need[k] && need[k] <= before + mine;
+            if (here) {
+                u32 run = before;
+                bool done = false;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if (!done && run + c[q] >= need[k]) {
+                        out_bin[k] = (u32)(hi - 4 * (int)lane - q);
+                        out_before[k] = run;
+                        done = true;
+                    }
+                    run += c[q];
+                }
+            }
+            if (__ballot(here) != 0ull) pending[k] = false;
+            any = any || pending[k];
+        }
+        if (!any) break;
+        above += (u32)__builtin_amdgcn_readlane((int)inc, kWave - 1);
+    }
+}
+
 __device__ __forceinline__ void
 estimate_body(const u32 *__restrict__ samples, Geom g, EncodeCtl *ctl)
 {
@@ -423,7 +435,7 @@ estimate_body(const u32 *__restrict__ samples, Geom g, EncodeCtl *ctl)
     __shared__ u32 h_max[4096];                           // buckets of the per-thread maxima
     __shared__ u32 h[4096];                               // buckets of the samples that matter
     __shared__ u32 scan_lds[kEstThreads / kWave + 1];
-    __shared__ u32 bin_s[3], before_s[3];
+    __shared__ u32 bin_s[3], before_s[3], top_s;
     const u32 tid = threadIdx.x;
     constexpr u32 kVecs = kSampleLoc / kEstThreads;       // 16-byte sample groups per thread
     const uint4 *s4 = reinterpret_cast<const uint4 *>(samples);
@@ -432,6 +444,7 @@ estimate_body(const u32 *__restrict__ samples, Geom g, EncodeCtl *ctl)
     for (u32 q = 0; q < kVecs; ++q) v[q] = s4[q * kEstThreads + tid];
     for (u32 b = tid; b < 4096u; b += kEstThreads) { h[b] = 0u; h_max[b] = 0u; }
     if (tid < 3u) { bin_s[tid] = 0u; before_s[tid] = 0u; }
+    if (tid == 0) top_s = 0u;
     auto smax = [](int a, int b) { return a > b ? a : b; };
     int gmax[kVecs];                                      // largest of each group, -1 if none
     int tmax = -1;
@@ -466,12 +479,19 @@ estimate_body(const u32 *__restrict__ samples, Geom g, EncodeCtl *ctl)
     // Only the top s_lo samples matter. At most s_lo - 1 threads hold a sample
     // above the s_lo-th largest one, so the s_lo-th largest of the per-thread
     // maxima is not above it: buckets below that maximum's bucket need no count.
+    // (the bucket of the largest sample of all is where every walk starts)
+    {
+        const u32 wmax = wave_max_dpp(tmax >= 0 ? (u32)tmax >> 19 : 0u);
+        if (lane_id() == 0 && wmax) atomicMax(&top_s, wmax);
+    }
     u32 cut_bucket = 0;
     if (s_lo < kEstThreads) {
         if (tmax >= 0) atomicAdd(&h_max[(u32)tmax >> 19], 1u);
         lds_barrier();
-        const u32 want_cut[1] = {s_lo};
-        block_pick_desc<4, 1>(h_max, want_cut, &bin_s[2], &before_s[2], scan_lds);
+        if (tid < kWave) {
+            const u32 want_cut[1] = {s_lo};
+            wave_pick_from_top<1>(h_max, top_s, want_cut, &bin_s[2], &before_s[2]);
+        }
         lds_barrier();
         cut_bucket = bin_s[2];                     // stays 0 when fewer than s_lo threads hold samples
     }
@@ -490,8 +510,10 @@ estimate_body(const u32 *__restrict__ samples, Geom g, EncodeCtl *ctl)
     nzero = wave_sum(nzero);
     if (lane_id() == 0 && nzero) atomicAdd(&h[0], nzero);
     __syncthreads();
-    const u32 want[2] = {s_lo, s_hi};
-    block_pick_desc<4, 2>(h, want, &bin_s[0], &before_s[0], scan_lds);
+    if (tid < kWave) {
+        const u32 want[2] = {s_lo, s_hi};
+        wave_pick_from_top<2>(h, top_s, want, &bin_s[0], &before_s[0]);
+    }
     __syncthreads();
     if (tid == 0) {
         u32 t_lo = lo_all ? 0u : (bin_s[0] << 19);
