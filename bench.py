@@ -48,7 +48,7 @@ METRIC = "rTop-k encode gradient GB/s and % of HBM peak at d=25.6M; aggregate GB
 # copy of known size in the same run; the summary and the commands are in
 # profiles/k_fused_cfg3_hbm_traffic.txt. Only valid for the default workload.
 SINGLE_KERNEL_TRAFFIC_BYTES = 309_655_484       # one vector per launch (--sequential)
-BATCH_KERNEL_TRAFFIC_BYTES = 2_476_118_402   # the default: 8 workers per launch
+BATCH_KERNEL_TRAFFIC_BYTES = 2_476_223_559   # the default: 8 workers per launch
 
 
 class HipEvents:
