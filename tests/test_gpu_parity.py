@@ -812,6 +812,49 @@ def test_seeded_random_sweep_of_sizes_and_value_patterns():
         assert u.same_floats(gw, ww) and u.same_floats(gv, wv), what
 
 
+def test_batch_with_members_on_different_paths():
+    """One batched call whose members take different paths: ordinary vectors
+    next to a frozen tensor's zeros, a ternary vector and a vector with two
+    neighbouring magnitudes crowding the deciding bin. Every member as alone."""
+    import torch
+    u = _u()
+    rt = u.rt
+    dev = u.DEV
+    d, r, k = 250_000, 20_000, 2_000
+    rng = np.random.default_rng(77)
+    one = np.float32(1.0)
+    two_mags = np.where(rng.random(d) < 0.5, one, np.nextafter(one, np.float32(2.0))).astype(np.float32)
+    gs = [Workload(3, d=d, r=r, k=k).gradient(0, 0),
+          np.zeros(d, np.float32),
+          rng.integers(-1, 2, d).astype(np.float32),
+          two_mags,
+          Workload(2, d=d, r=r, k=k).gradient(1, 3)]
+    want_path = [0, 4, 4, 1, 0]
+    n = len(gs)
+    ms = [np.zeros(d, np.float32) for _ in range(n)]
+    stride = rt.encode_workspace_bytes(d, r, k)
+    ws = torch.empty(n * stride, dtype=torch.uint8, device=dev)
+    ws.fill_(0x3C)
+    grads = [torch.from_numpy(g).to(dev) for g in gs]
+    resid = [torch.from_numpy(m).to(dev) for m in ms]
+    out_i = [torch.full((k,), -1, dtype=torch.int32, device=dev) for _ in range(n)]
+    out_v = [torch.full((k,), float("nan"), dtype=torch.float32, device=dev) for _ in range(n)]
+    seeds = [100 + i for i in range(n)]
+    for t in range(2):
+        rt.encode_batch(grads, resid, r, k, seeds, t, out_i, out_v, ws)
+        torch.cuda.synchronize()
+        for i in range(n):
+            st = rt.encode_stats(ws[i * stride:(i + 1) * stride])
+            assert st["error_flags"] == 0, (t, i, st)
+            if t == 0:
+                assert st["path"] == want_path[i], (i, st)
+            want = oracle.encode(gs[i], ms[i], r, k, seeds[i], t)
+            got = (out_i[i].cpu().numpy().view(np.uint32), out_v[i].cpu().numpy(),
+                   resid[i].cpu().numpy())
+            u.assert_encode_equal(got, want, f"step {t} member {i}")
+            ms[i] = want[2]
+
+
 # --------------------------------------------------------------------------
 # the whole step inside a captured HIP graph
 # --------------------------------------------------------------------------
