@@ -125,6 +125,57 @@ def test_long_run_of_equal_magnitudes_at_the_threshold():
     assert st["ties_taken"] == 1
 
 
+def test_seeded_sweep_of_tie_heavy_vectors():
+    """Eighty seeded cases of vectors that are mostly ties (a few levels, sparse,
+    quantised, constant with outliers, piecewise constant, signs of one or two
+    neighbouring magnitudes) with every kind of (r, k): all paths, bit-exact."""
+    rng = np.random.default_rng(20051076)
+    paths = set()
+    for case in range(80):
+        d = int(rng.choice([30_000, 65_536, 100_003, 262_144]))
+        kind = case % 6
+        if kind == 0:
+            nl = int(rng.integers(1, 7))
+            lv = rng.choice([0.0, 0.5, 1.0, -1.0, 2.0, 3.0, -0.25, 1e-30, 1e-40], nl, replace=False)
+            g = rng.choice(lv, d, p=rng.dirichlet(np.ones(nl) * 0.7))
+        elif kind == 1:
+            g = np.where(rng.random(d) < 10.0 ** rng.uniform(-4, -0.5), rng.standard_normal(d), 0.0)
+        elif kind == 2:
+            q = 10.0 ** rng.uniform(-0.5, 1.0)
+            g = np.round(rng.standard_normal(d) * q) / q
+        elif kind == 3:
+            g = np.full(d, rng.choice([0.0, 0.75, -3.0]))
+            sel = rng.random(d) < 10.0 ** rng.uniform(-5, -2)
+            g[sel] = rng.standard_normal(int(sel.sum())) * 10
+        elif kind == 4:
+            cuts = np.sort(rng.integers(0, d, int(rng.integers(2, 40))))
+            g = np.zeros(d)
+            for a, b in zip(np.r_[0, cuts], np.r_[cuts, d]):
+                g[a:b] = rng.choice([0.0, 1.0, -1.0, 0.5, 2.0])
+        else:
+            g = (rng.integers(0, 2, d) * 2 - 1) * rng.choice(
+                [1.0, 1.0 + 2.0 ** -23], d, p=[0.9, 0.1] if case % 2 else [1.0, 0.0])
+        g = g.astype(np.float32)
+        m = np.zeros(d, np.float32) if case % 3 else rng.choice([0.0, 0.5, -0.5], d).astype(np.float32)
+        mode = (case // 6) % 6
+        if mode == 0:
+            r = int(rng.integers(1, d + 1)); k = int(rng.integers(1, r + 1))
+        elif mode == 1:
+            r = max(1, d // 200); k = max(1, r // 5)
+        elif mode == 2:
+            r = int(rng.integers(1, d + 1)); k = r
+        elif mode == 3:
+            r = d - int(rng.integers(0, 3)); k = int(rng.integers(1, r + 1))
+        elif mode == 4:
+            r = int(rng.integers(1, 2000)); k = int(rng.integers(1, r + 1))
+        else:
+            r = max(1, d // 10); k = max(1, r // 10)
+        st = _check(g, m, r, k, int(rng.integers(0, 2 ** 63)), int(rng.integers(0, 2 ** 40)),
+                    what=f"case {case} d={d} kind={kind} mode={mode} r={r} k={k}")
+        paths.add(st["path"])
+    assert {0, 4} <= paths, paths
+
+
 def test_crowded_deciding_bin_with_two_magnitudes_takes_the_slow_selection():
     """Two neighbouring patterns share the deciding bin and fill it beyond the
     short list: no run of equal magnitudes, the exact selection over all
