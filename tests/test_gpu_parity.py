@@ -906,6 +906,37 @@ def test_batch_with_members_on_different_paths():
             ms[i] = want[2]
 
 
+def test_two_streams_with_their_own_workspaces_do_not_disturb_each_other():
+    """Calls on different streams share nothing but the library's per-device
+    launch width: with distinct workspaces, residuals and outputs they may
+    overlap freely (both streams at the default priority)."""
+    import torch
+    u = _u()
+    rt = u.rt
+    dev = u.DEV
+    d = 1_500_000
+    wl = Workload(3, d=d)
+    r, k = wl.r, wl.k
+    streams = [torch.cuda.Stream(device=dev), torch.cuda.Stream(device=dev)]
+    gs = [wl.gradient(w, 0) for w in range(2)]
+    ms = [np.zeros(d, np.float32) for _ in range(2)]
+    grads = [torch.from_numpy(g).to(dev) for g in gs]
+    resid = [torch.zeros(d, dtype=torch.float32, device=dev) for _ in range(2)]
+    ws = [torch.empty(rt.encode_workspace_bytes(d, r, k), dtype=torch.uint8, device=dev) for _ in range(2)]
+    oi = [torch.empty(k, dtype=torch.int32, device=dev) for _ in range(2)]
+    ov = [torch.empty(k, dtype=torch.float32, device=dev) for _ in range(2)]
+    torch.cuda.synchronize()
+    for t in range(3):
+        for w in range(2):                                   # enqueue both before either finishes
+            rt.encode(grads[w], resid[w], r, k, 42 + w, t, oi[w], ov[w], ws[w], stream=streams[w])
+        torch.cuda.synchronize()
+        for w in range(2):
+            want = oracle.encode(gs[w], ms[w], r, k, 42 + w, t)
+            got = (oi[w].cpu().numpy().view(np.uint32), ov[w].cpu().numpy(), resid[w].cpu().numpy())
+            u.assert_encode_equal(got, want, f"step {t} stream {w}")
+            ms[w] = want[2]
+
+
 # --------------------------------------------------------------------------
 # the whole step inside a captured HIP graph
 # --------------------------------------------------------------------------
