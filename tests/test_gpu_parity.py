@@ -937,6 +937,43 @@ def test_two_streams_with_their_own_workspaces_do_not_disturb_each_other():
             ms[w] = want[2]
 
 
+def test_test_hooks_belong_to_the_calling_host_thread():
+    """rtopk_force_next_encode (like rtopk_trace_next_encode) is remembered per
+    host thread: a request made on one thread must not reach another thread's
+    call, and is still there for the first thread's own next call."""
+    import threading
+    import paper_2005_10761_amd as rt
+    u = _u()
+    d = 60_000
+    wl = Workload(2, d=d)
+    g = wl.gradient(0, 0)
+    m = np.zeros(d, np.float32)
+    want = oracle.encode(g, m, wl.r, wl.k, 9, 1)
+    asked, other_done = threading.Event(), threading.Event()
+    seen = {}
+
+    def first():
+        rt.force_next_encode(rt.FORCE_ESTIMATE_MISS)
+        asked.set()
+        other_done.wait(60)
+        seen["first"] = u.gpu_encode_once(g, m, wl.r, wl.k, 9, 1)
+
+    def second():
+        asked.wait(60)
+        seen["second"] = u.gpu_encode_once(g, m, wl.r, wl.k, 9, 1)
+        other_done.set()
+
+    ts = [threading.Thread(target=first), threading.Thread(target=second)]
+    for t in ts:
+        t.start()
+    for t in ts:
+        t.join(120)
+    assert set(seen) == {"first", "second"}
+    u.assert_encode_equal(seen["second"], want, "other thread")
+    u.assert_encode_equal(seen["first"], want, "requesting thread")
+    assert seen["second"][3]["path"] == 0 and seen["first"][3]["path"] & 2, (seen["second"][3], seen["first"][3])
+
+
 # --------------------------------------------------------------------------
 # the whole step inside a captured HIP graph
 # --------------------------------------------------------------------------
