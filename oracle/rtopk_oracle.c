@@ -27,8 +27,8 @@
  *   - Magnitude order is the order of the 31 low bits of the binary32 pattern
  *     (identical to |x| order for finite values; +0 and -0 tie).
  *   - Among equal magnitudes the lower index comes first in the permutation.
- *   - "Uniformly at random chosen" k-subset U of the top-r set: every member
- *     i of the top-r set gets the 64-bit key
+ *   - The k-subset U of the top-r set, which Definition 3 draws uniformly
+ *     among all k-subsets: every member i of the top-r set gets the 64-bit key
  *         K(i) = Philox4x32-10(counter = (i, 0, step_lo, step_hi),
  *                              key     = (seed_lo, seed_hi)),
  *         K = (out0 << 32) | out1,
@@ -181,17 +181,19 @@ int rtopk_oracle_encode(const float *grad, float *residual,
         return ORACLE_ENOMEM;
     }
 
-    /* g <- g + m */
+    /* error compensation (Algorithm 1, node loop): the memory is added to the
+       fresh gradient, one rounded binary32 addition per coordinate */
     for (uint64_t i = 0; i < d; ++i) {
         volatile float s = grad[i] + residual[i];
         acc[i] = s;
     }
 
-    /* I <- indices of the r largest-magnitude components */
+    /* Definition 1: the top-r set, by a full sort */
     rc = rtopk_oracle_top_r(acc, d, r, top);
     if (rc) { free(acc); free(ghat); free(top); free(keyed); return rc; }
 
-    /* I <- a uniformly random k-subset of I: the k smallest (key, index) */
+    /* Definition 3: k of those r, the ones whose (key, index) is smallest;
+       the message lists them by ascending index */
     for (uint64_t j = 0; j < r; ++j) {
         keyed[j].idx = top[j];
         keyed[j].key = rtopk_oracle_key64(seed, step, top[j]);
@@ -200,13 +202,14 @@ int rtopk_oracle_encode(const float *grad, float *residual,
     for (uint64_t j = 0; j < k; ++j) out_idx[j] = keyed[j].idx;
     qsort(out_idx, (size_t)k, sizeof *out_idx, by_u32_asc);
 
-    /* ghat <- g with the indices not in I set to zero */
+    /* the sparsified vector: a on U, zero elsewhere */
     for (uint64_t j = 0; j < k; ++j) {
         ghat[out_idx[j]] = acc[out_idx[j]];
         out_val[j] = acc[out_idx[j]];
     }
 
-    /* m <- g - ghat */
+    /* the new memory is what was not sent: one rounded binary32 subtraction
+       per coordinate */
     for (uint64_t i = 0; i < d; ++i) {
         volatile float e = acc[i] - ghat[i];
         residual[i] = e;
@@ -270,7 +273,9 @@ int rtopk_oracle_aggregate_f32(const uint32_t *idx, const float *val,
 
 /*
  * Master step of Algorithm 1 with the weight update folded in:
- *     omega_out = omega_in - eta * scale * (1/n) * sum_i ghat_i.
+ *     omega_out = omega_in - eta * scale * (1/n) * sum_i ghat_i
+ * for EVERY coordinate, exactly as the algorithm's master lines read: a
+ * coordinate nobody sent has ghat = 0 and goes through the same subtraction.
  * Sum in binary64 in worker order, everything else in binary64, one rounding
  * to binary32 at the end. omega_in and omega_out may be the same array.
  */
@@ -292,10 +297,6 @@ int rtopk_oracle_aggregate_update(const uint32_t *idx, const float *val,
         }
     for (uint64_t i = 0; i < d; ++i) {
         const double ghat = acc[i] / (double)n;
-        /* a coordinate the average does not move is copied, not recomputed:
-           the same number for every finite weight, and not-a-number weights
-           keep their bit pattern */
-        if (ghat == 0.0) { omega_out[i] = omega_in[i]; continue; }
         omega_out[i] = (float)((double)omega_in[i] - eta * scale * ghat);
     }
     free(acc);
@@ -307,10 +308,12 @@ int rtopk_oracle_aggregate_update(const uint32_t *idx, const float *val,
  * exactly as rtopk_oracle_aggregate_f32 forms it (sum from +0 in worker
  * order, one division by (float)n), the step c = (float)eta * (float)scale
  * rounded once, and omega_out = fma(-c, average, omega_in) with the single
- * rounding of a fused multiply-add. A coordinate whose sum is zero keeps its
- * weight bit for bit: it is copied (fma(-c, 0, w) would give the same number
- * for every finite w, signed zeros included, but would quieten a signalling
- * not-a-number).
+ * rounding of a fused multiply-add. Reading taken for binary32 only (the
+ * binary64 form above is the algorithm's line as it stands): a coordinate
+ * whose AVERAGE is zero (nobody sent it, what was sent cancels, or the
+ * quotient by n underflows) keeps its weight bit for bit, it is copied. For
+ * finite c and w that is the number fma(-c, 0, w) gives, up to the sign of a
+ * zero weight; a signalling not-a-number stays signalling.
  */
 int rtopk_oracle_aggregate_update_f32(const uint32_t *idx, const float *val,
                                       uint32_t n, uint64_t k, uint64_t d,

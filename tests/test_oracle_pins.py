@@ -482,17 +482,101 @@ def test_aggregate_update_rejects_out_of_range_index_and_wrong_length():
         oracle.aggregate_update(np.array([1], np.uint32), one, 1, 4, 0.1, 1.0, np.zeros(3, np.float32))
 
 
-def test_aggregate_update_copies_coordinates_the_average_does_not_move():
-    # nobody sent coordinate 1 and the two entries at 2 cancel: both keep their
-    # bits, a signalling not-a-number and a negative zero included
+def test_aggregate_update_binary64_is_the_master_line_for_every_coordinate():
+    # Algorithm 1's master lines, omega - eta * ghat, are applied to every
+    # coordinate, also where ghat = 0: nobody sent coordinate 1 and the two
+    # entries at 2 cancel. A negative zero stays (-0 - (+0) = -0) with a
+    # positive step and becomes +0 with a negative one (-0 - (-0) = +0); a
+    # signalling not-a-number comes out quiet, as from any arithmetic operation.
     omega = np.array([1.0, 0.0, -0.0, 4.0], np.float32)
     omega.view(np.uint32)[1] = 0x7FA00001
     idx = np.array([0, 2, 2, 3], np.uint32)
     val = np.array([1.0, 2.5, -2.5, 2.0], np.float32)
-    for fn in (oracle.aggregate_update, oracle.aggregate_update_f32):
-        out = fn(idx, val, 2, 4, 0.5, 1.0, omega)
-        assert list(bits(out)) == [bits(np.float32(0.75)), 0x7FA00001, 0x80000000,
-                                   bits(np.float32(3.5))]
+    out = oracle.aggregate_update(idx, val, 2, 4, 0.5, 1.0, omega)
+    assert list(bits(out)) == [bits(np.float32(0.75)), 0x7FE00001, 0x80000000,
+                               bits(np.float32(3.5))]
+    out = oracle.aggregate_update(idx, val, 2, 4, -0.5, 1.0, omega)
+    assert list(bits(out)) == [bits(np.float32(1.25)), 0x7FE00001, 0x00000000,
+                               bits(np.float32(4.5))]
+
+
+def test_aggregate_update_f32_copies_coordinates_the_average_does_not_move():
+    # the binary32 reading: where the average is zero the weight keeps its
+    # bits, a signalling not-a-number and a negative zero included, whatever
+    # the sign of the step; nobody sent coordinate 1, the two entries at 2 cancel
+    omega = np.array([1.0, 0.0, -0.0, 4.0], np.float32)
+    omega.view(np.uint32)[1] = 0x7FA00001
+    idx = np.array([0, 2, 2, 3], np.uint32)
+    val = np.array([1.0, 2.5, -2.5, 2.0], np.float32)
+    out = oracle.aggregate_update_f32(idx, val, 2, 4, 0.5, 1.0, omega)
+    assert list(bits(out)) == [bits(np.float32(0.75)), 0x7FA00001, 0x80000000,
+                               bits(np.float32(3.5))]
+    out = oracle.aggregate_update_f32(idx, val, 2, 4, -0.5, 1.0, omega)
+    assert list(bits(out)) == [bits(np.float32(1.25)), 0x7FA00001, 0x80000000,
+                               bits(np.float32(4.5))]
+    # the test is on the AVERAGE: a sum of 2^-149 divided by 3 rounds to zero,
+    # so the weight is copied although something was sent for it
+    tiny = np.array([2.0 ** -149], np.float32)
+    w = np.array([0.0], np.float32)
+    w.view(np.uint32)[0] = 0x7FA00001
+    out = oracle.aggregate_update_f32(np.array([0, 0, 0], np.uint32),
+                                      np.array([tiny[0], 0.0, 0.0], np.float32), 3, 1, 1.0, 1.0, w)
+    assert int(bits(out)[0]) == 0x7FA00001
+    # ... while with n = 1 the same entry moves a weight: 0 + 2^-149
+    out = oracle.aggregate_update_f32(np.array([0], np.uint32), tiny, 1, 1, -1.0, 1.0,
+                                      np.zeros(1, np.float32))
+    assert int(bits(out)[0]) == 1
+
+
+# --------------------------------------------------------------------------
+# order of the binary32 additions: from +0, workers 0, 1, 2, ..., entries of
+# one message in position order
+# --------------------------------------------------------------------------
+def test_f32_sums_add_workers_in_order_from_zero():
+    # One coordinate sent by three workers: 2^24, 1, -2^24. In worker order
+    # fl(2^24 + 1) = 2^24 (the tie goes to even), then - 2^24 = 0: average 0.
+    # Backwards, fl(-2^24 + 1) = -(2^24 - 1) is exact, + 2^24 = 1: average 1/3.
+    # (1, 2^24, -2^24) in order also gives 0; (2^24, -2^24, 1) gives 1/3: so
+    # neither a reversed nor a rotated order passes all three cases.
+    big = np.float32(2.0 ** 24)
+    third = np.float32(1.0) / np.float32(3.0)
+    d = 5
+    idx = np.array([3, 3, 3], np.uint32)
+    cases = [((big, 1.0, -big), 0.0), ((1.0, big, -big), 0.0), ((big, -big, 1.0), third),
+             ((-big, 1.0, big), third)]
+    for vals, want in cases:
+        val = np.array(vals, np.float32)
+        out = oracle.aggregate_f32(idx, val, 3, d)
+        assert float(out[3]) == float(want), (vals, out[3])
+        assert np.all(bits(np.delete(out, 3)) == 0)
+        # binary64 holds every partial sum exactly: always 1/3, correctly rounded
+        assert float(oracle.aggregate(idx, val, 3, d)[3]) == float(np.float32(1.0 / 3.0))
+        # the weight step built on the same sum: omega = 1, eta = -1 adds the average
+        one = np.ones(d, np.float32)
+        upd = oracle.aggregate_update_f32(idx, val, 3, d, -1.0, 1.0, one)
+        assert float(upd[3]) == float(np.float32(1.0) + np.float32(want))
+        # ... and with momentum from rest (mu = 0): velocity = the average
+        w, v = oracle.aggregate_update_momentum_f32(idx, val, 3, d, -1.0, 1.0, 0.0, one,
+                                                    np.zeros(d, np.float32))
+        assert float(v[3]) == float(want) and float(w[3]) == float(np.float32(1.0) + np.float32(want))
+
+
+def test_f32_sums_add_the_entries_of_one_message_in_position_order():
+    # the same index three times inside ONE message (never produced by the
+    # encoder, but defined: it is added again), next to a second worker
+    big = np.float32(2.0 ** 24)
+    idx = np.array([2, 2, 2, 0, 1, 4], np.uint32)        # worker 0: 2, 2, 2; worker 1: 0, 1, 4
+    for vals, want in (((big, 1.0, -big), 0.0), ((-big, 1.0, big), 0.5)):
+        val = np.array(list(vals) + [8.0, 8.0, 8.0], np.float32)
+        out = oracle.aggregate_f32(idx, val, 2, 5)
+        assert [float(x) for x in out] == [4.0, 4.0, want, 0.0, 4.0]
+
+
+def test_f32_sum_starts_from_positive_zero():
+    # -0 sent by every worker: +0 + (-0) = +0, so the average is +0, not -0
+    idx = np.array([1, 1], np.uint32)
+    val = np.array([-0.0, -0.0], np.float32)
+    assert list(bits(oracle.aggregate_f32(idx, val, 2, 3))) == [0, 0, 0]
 
 
 # --------------------------------------------------------------------------
