@@ -151,7 +151,9 @@ int rtopk_aggregate(const uint32_t *idx, const float *val,
  * Arithmetic, all binary32: the sum and the division by n exactly as in
  * rtopk_aggregate; the step c = eta * scale rounded once; then one fused
  * multiply-add, omega[i] = fma(-c, average[i], omega[i]). A coordinate whose
- * sum is zero (nobody sent it, or what was sent cancels) keeps its bits.
+ * average is zero (nobody sent it, what was sent cancels, or the quotient by
+ * n underflows) is not written and keeps its bits; for finite c and omega[i]
+ * that is the number the formula gives, up to the sign of a zero weight.
  * Reproducible bit for bit; no atomics.
  *
  * idx, val, n, k, d   as for rtopk_aggregate; n <= 65535

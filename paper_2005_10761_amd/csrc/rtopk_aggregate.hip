@@ -312,7 +312,7 @@ k_tile_starts(const u32 *__restrict__ idx, u32 n, u64 k, u64 tiles, u32 *__restr
 
 // ---------------------------------------------------------------------------
 // update: one wavefront per tile. omega[i] = fma(neg_step, average[i],
-// omega[i]) wherever the sum of what the workers sent for i is not zero.
+// omega[i]) wherever the average of what the workers sent for i is not zero.
 // ---------------------------------------------------------------------------
 constexpr u32 kDenseTileEntries = 512;     // from here on the whole tile is read and written
 constexpr int kUpdateAhead = 16;           // workers whose entries are held in registers together
@@ -333,10 +333,10 @@ k_update(const u32 *__restrict__ idx, const float *__restrict__ val, u32 n, u64 
     const float rn = 1.0f / fn;
     bool cleared = false;
     u32 entries = 0;
-    auto step = [&](float sum, float w) {
-        const float avg = n_pow2 ? sum * rn : sum / fn;
-        return fmaf(neg_step, avg, w);
-    };
+    // the average of a coordinate from its sum; a weight moves only where the
+    // AVERAGE is not zero (a tiny sum may underflow in the division)
+    auto average = [&](float sum) { return n_pow2 ? sum * rn : sum / fn; };
+    auto step = [&](float avg, float w) { return fmaf(neg_step, avg, w); };
 
     // ---- few workers with at most 64 entries each in this tile (the usual
     //      case): every entry stays in a register of "its" lane. The weight at
@@ -402,8 +402,8 @@ k_update(const u32 *__restrict__ idx, const float *__restrict__ val, u32 n, u64 
 #pragma unroll
             for (int q = 0; q < kUpdateAhead; ++q) {
                 if ((u32)q < n && in[q]) {
-                    const float sum = atomicExch(&tile[ei[q] - tile_base], 0.0f);
-                    if (sum != 0.0f) omega[ei[q]] = step(sum, ew[q]);
+                    const float avg = average(atomicExch(&tile[ei[q] - tile_base], 0.0f));
+                    if (avg != 0.0f) omega[ei[q]] = step(avg, ew[q]);
                 }
             }
             return;
@@ -477,9 +477,12 @@ k_update(const u32 *__restrict__ idx, const float *__restrict__ val, u32 n, u64 
     if (!cleared) return;                               // nobody sent anything in this tile
 
     constexpr int kVecs = kAggTile / 4 / kWave;         // float4 per lane
-    float4 s4[kVecs];
+    float4 s4[kVecs];                                   // the averages of this lane's coordinates
 #pragma unroll
-    for (int q = 0; q < kVecs; ++q) s4[q] = reinterpret_cast<const float4 *>(tile)[q * kWave + lane];
+    for (int q = 0; q < kVecs; ++q) {
+        const float4 t4 = reinterpret_cast<const float4 *>(tile)[q * kWave + lane];
+        s4[q] = make_float4(average(t4.x), average(t4.y), average(t4.z), average(t4.w));
+    }
     if (entries >= kDenseTileEntries && ((uintptr_t)omega & 15u) == 0 &&
         tile_base + kAggTile <= d) {
         float4 *o4 = reinterpret_cast<float4 *>(omega + tile_base);

@@ -330,7 +330,7 @@ __device__ __forceinline__ u64 stratum_start(const Geom &g, u32 j)
 
 __device__ __forceinline__ void
 sample_body(const float *__restrict__ grad, const float *__restrict__ residual, Geom g,
-         u32 *__restrict__ zero_base, u32 zero_words, u32 *__restrict__ samples)
+         PhiloxSeed seed, u32 *__restrict__ zero_base, u32 zero_words, u32 *__restrict__ samples)
 {
     const u32 j = blockIdx.x * kSampleThreads + threadIdx.x;
     for (u32 i = j; i < zero_words; i += gridDim.x * kSampleThreads) zero_base[i] = 0u;
@@ -341,8 +341,15 @@ sample_body(const float *__restrict__ grad, const float *__restrict__ residual, 
         const u64 len = end - start;
         u64 p = start;
         if (len > 4) {
+            // The offset depends on the stratum AND on (seed, step): a vector whose
+            // layout happens to mislead one set of offsets (a period close to the
+            // stratum length) does not mislead the next step's or another worker's.
+            // Which elements are sampled never changes the result, only the path.
             u32 hsh = (j + 1u) * 0x9E3779B1u;
+            hsh ^= seed.seed_lo * 0x85EBCA77u + seed.step_lo * 0xC2B2AE3Du +
+                   (seed.seed_hi ^ seed.step_hi) * 0x27D4EB2Fu;
             hsh ^= hsh >> 15; hsh *= 0x85EBCA77u; hsh ^= hsh >> 13;
+            hsh *= 0xC2B2AE3Du; hsh ^= hsh >> 16;
             // offset in [0, len - 4], scaled from the hash instead of a remainder
             p += (u64)(((u64)hsh * (u64)(len - 3)) >> 32);
         }
@@ -1697,7 +1704,8 @@ struct Member {
 __global__ void __launch_bounds__(kSampleThreads) k_sample(Batch B, Geom g, EncodeLayout L)
 {
     const Member m(B);
-    sample_body(m.grad, m.residual, g, m.at<u32>(0), (u32)(L.zero_bytes / 4), m.at<u32>(L.samples));
+    sample_body(m.grad, m.residual, g, m.seed, m.at<u32>(0), (u32)(L.zero_bytes / 4),
+                m.at<u32>(L.samples));
 }
 
 __global__ void __launch_bounds__(kEstThreads) k_estimate(Batch B, Geom g, EncodeLayout L)

@@ -476,6 +476,67 @@ def test_update_random_messages(d, n, k, offset):
     _check_update(u, idx, val, n, d, eta, scale, omega, offset=offset)
 
 
+def test_master_sums_add_workers_in_order_from_zero():
+    """The cases that pin the order of the oracle's binary32 sums (2^24, 1 and
+    -2^24 for one coordinate: 0 in worker order, 1/3 backwards), through all
+    three master entry points; few workers and entries (the register path of
+    the fused update) and the same coordinate inside a crowded tile (its
+    scanning path)."""
+    u = _u()
+    big = np.float32(2.0 ** 24)
+    d = 6000
+    rng = np.random.default_rng(23)
+    for vals in ((big, 1.0, -big), (1.0, big, -big), (big, -big, 1.0), (-big, 1.0, big)):
+        for fill in (0, 300):                       # other entries of each worker in the same tile
+            rows = []
+            for w in range(3):
+                others = np.sort(rng.choice(np.arange(2100, 4000), fill, replace=False))
+                rows.append(np.sort(np.concatenate([[2077], others])))
+            idx = np.stack(rows).astype(np.uint32)
+            val = rng.standard_normal(idx.shape).astype(np.float32)
+            for w in range(3):
+                val[w, np.searchsorted(idx[w], 2077)] = vals[w]
+            want = oracle.aggregate_f32(idx, val, 3, d)
+            assert float(want[2077]) in (0.0, float(np.float32(1.0) / np.float32(3.0)))
+            out = u.gpu_aggregate(idx, val, 3, d)
+            assert np.array_equal(u.bits(out), u.bits(want)), (vals, fill)
+            omega = np.ones(d, np.float32)
+            got = u.gpu_aggregate_update(idx, val, 3, d, -1.0, 1.0, omega)
+            assert np.array_equal(u.bits(got), u.bits(oracle.aggregate_update_f32(idx, val, 3, d, -1.0, 1.0, omega)))
+            gw, gv = u.gpu_aggregate_update_momentum(idx, val, 3, d, -1.0, 1.0, 0.5, omega, omega)
+            ww, wv = oracle.aggregate_update_momentum_f32(idx, val, 3, d, -1.0, 1.0, 0.5, omega, omega)
+            assert np.array_equal(u.bits(gw), u.bits(ww)) and np.array_equal(u.bits(gv), u.bits(wv))
+
+
+def test_update_moves_a_weight_only_where_the_average_is_not_zero():
+    """A sum that is not zero but whose quotient by n underflows to zero leaves
+    the weight's bits alone (a signalling not-a-number stays signalling), on the
+    register path, on the scanning path (more than 64 entries of a worker in
+    the tile) and with more than 16 workers."""
+    u = _u()
+    tiny = np.float32(2.0 ** -149)
+    d = 5000
+    for n, fill in ((3, 0), (3, 200), (17, 0)):
+        rng = np.random.default_rng(n + fill)
+        rows = []
+        for w in range(n):
+            others = np.sort(rng.choice(np.arange(100, 2000), fill, replace=False))
+            rows.append(np.sort(np.concatenate([[7, 40], others])))
+        idx = np.stack(rows).astype(np.uint32)
+        val = rng.standard_normal(idx.shape).astype(np.float32)
+        val[:, 0] = 0.0
+        val[0, 0] = tiny                                   # coordinate 7: sum 2^-149, average 0
+        val[:, 1] = 0.0
+        val[n - 1, 1] = np.float32(2.0 ** -140)            # coordinate 40: a denormal average
+        omega = rng.standard_normal(d).astype(np.float32)
+        omega.view(np.uint32)[7] = 0x7FA00001
+        omega[40] = 0.0
+        want = oracle.aggregate_update_f32(idx, val, n, d, 1.0, 1.0, omega)
+        assert int(u.bits(want)[7]) == 0x7FA00001 and want[40] != omega[40]
+        got = u.gpu_aggregate_update(idx, val, n, d, 1.0, 1.0, omega)
+        assert np.array_equal(u.bits(got), u.bits(want)), (n, fill)
+
+
 def test_update_clustered_messages_leave_far_tiles_alone():
     # all entries inside two narrow ranges far apart; everything between them
     # and around them must come back bit for bit
