@@ -47,6 +47,7 @@ extern "C" {
 #define RTOPK_EINVAL (-1)     /* null pointer, or sizes outside 1 <= k <= r <= d < 2^32, n < 1, aliasing */
 #define RTOPK_EWORKSPACE (-2) /* workspace null, misaligned (256 bytes) or too small */
 #define RTOPK_EHIP (-3)       /* a HIP call or kernel launch failed */
+#define RTOPK_ETOOLARGE (-4)  /* sizes beyond the built-in scratch of rtopk_aggregate_update_static */
 
 /* Bytes of device workspace rtopk_encode needs for these sizes.
  * bytes: host pointer, written on success. */
@@ -172,6 +173,32 @@ int rtopk_aggregate_update(const uint32_t *idx, const float *val,
                            float eta, float scale,
                            float *omega,
                            void *workspace, uint64_t workspace_bytes, void *stream);
+
+/*
+ * rtopk_aggregate_update for callers that cannot allocate device memory and
+ * have no workspace to pass: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc. Same arguments, same kernels and
+ * the same results bit for bit as rtopk_aggregate_update, but the table of
+ * tile starts lives in a device array of RTOPK_STATIC_SCRATCH_BYTES that is
+ * part of the library (every GPU the library runs on holds it until the
+ * process ends). The call allocates nothing and calls no allocating routine.
+ *
+ * Limit: (ceil(d / 2048) + 1) * n * 4 bytes, rounded up to 256, must not
+ * exceed RTOPK_STATIC_SCRATCH_BYTES (16 MiB: d = 2^28 with up to 31 workers,
+ * d = 2^32 - 1 with one); beyond it the call returns RTOPK_ETOOLARGE and
+ * launches nothing.
+ * The first call on a device looks up the array's address (it may load the
+ * library's device code): make it once outside any stream capture.
+ * All calls on one GPU share the one array: two calls whose kernels may
+ * overlap (different streams, no ordering between them) race; calls on one
+ * stream, or ordered by events, are safe. Nothing in the array has to be
+ * cleared between calls: every word a call reads it has written itself.
+ */
+#define RTOPK_STATIC_SCRATCH_BYTES (16u << 20)
+int rtopk_aggregate_update_static(const uint32_t *idx, const float *val,
+                                  uint32_t n, uint64_t k, uint64_t d,
+                                  float eta, float scale,
+                                  float *omega, void *stream);
 
 /*
  * The master's update with momentum, the optimiser the experiments section

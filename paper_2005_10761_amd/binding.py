@@ -16,7 +16,7 @@ _LIB: Optional[ctypes.CDLL] = None
 EXPORTS = ("rtopk_encode_workspace_bytes", "rtopk_aggregate_workspace_bytes", "rtopk_encode",
            "rtopk_encode_batch",
            "rtopk_aggregate", "rtopk_aggregate_update", "rtopk_aggregate_update_workspace_bytes",
-           "rtopk_aggregate_update_momentum",
+           "rtopk_aggregate_update_momentum", "rtopk_aggregate_update_static",
            "rtopk_encode_stats", "rtopk_trace_next_encode",
            "rtopk_force_next_encode", "rtopk_strerror", "rtopk_version")
 
@@ -64,6 +64,9 @@ def load_library() -> ctypes.CDLL:
     L.rtopk_aggregate_update.argtypes = [vp, vp, u32, u64, u64, ctypes.c_float, ctypes.c_float,
                                          vp, vp, u64, vp]
     L.rtopk_aggregate_update.restype = ctypes.c_int
+    L.rtopk_aggregate_update_static.argtypes = [vp, vp, u32, u64, u64, ctypes.c_float,
+                                                ctypes.c_float, vp, vp]
+    L.rtopk_aggregate_update_static.restype = ctypes.c_int
     L.rtopk_aggregate_update_momentum.argtypes = [vp, vp, u32, u64, u64, ctypes.c_float,
                                                   ctypes.c_float, ctypes.c_float, vp, vp, vp]
     L.rtopk_aggregate_update_momentum.restype = ctypes.c_int
@@ -211,6 +214,25 @@ def aggregate_update(idx: torch.Tensor, val: torch.Tensor, n: int, k: int, eta: 
                                                _stream_handle(stream))
     if rc:
         raise RtopkError(rc, "rtopk_aggregate_update")
+
+
+STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def aggregate_update_static(idx: torch.Tensor, val: torch.Tensor, n: int, k: int, eta: float,
+                            scale: float, omega: torch.Tensor, stream=None) -> None:
+    """rtopk_aggregate_update_static: as :func:`aggregate_update`, with the
+    library's built-in scratch array in place of a workspace."""
+    _need(idx, torch.int32, "idx")
+    _need(val, torch.float32, "val")
+    _need(omega, torch.float32, "omega")
+    if idx.numel() < n * k or val.numel() < n * k:
+        raise ValueError("idx/val must hold n*k entries")
+    rc = load_library().rtopk_aggregate_update_static(_ptr(idx), _ptr(val), n, k, omega.numel(),
+                                                      eta, scale, _ptr(omega),
+                                                      _stream_handle(stream))
+    if rc:
+        raise RtopkError(rc, "rtopk_aggregate_update_static")
 
 
 def aggregate_update_momentum(idx: torch.Tensor, val: torch.Tensor, n: int, k: int, eta: float,

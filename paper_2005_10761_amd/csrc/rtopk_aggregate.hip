@@ -37,6 +37,8 @@
 #include "rtopk_common.h"
 #include "../../include/rtopk.h"
 
+#include <mutex>
+
 namespace rtopk {
 
 constexpr int kAggThreads = 256;
@@ -586,6 +588,21 @@ extern "C" int rtopk_aggregate_update_workspace_bytes(uint64_t d, uint32_t n, ui
     return RTOPK_OK;
 }
 
+// the two kernels of the fused update; `start` holds (tiles + 1) * n words
+static int launch_update(const uint32_t *idx, const float *val, uint32_t n, uint64_t k, uint64_t d,
+                         float eta, float scale, float *omega, u32 *start, hipStream_t stream)
+{
+    const u64 tiles = (d + kAggTile - 1) / kAggTile;
+    const dim3 sgrid((unsigned)((k + 1 + kStartThreads - 1) / kStartThreads), n);
+    k_tile_starts<<<sgrid, kStartThreads, 0, stream>>>(idx, n, k, tiles, start);
+    if (hipGetLastError() != hipSuccess) return RTOPK_EHIP;
+    volatile float step = eta * scale;                  // one binary32 rounding, then negated
+    const unsigned grid = (unsigned)((tiles + kAggWaves - 1) / kAggWaves);
+    k_update<<<grid, kAggThreads, 0, stream>>>(idx, val, n, k, d, tiles, start, -step, omega);
+    if (hipGetLastError() != hipSuccess) return RTOPK_EHIP;
+    return RTOPK_OK;
+}
+
 extern "C" int rtopk_aggregate_update(const uint32_t *idx, const float *val, uint32_t n,
                                       uint64_t k, uint64_t d, float eta, float scale,
                                       float *omega, void *workspace, uint64_t workspace_bytes,
@@ -597,17 +614,56 @@ extern "C" int rtopk_aggregate_update(const uint32_t *idx, const float *val, uin
     if (n > 65535u) return RTOPK_EINVAL;                // workers are a grid dimension
     if (!workspace || ((uintptr_t)workspace & 255u) || workspace_bytes < need)
         return RTOPK_EWORKSPACE;
-    hipStream_t stream = (hipStream_t)stream_v;
-    const u64 tiles = (d + kAggTile - 1) / kAggTile;
-    u32 *start = static_cast<u32 *>(workspace);
-    const dim3 sgrid((unsigned)((k + 1 + kStartThreads - 1) / kStartThreads), n);
-    k_tile_starts<<<sgrid, kStartThreads, 0, stream>>>(idx, n, k, tiles, start);
-    if (hipGetLastError() != hipSuccess) return RTOPK_EHIP;
-    volatile float step = eta * scale;                  // one binary32 rounding, then negated
-    const unsigned grid = (unsigned)((tiles + kAggWaves - 1) / kAggWaves);
-    k_update<<<grid, kAggThreads, 0, stream>>>(idx, val, n, k, d, tiles, start, -step, omega);
-    if (hipGetLastError() != hipSuccess) return RTOPK_EHIP;
+    return launch_update(idx, val, n, k, d, eta, scale, omega, static_cast<u32 *>(workspace),
+                         (hipStream_t)stream_v);
+}
+
+// ---------------------------------------------------------------------------
+// rtopk_aggregate_update_static: the same two kernels with the tile-start
+// table in a device array that is part of the library's code object, for
+// callers that can neither allocate nor pass a workspace. Every device the
+// library runs on holds its own copy of the array at its own address; the
+// address is looked up once per device, with that device current, and kept.
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[RTOPK_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxScratchDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxScratchDevices];      // device address of `scratch`, per device
+
+int static_scratch(void **out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxScratchDevices) return RTOPK_EHIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        // in host code the array's name is only a handle: the device address comes from here
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return RTOPK_EHIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
     return RTOPK_OK;
+}
+}  // namespace
+
+extern "C" int rtopk_aggregate_update_static(const uint32_t *idx, const float *val, uint32_t n,
+                                             uint64_t k, uint64_t d, float eta, float scale,
+                                             float *omega, void *stream_v)
+{
+    uint64_t need = 0;
+    if (!idx || !val || !omega || rtopk_aggregate_update_workspace_bytes(d, n, k, &need) != RTOPK_OK)
+        return RTOPK_EINVAL;
+    if (n > 65535u) return RTOPK_EINVAL;
+    if (need > (uint64_t)RTOPK_STATIC_SCRATCH_BYTES) return RTOPK_ETOOLARGE;
+    void *table = nullptr;
+    const int rc = static_scratch(&table);
+    if (rc) return rc;
+    // k_tile_starts writes every word of the table that k_update reads, so
+    // nothing of what the previous call left in the array has to be cleared
+    return launch_update(idx, val, n, k, d, eta, scale, omega, static_cast<u32 *>(table),
+                         (hipStream_t)stream_v);
 }
 
 extern "C" const char *rtopk_strerror(int code)
@@ -617,6 +673,7 @@ extern "C" const char *rtopk_strerror(int code)
     case RTOPK_EINVAL: return "invalid argument (null pointer, sizes outside 1 <= k <= r <= d < 2^32, n < 1, or grad overlaps residual)";
     case RTOPK_EWORKSPACE: return "workspace missing, not 256-byte aligned, or too small";
     case RTOPK_EHIP: return "a HIP call or kernel launch failed";
+    case RTOPK_ETOOLARGE: return "sizes exceed the library's built-in scratch array (rtopk_aggregate_update_static needs 4 bytes per worker and per 2048 coordinates within RTOPK_STATIC_SCRATCH_BYTES); use the entry point that takes a workspace";
     default: return "unknown rtopk error code";
     }
 }
