@@ -27,3 +27,13 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture
+def progress(capsys):
+    """A print that reaches the terminal while the test runs (output capture is
+    suspended for the line): long full-size tests report each finished step."""
+    def say(msg: str) -> None:
+        with capsys.disabled():
+            print(msg, flush=True)
+    return say
