@@ -2,30 +2,37 @@
 """Benchmark of the rTop-k hot path on one MI355X.
 
 One *step* is one pass of the whole hot path over one batch of synthetic
-input: the n workers' fresh d-element gradients go through the
-error-compensated rTop-k sparsifier (``rtopk_encode_batch``: one call, shared
-kernel launches, every worker computed exactly as by ``rtopk_encode``) and the
-master runs ``rtopk_aggregate`` on the n messages. The workload is the
+input: the n workers' d-element gradients go through the error-compensated
+rTop-k sparsifier (``rtopk_encode_batch``: one call, shared kernel launches,
+every worker computed exactly as by ``rtopk_encode``) and the master runs
+``rtopk_aggregate`` on the n messages. The headline workload is the
 ResNet-50-sized configuration (d = 25,557,032, r = 0.5% d, k = 0.1% d, n = 8
-workers) that the headline metric is quoted on. All gradients of the warm-up
-and timed steps are resident in HBM before the clock starts; everything runs
-on one stream. ``--sequential`` times n separate ``rtopk_encode`` calls per
-step instead; by default that variant runs once more after the timed region
-and is reported as ``per_call`` (the latency of a single call). Inside the timed
-region the stream carries, besides the work, only the two HIP events around the
-dominant kernel of every step; the split of a step into encode and aggregate
-time (``encode_ms_per_vector``, ``aggregate_ms_per_call``) comes from a second
-pass over the same steps with an event after each call.
+workers) that the metric is quoted on. All gradients are resident in HBM
+before any clock starts; everything runs on one stream; every step uses a
+step number that was not used before on its residuals.
+
+Order of the run (default flags):
+  warm-up      W steps
+  steady loop  ``--steady-steps`` further steps (at least 100 ms of device
+               time), timed as a whole and with the dominant kernel of every
+               step bracketed: the device is at its steady clocks afterwards,
+               and the line shows the kernel's mean over the first and the
+               last tenth of the loop
+  timed region EXACTLY K steps between two synchronisations -> ``value``
+  legs         (outside the timed region) the encode / aggregate split of a
+               step, one ``rtopk_encode`` call per worker (``per_call``), the
+               fused master updates, a bare streaming add over the same
+               buffers (what a read-read-write stream reaches on this memory
+               system), the other benchmark configurations (``configs``), and
+               the CPU oracle on a bounded sample (``cpu_baseline``)
 
 Prints ONE JSON line:
   value      = gradient bytes consumed per second over whole steps
                (n * 4d bytes per step / seconds per step), GB/s
   roofline   = the dominant kernel (fused residual add + candidate append):
                algorithmic bytes per launch (12 d per vector in the launch)
-               over its mean duration, measured with HIP events on the launch
-               stream, against the 8 TB/s HBM peak
-  cpu_baseline = the CPU oracle, one thread, timed on a bounded sample of the
-               same workload
+               over its mean duration in the timed region, measured with HIP
+               events on the launch stream, against the 8 TB/s HBM peak
 """
 from __future__ import annotations
 
@@ -33,6 +40,7 @@ import argparse
 import ctypes
 import json
 import os
+import re
 import sys
 import time
 
@@ -42,13 +50,24 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 METRIC = "rTop-k encode gradient GB/s and % of HBM peak at d=25.6M; aggregate GB/s"
+TRAFFIC_PROFILE = os.path.join("profiles", "k_fused_cfg3_hbm_traffic.txt")
 
-# HBM bytes per launch of the dominant kernel (k_fused at d = 25,557,032) from
-# two rocprofv3 --pmc runs, FETCH_SIZE then WRITE_SIZE, each scaled by a device
-# copy of known size in the same run; the summary and the commands are in
-# profiles/k_fused_cfg3_hbm_traffic.txt. Only valid for the default workload.
-SINGLE_KERNEL_TRAFFIC_BYTES = 309_655_484       # one vector per launch (--sequential)
-BATCH_KERNEL_TRAFFIC_BYTES = 2_476_223_559   # the default: 8 workers per launch
+
+def traffic_from_profile(d: int, vectors_per_launch: int):
+    """HBM bytes per launch of the dominant kernel as the tracked rocprofv3
+    counter summary states them (FETCH_SIZE and WRITE_SIZE runs, each scaled by
+    a device copy of known size), or None when there is no summary for this
+    vector length and launch shape. The summary's last lines are
+    ``traffic_bytes_per_launch: N  vectors_per_launch: V  d: D``."""
+    try:
+        text = open(os.path.join(ROOT, TRAFFIC_PROFILE)).read()
+    except OSError:
+        return None
+    for m in re.finditer(r"traffic_bytes_per_launch:\s*(\d+)\s+vectors_per_launch:\s*(\d+)\s+d:\s*(\d+)",
+                         text):
+        if int(m.group(2)) == vectors_per_launch and int(m.group(3)) == d:
+            return int(m.group(1))
+    return None
 
 
 class HipEvents:
@@ -70,6 +89,9 @@ class HipEvents:
         self.events.append(ev)
         return ev.value
 
+    def pair(self):
+        return (self.new(), self.new())
+
     def elapsed_ms(self, a: int, b: int) -> float:
         ms = ctypes.c_float()
         rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b)
@@ -81,6 +103,153 @@ class HipEvents:
         for ev in self.events:
             self.hip.hipEventDestroy(ev)
         self.events = []
+
+
+class Job:
+    """Device state of n simulated workers for sizes (d, r, k): residuals,
+    message buffers, workspace slices, the dense output; and the step."""
+
+    def __init__(self, rt, torch, dev, d, r, k, n, stream):
+        from workloads import philox_seed_for_worker
+        self.rt, self.torch, self.stream = rt, torch, stream
+        self.d, self.r, self.k, self.n = d, r, k, n
+        self.residual = [torch.zeros(d, dtype=torch.float32, device=dev) for _ in range(n)]
+        self.idx = torch.empty(n * k, dtype=torch.int32, device=dev)
+        self.val = torch.empty(n * k, dtype=torch.float32, device=dev)
+        self.out_i = [self.idx[w * k:(w + 1) * k] for w in range(n)]
+        self.out_v = [self.val[w * k:(w + 1) * k] for w in range(n)]
+        self.seeds = [philox_seed_for_worker(w) for w in range(n)]
+        self.out = torch.empty(d, dtype=torch.float32, device=dev)
+        self.ws_bytes = rt.encode_workspace_bytes(d, r, k)
+        self.ws = torch.empty(n * self.ws_bytes, dtype=torch.uint8, device=dev)
+        self.ws_of = [self.ws[w * self.ws_bytes:(w + 1) * self.ws_bytes] for w in range(n)]
+        self.next_step = 0                       # step numbers are never reused on these residuals
+
+    def step(self, grads, as_batch=True, trace=None, phase=None):
+        """The n workers' encodes (one batched call, or n calls) and the
+        master's average. ``trace``: (begin, end) HIP events around the dominant
+        kernel (a list of n such pairs or None entries for single calls);
+        ``phase``: three torch events recorded before, between and after the calls."""
+        rt, stream, n = self.rt, self.stream, self.n
+        step_no = self.next_step
+        self.next_step += 1
+        if phase is not None:
+            phase[0].record(stream)
+        if as_batch:
+            if trace is not None:
+                rt.trace_next_encode(rt.STAGES["fused"], *trace)
+            rt.encode_batch(grads, self.residual, self.r, self.k, self.seeds, step_no, self.out_i,
+                            self.out_v, self.ws, stream)
+        else:
+            for w in range(n):
+                if trace is not None and trace[w] is not None:
+                    rt.trace_next_encode(rt.STAGES["fused"], *trace[w])
+                rt.encode(grads[w], self.residual[w], self.r, self.k, self.seeds[w], step_no,
+                          self.out_i[w], self.out_v[w], self.ws_of[w], stream)
+        if phase is not None:
+            phase[1].record(stream)
+        rt.aggregate(self.idx, self.val, n, self.k, self.out, None, stream)
+        if phase is not None:
+            phase[2].record(stream)
+
+    def check_stats(self, what):
+        last = None
+        for w in range(self.n):
+            last = self.rt.encode_stats(self.ws_of[w], self.stream)
+            if last["error_flags"] != 0:
+                raise RuntimeError(f"{what}: encode of worker {w} reported error flags {last}")
+        return last
+
+
+def timed_loop(job, torch, ev, grad_sets, steps, as_batch=True, trace_all=True):
+    """``steps`` steps on job.stream between two events; returns (ms per step,
+    list of per-step durations of the dominant kernel in ms)."""
+    n = job.n
+    pairs = [ev.pair() if trace_all else None for _ in range(steps)]
+    t0 = torch.cuda.Event(enable_timing=True)
+    t1 = torch.cuda.Event(enable_timing=True)
+    t0.record(job.stream)
+    for s in range(steps):
+        tr = pairs[s]
+        if not as_batch and tr is not None:
+            # one launch per step is bracketed, a different worker every step
+            tr = [pairs[s] if w == s % n else None for w in range(n)]
+        job.step(grad_sets[s % len(grad_sets)], as_batch, trace=tr)
+    t1.record(job.stream)
+    torch.cuda.synchronize()
+    fused = [ev.elapsed_ms(*p) for p in pairs if p is not None]
+    return t0.elapsed_time(t1) / steps, fused
+
+
+def split_loop(job, torch, grad_sets, steps, as_batch=True):
+    """The same steps with an event after each call: (encode ms per vector,
+    aggregate ms per call, ms per step)."""
+    phase = [tuple(torch.cuda.Event(enable_timing=True) for _ in range(3)) for _ in range(steps)]
+    job.step(grad_sets[0], as_batch)
+    for s in range(steps):
+        job.step(grad_sets[s % len(grad_sets)], as_batch, phase=phase[s])
+    torch.cuda.synchronize()
+    enc = sum(p[0].elapsed_time(p[1]) for p in phase) / (steps * job.n)
+    agg = sum(p[1].elapsed_time(p[2]) for p in phase) / steps
+    whole = phase[0][0].elapsed_time(phase[-1][2]) / steps
+    return enc, agg, whole
+
+
+def mean(xs):
+    return sum(xs) / len(xs)
+
+
+def measure_config(rt, torch, dev, stream, ev, wl, r, k, n, grads, steps, warmup):
+    """One benchmark configuration other than the headline one: batched steps
+    over ONE resident gradient set (the same n gradients every step, on top of
+    the evolving residuals, fresh step numbers)."""
+    d = wl.d
+    job = Job(rt, torch, dev, d, r, k, n, stream)
+    for _ in range(warmup):
+        job.step(grads)
+    torch.cuda.synchronize()
+    ms_step, fused = timed_loop(job, torch, ev, [grads], steps)
+    enc, agg, _ = split_loop(job, torch, [grads], min(steps, 5))
+    st = job.check_stats(f"{wl.config.name} r={r} k={k}")
+    fused_ms = mean(fused)
+    res = {"d": d, "r": r, "k": k, "workers": n, "steps": steps,
+           "ms_per_step": round(ms_step, 4),
+           "value_GBps": round(n * 4.0 * d / (ms_step * 1e-3) / 1e9, 1),
+           "encode_us_per_vector": round(enc * 1e3, 2),
+           "encode_pct_hbm_peak_at_12d": round(100.0 * 12.0 * d / (enc * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2),
+           "k_fused_ms": round(fused_ms, 5),
+           "k_fused_frac": round(n * 12.0 * d / (fused_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+           "aggregate_us": round(agg * 1e3, 2),
+           "aggregate_GBps": round(4.0 * d / (agg * 1e-3) / 1e9, 1),
+           "path": st["path"], "candidates_per_vector": st["superset_size"]}
+    del job
+    torch.cuda.empty_cache()
+    return res
+
+
+def other_configs(rt, torch, dev, stream, ev, which, steps, warmup):
+    """Configurations 1, 2, 4 and the nine stress points (16 workers each)."""
+    from workloads import Workload
+    from workloads.gradients import STRESS_K_FRACS, STRESS_R_OVER_K
+    out = {}
+    for cfg in which:
+        wl = Workload(cfg)
+        n = wl.n_workers
+        grads = [torch.from_numpy(wl.gradient(w, 0)).to(dev) for w in range(n)]
+        if cfg != 5:
+            out[wl.config.name] = measure_config(rt, torch, dev, stream, ev, wl, wl.r, wl.k, n,
+                                                 grads, steps, warmup)
+        else:
+            points = {}
+            for num, den in STRESS_K_FRACS:
+                for ratio in STRESS_R_OVER_K:
+                    k = (wl.d * num + den - 1) // den
+                    points[f"k={100.0 * num / den:g}%d,r={ratio}k"] = measure_config(
+                        rt, torch, dev, stream, ev, wl, ratio * k, k, n, grads, steps, warmup)
+            out[wl.config.name] = points
+        del grads
+        torch.cuda.empty_cache()
+    return out
 
 
 def cpu_baseline(wl, n_sample: int):
@@ -132,20 +301,25 @@ def cpu_baseline(wl, n_sample: int):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=3, help="workload configuration (1-5; 6 = the federated update vector)")
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=3,
+                    help="workload configuration of the timed region (1-5; 6 = the federated update vector)")
     ap.add_argument("--workers", type=int, default=0, help="override the workload's worker count")
+    ap.add_argument("--steady-steps", type=int, default=240, metavar="S",
+                    help="steps of the steady loop that precedes the timed region (0 = none)")
+    ap.add_argument("--grad-sets", type=int, default=6, metavar="G",
+                    help="distinct gradient sets resident in HBM; step s uses set s mod G")
     ap.add_argument("--sequential", action="store_true",
                     help="the timed steps call rtopk_encode once per worker instead of "
                          "rtopk_encode_batch once per step")
-    ap.add_argument("--trace-stride", type=int, default=0, metavar="N",
-                    help="with --sequential: bracket every N-th launch of the dominant kernel "
-                         "with HIP events (default: the number of workers, i.e. one launch per "
-                         "step, a different worker each step; 1 = every launch). The two event "
-                         "records cost the stream a few microseconds per traced launch.")
     ap.add_argument("--no-per-call-leg", action="store_true",
                     help="skip the extra pass that times one rtopk_encode call per worker")
+    ap.add_argument("--configs", default="1,2,4,5",
+                    help="other benchmark configurations to measure after the timed region "
+                         "(comma separated; 5 = the nine stress points with 16 workers; "
+                         "'none' skips the leg)")
+    ap.add_argument("--configs-steps", type=int, default=8)
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
                     help="after the timed region, also run N plain device copies of d floats "
                          "(4d bytes read + 4d bytes written each): a kernel of known HBM "
@@ -158,10 +332,9 @@ def main() -> int:
               "collective exists, so --gpus must be 1", file=sys.stderr)
         return 2
 
-    import numpy as np
     import torch
     import paper_2005_10761_amd as rt
-    from workloads import Workload, philox_seed_for_worker
+    from workloads import Workload
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -172,128 +345,86 @@ def main() -> int:
     d, r, k = wl.d, wl.r, wl.k
     n = args.workers or wl.n_workers
     K, W = args.steps, args.warmup
-    total_steps = K + W
     batched = not args.sequential
 
-    # ---- inputs: every gradient of every step resident in HBM ------------
-    grads = [[torch.from_numpy(wl.gradient(w, t)).to(dev) for w in range(n)]
-             for t in range(total_steps)]
-    residual = [torch.zeros(d, dtype=torch.float32, device=dev) for _ in range(n)]
-    idx = torch.empty(n * k, dtype=torch.int32, device=dev)
-    val = torch.empty(n * k, dtype=torch.float32, device=dev)
-    out_i = [idx[w * k:(w + 1) * k] for w in range(n)]
-    out_v = [val[w * k:(w + 1) * k] for w in range(n)]
-    seeds = [philox_seed_for_worker(w) for w in range(n)]
-    out = torch.empty(d, dtype=torch.float32, device=dev)
-    ws_bytes = rt.encode_workspace_bytes(d, r, k)
-    ws = torch.empty(n * ws_bytes, dtype=torch.uint8, device=dev)   # one slice per worker
-    ws_of = [ws[w * ws_bytes:(w + 1) * ws_bytes] for w in range(n)]
+    # ---- inputs: G gradient sets resident in HBM, cycled ------------------
+    G = max(1, min(args.grad_sets, K + W + args.steady_steps))
+    grad_sets = [[torch.from_numpy(wl.gradient(w, t)).to(dev) for w in range(n)] for t in range(G)]
     stream = torch.cuda.Stream(device=dev)                           # default priority
+    job = Job(rt, torch, dev, d, r, k, n, stream)
+    ev = HipEvents()
     torch.cuda.synchronize()
-
-    def one_step(t: int, step_no: int, as_batch: bool, trace=None, phase=None):
-        """The n workers' encodes (one batched call, or n calls) and the
-        master's average, all on one stream."""
-        if phase is not None:
-            phase[0].record(stream)
-        if as_batch:
-            if trace is not None and trace[0] is not None:
-                rt.trace_next_encode(rt.STAGES["fused"], *trace[0])
-            rt.encode_batch(grads[t], residual, r, k, seeds, step_no, out_i, out_v, ws, stream)
-        else:
-            for w in range(n):
-                if trace is not None and trace[w] is not None:
-                    rt.trace_next_encode(rt.STAGES["fused"], *trace[w])
-                rt.encode(grads[t][w], residual[w], r, k, seeds[w], step_no, out_i[w], out_v[w],
-                          ws_of[w], stream)
-        if phase is not None:
-            phase[1].record(stream)
-        rt.aggregate(idx, val, n, k, out, None, stream)
-        if phase is not None:
-            phase[2].record(stream)
-
-    def check_stats():
-        last = None
-        for w in range(n):
-            last = rt.encode_stats(ws_of[w], stream)
-            if last["error_flags"] != 0:
-                print(f"bench.py: encode of worker {w} reported error flags {last}",
-                      file=sys.stderr)
-                return None
-        return last
 
     for t in range(W):
-        one_step(t, t, batched)
+        job.step(grad_sets[t % G], batched)
     torch.cuda.synchronize()
 
-    # ---- timed region: K steps, events on the launch stream ----------------
-    ev = HipEvents()
-    if batched:
-        fused_pairs = [[(ev.new(), ev.new())] for _ in range(K)]
-        vectors_per_launch = n
-    else:
-        stride = args.trace_stride if args.trace_stride > 0 else n
-        offset = 0 if stride == 1 else 1             # n | stride would always pick worker 0
-        fused_pairs = [[(ev.new(), ev.new()) if (s_ * (n + offset) + w) % stride == 0 else None
-                        for w in range(n)] for s_ in range(K)]
-        vectors_per_launch = 1
-    t_begin = torch.cuda.Event(enable_timing=True)
-    t_end = torch.cuda.Event(enable_timing=True)
+    # ---- steady loop: long enough for the clocks to settle -----------------
+    steady = None
+    if args.steady_steps > 0:
+        S = args.steady_steps
+        ms_s, fused_s = timed_loop(job, torch, ev, grad_sets, S, batched)
+        tenth = max(1, S // 10)
+        steady = {"steps": S, "ms_per_step": round(ms_s, 4), "region_ms": round(ms_s * S, 1),
+                  "value": round(n * 4.0 * d / (ms_s * 1e-3) / 1e9, 2), "unit": "GB/s",
+                  "k_fused_ms_first_tenth": round(mean(fused_s[:tenth]), 5),
+                  "k_fused_ms_last_tenth": round(mean(fused_s[-tenth:]), 5),
+                  "k_fused_ms_mean": round(mean(fused_s), 5)}
+        job.check_stats("steady loop")
+
+    # ---- timed region: EXACTLY K steps between two synchronisations --------
     torch.cuda.synchronize()
     t_wall0 = time.perf_counter()
-    t_begin.record(stream)
-    for s_ in range(K):
-        one_step(W + s_, W + s_, batched, trace=fused_pairs[s_])
-    t_end.record(stream)
-    torch.cuda.synchronize()
+    ms_per_step, fused_ms = timed_loop(job, torch, ev, grad_sets, K, batched)
     t_wall1 = time.perf_counter()
-    total_ms = t_begin.elapsed_time(t_end)
-    fused_ms = [ev.elapsed_ms(*pair) for row in fused_pairs for pair in row if pair is not None]
-    ev.close()
-    stats = check_stats()
-    if stats is None:
-        return 4
+    stats = job.check_stats("timed region")
+    vectors_per_launch = n if batched else 1
 
-    # ---- outside the timed region: the same K steps again with an event after
-    #      the encode and after the aggregate of every step, for the split of a
-    #      step into its two calls (three more event records per step cost the
-    #      stream ~2% and are kept out of the timed region); fresh step numbers,
-    #      see below ----------------------------------------------------------
-    phase = [tuple(torch.cuda.Event(enable_timing=True) for _ in range(3)) for _ in range(K)]
-    one_step(W, 2 * total_steps + 1, batched)
-    for s_ in range(K):
-        one_step(W + s_, 2 * total_steps + 2 + s_, batched, phase=phase[s_])
-    torch.cuda.synchronize()
-    enc_ms_vector = sum(p[0].elapsed_time(p[1]) for p in phase) / (K * n)
-    agg_ms_call = sum(p[1].elapsed_time(p[2]) for p in phase) / K
-    if check_stats() is None:
-        return 4
+    # ---- outside the timed region: the split of a step into its two calls
+    #      (three more event records per step cost the stream ~2%) -----------
+    legs = min(K, 20)
+    enc_ms_vector, agg_ms_call, _ = split_loop(job, torch, grad_sets, legs, batched)
+    job.check_stats("split leg")
 
-    # ---- outside the timed region: the same K steps once more, one
-    #      rtopk_encode call per worker (the latency of a single call). The
-    #      gradients of step t again, on top of the residuals as they are now,
-    #      under step numbers not used before: sampling keys that already decided
-    #      what left these residuals would not be independent of the top-r set. ---
+    # ---- one rtopk_encode call per worker (the latency of a single call) ---
     per_call = None
     if batched and not args.no_per_call_leg:
-        edge = [tuple(torch.cuda.Event(enable_timing=True) for _ in range(3)) for _ in range(K)]
-        one_step(W, total_steps, False)
-        for s_ in range(K):
-            one_step(W + s_, total_steps + 1 + s_, False, phase=edge[s_])
-        torch.cuda.synchronize()
-        ms_call = sum(p[0].elapsed_time(p[1]) for p in edge) / (K * n)
-        ms_step = edge[0][0].elapsed_time(edge[-1][2]) / K
-        if check_stats() is None:
-            return 4
+        ms_call, _, ms_step = split_loop(job, torch, grad_sets, legs, False)
+        _, fused_single = timed_loop(job, torch, ev, grad_sets, legs, False)
+        job.check_stats("per-call leg")
         per_call = {"encode_ms_per_call": round(ms_call, 4),
                     "encode_gradient_GBps": round(4.0 * d / (ms_call * 1e-3) / 1e9, 2),
                     "encode_pct_hbm_peak_at_12d": round(100.0 * 12.0 * d / (ms_call * 1e-3) / 1e9
                                                         / HBM_PEAK_GBPS, 2),
+                    "k_fused_ms": round(mean(fused_single), 5),
+                    "k_fused_frac": round(12.0 * d / (mean(fused_single) * 1e-3) / 1e9
+                                          / HBM_PEAK_GBPS, 4),
                     "ms_per_step": round(ms_step, 4),
                     "value": round(n * 4.0 * d / (ms_step * 1e-3) / 1e9, 2), "unit": "GB/s"}
 
-    # ---- outside the timed region: the master's fused update on the last
-    #      step's messages (averaging and weight step in one call) ------------
+    # ---- the bare stream: residual += gradient over the same n buffer pairs,
+    #      same accesses and grid as the dominant kernel, nothing else --------
+    rounds = 10
+    for w in range(n):
+        rt.diag_stream_add(grad_sets[0][w], job.residual[w], stream)
+    c0, c1 = (torch.cuda.Event(enable_timing=True) for _ in range(2))
+    c0.record(stream)
+    for q in range(rounds):
+        for w in range(n):
+            rt.diag_stream_add(grad_sets[q % G][w], job.residual[w], stream)
+    c1.record(stream)
+    torch.cuda.synchronize()
+    add_ms = c0.elapsed_time(c1) / (rounds * n)
+    stream_add = {"what": "residual += gradient, 12 d bytes per launch, launches back to back "
+                          f"over the {n} workers' buffers",
+                  "ms_per_launch": round(add_ms, 5),
+                  "achieved": round(12.0 * d / (add_ms * 1e-3) / 1e9, 1), "unit": "GB/s",
+                  "frac": round(12.0 * d / (add_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+    for m in job.residual:
+        m.zero_()                                  # the sums above are no residuals
+
+    # ---- the master's fused updates on the last step's messages -------------
+    idx, val = job.idx, job.val
     upd_ws = torch.empty(rt.aggregate_update_workspace_bytes(d, n, k), dtype=torch.uint8,
                          device=dev)
     omegas = [torch.randn(d, dtype=torch.float32, device=dev) for _ in range(4)]
@@ -307,7 +438,6 @@ def main() -> int:
     upd[1].record(stream)
     torch.cuda.synchronize()
     upd_ms_call = upd[0].elapsed_time(upd[1]) / upd_calls
-    # ... and with momentum (a dense pass over weights and velocity)
     vels = [torch.zeros(d, dtype=torch.float32, device=dev) for _ in range(len(omegas))]
     for om, ve in zip(omegas, vels):
         rt.aggregate_update_momentum(idx, val, n, k, 0.1, r / k, 0.9, om, ve, stream)
@@ -321,20 +451,17 @@ def main() -> int:
     del omegas, vels
 
     if args.copy_calibration > 0:
-        src = grads[0][0]
+        src = grad_sets[0][0]
         for _ in range(args.copy_calibration):
-            out.copy_(src)
+            job.out.copy_(src)
         torch.cuda.synchronize()
 
-    ms_per_step = total_ms / K
-    fused_ms_avg = sum(fused_ms) / len(fused_ms)
+    fused_ms_avg = mean(fused_ms)
     value = n * 4.0 * d / (ms_per_step * 1e-3) / 1e9
     launch_bytes = vectors_per_launch * 12 * d
     achieved = launch_bytes / (fused_ms_avg * 1e-3) / 1e9
-    traffic = None
-    if args.config == 3:
-        traffic = (BATCH_KERNEL_TRAFFIC_BYTES if batched and n == wl.n_workers
-                   else None if batched else SINGLE_KERNEL_TRAFFIC_BYTES)
+    traffic = traffic_from_profile(d, vectors_per_launch)
+    ws_bytes = job.ws_bytes
     result = {
         "metric": METRIC,
         "value": round(value, 2),
@@ -351,7 +478,11 @@ def main() -> int:
         "config": {"workload": wl.config.name, "d": d, "r": r, "k": k, "workers": n,
                    "step": (f"1 x rtopk_encode_batch ({n} workers) + 1 x rtopk_aggregate"
                             if batched else f"{n} x rtopk_encode + 1 x rtopk_aggregate")
-                           + ", one stream"},
+                           + f", one stream; {G} gradient sets resident in HBM, step s uses set "
+                             f"s mod {G} on the evolving residuals under a fresh step number",
+                   "encode_workspace_bytes_per_vector": ws_bytes},
+        "timed_region_ms": round(ms_per_step * K, 2),
+        "steady": steady,
         "encode_gradient_GBps": round(4.0 * d / (enc_ms_vector * 1e-3) / 1e9, 2),
         "encode_ms_per_vector": round(enc_ms_vector, 4),
         "encode_pct_hbm_peak_at_12d": round(100.0 * 12.0 * d / (enc_ms_vector * 1e-3) / 1e9
@@ -374,14 +505,20 @@ def main() -> int:
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
             "traffic": traffic,
+            "traffic_source": TRAFFIC_PROFILE if traffic is not None else None,
             "bytes_per_launch": launch_bytes,
             "vectors_per_launch": vectors_per_launch,
             "avg_launch_ms": round(fused_ms_avg, 5),
             "launches": len(fused_ms),
+            "stream_add_calibration": stream_add,
         },
     }
-    del grads
+    del grad_sets, job
     torch.cuda.empty_cache()
+    if args.configs.strip().lower() not in ("", "none"):
+        which = [int(c) for c in args.configs.split(",") if int(c) != args.config]
+        result["configs"] = other_configs(rt, torch, dev, stream, ev, which, args.configs_steps, 2)
+    ev.close()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, max(1, min(args.cpu_sample, n)))
     print(json.dumps(result), flush=True)

@@ -19,15 +19,24 @@
  *     stream has drained.
  *   - The hot-path calls only launch kernels (what must start at zero is
  *     cleared by those kernels, not by memset nodes): they may be issued on a
- *     stream that is being captured into a HIP graph and replayed. The stats,
- *     trace and force hooks are for eager use.
+ *     stream that is being captured into a HIP graph and replayed. A replay
+ *     repeats the arguments it was captured with, the step number included:
+ *     rtopk_encode and rtopk_encode_batch in a graph draw the SAME random
+ *     subset on every replay, which under error feedback starves the members
+ *     with large keys. A loop that replays a graph uses
+ *     rtopk_encode_batch_device_step, which reads the step number from device
+ *     memory that the graph itself advances.
+ *   - Diagnostics (statistics of the last encode, event tracing, hooks that
+ *     force the exact fallback paths, a streaming calibration kernel) are not
+ *     part of this interface: they are declared in rtopk_diag.h.
  *   - Two calls may run concurrently only with distinct workspaces, residuals
  *     and outputs.
  *   - Return value: RTOPK_OK or a negative error code; rtopk_strerror() gives
  *     a static description. Argument checks are made on the host before
  *     anything is launched; a failed check launches nothing.
  *   - Results are a pure function of the argument values and buffer contents:
- *     they do not depend on grid size, stream or run. Against another
+ *     they do not depend on grid size, stream or run, nor on what the
+ *     workspace held. Against another
  *     implementation of the same arithmetic they agree bit for bit, with one
  *     exception IEEE 754 leaves open: when an addition meets two not-a-number
  *     operands with different payloads (two workers sending NaN for one
@@ -49,11 +58,13 @@ extern "C" {
 #define RTOPK_EHIP (-3)       /* a HIP call or kernel launch failed */
 #define RTOPK_ETOOLARGE (-4)  /* sizes beyond the built-in scratch of rtopk_aggregate_update_static */
 
-/* Bytes of device workspace rtopk_encode needs for these sizes.
- * bytes: host pointer, written on success. */
+/* Bytes of device workspace one rtopk_encode call needs for these sizes: the
+ * caller-owned scratch memory behind Algorithm 1's node-side step (nothing of
+ * it survives the call). bytes: host pointer, written on success. */
 int rtopk_encode_workspace_bytes(uint64_t d, uint64_t r, uint64_t k, uint64_t *bytes);
 
-/* Bytes of device workspace rtopk_aggregate needs for these sizes. */
+/* Bytes of device workspace rtopk_aggregate (Algorithm 1's master step) needs
+ * for these sizes; currently 0, the argument is kept for the interface. */
 int rtopk_aggregate_workspace_bytes(uint64_t d, uint32_t n, uint64_t k, uint64_t *bytes);
 
 /*
@@ -118,6 +129,26 @@ int rtopk_encode_batch(uint32_t n,
                        const uint64_t *seed, uint64_t step,
                        uint32_t *const *out_idx, float *const *out_val,
                        void *workspace, uint64_t workspace_bytes, void *stream);
+
+/*
+ * rtopk_encode_batch with the step number of Algorithm 1's loop read from
+ * device memory when the kernels run, not passed by value when they are
+ * enqueued: for a step captured once into a HIP graph and replayed every
+ * iteration, with a small kernel in the same graph (or any other work on the
+ * stream) advancing *step_device in between. Every replay then draws a fresh
+ * uniform subset (Definition 3), as a loop of rtopk_encode_batch calls with
+ * step = 0, 1, 2, ... does; the results are the same bit for bit.
+ *
+ * step_device   device, one uint64, 8-byte aligned; read by every kernel of
+ *               the call, so it must not change while the call's kernels run
+ * everything else as for rtopk_encode_batch (n = 1 serves a single vector)
+ */
+int rtopk_encode_batch_device_step(uint32_t n,
+                                   const float *const *grad, float *const *residual,
+                                   uint64_t d, uint64_t r, uint64_t k,
+                                   const uint64_t *seed, const uint64_t *step_device,
+                                   uint32_t *const *out_idx, float *const *out_val,
+                                   void *workspace, uint64_t workspace_bytes, void *stream);
 
 /*
  * Master step of Algorithm 1: out = (1/n) * sum_{w<n} message_w as a dense
@@ -223,63 +254,6 @@ int rtopk_aggregate_update_momentum(const uint32_t *idx, const float *val,
                                     uint32_t n, uint64_t k, uint64_t d,
                                     float eta, float scale, float mu,
                                     float *omega, float *velocity, void *stream);
-
-/*
- * Diagnostics of the most recent rtopk_encode that used `workspace`.
- * Synchronises `stream`, then copies a few counters to the host. Not part of
- * the hot path; tests and profiling use it.
- */
-typedef struct rtopk_encode_stats {
-    uint32_t error_flags;        /* 0 = clean; bit 1: a selection found no element of the requested
-                                    rank; bit 2: the winners did not add up to k (results invalid) */
-    uint32_t path;               /* 0: both cut points came from the short lists; bit 0: at least one
-                                    came from the slow selection over all candidates; bit 1: the
-                                    sampled estimate failed and the vector itself was walked;
-                                    bit 2: the threshold lies in a run of equal magnitudes too long
-                                    for the short list (zeros, signs, a few quantisation levels):
-                                    its last member was located from per-chunk counts */
-    uint32_t threshold_bits;     /* magnitude pattern of the r-th largest |a_i|. With r == d no
-                                    magnitude is looked at: threshold_bits and count_greater
-                                    are reported as 0 and ties_taken as r */
-    uint32_t boundary_list_size; /* candidates that shared the deciding histogram bin */
-    uint64_t count_greater;      /* #{i : mag(a_i) > threshold} */
-    uint64_t ties_taken;         /* r - count_greater, taken from the lowest indices */
-    uint64_t superset_size;      /* entries compacted before the exact selection */
-    uint64_t key_list_size;      /* members whose sampling key fell inside the a-priori window */
-} rtopk_encode_stats_t;
-
-int rtopk_encode_stats(const void *workspace, void *stream, rtopk_encode_stats_t *host_out);
-
-/*
- * Instrumentation for benchmarks: the NEXT rtopk_encode issued from the
- * calling host thread records `ev_begin` (a hipEvent_t) on its stream right
- * before the kernels of `stage` and `ev_end` right after them; the request is
- * then forgotten. Stage RTOPK_STAGE_ALL brackets the whole call. The events
- * stay owned by the caller. Passing stage 0 cancels a pending request.
- */
-#define RTOPK_STAGE_PREPARE 1   /* sample a = g + m, estimate the threshold range, clear counters */
-#define RTOPK_STAGE_FUSED 2     /* a = g + m, store, candidates + histogram */
-#define RTOPK_STAGE_CLASSIFY 3  /* certain members, key window, short lists */
-#define RTOPK_STAGE_FINALIZE 4  /* exact cut points, output offsets */
-#define RTOPK_STAGE_EMIT 5      /* message + residual write-back */
-#define RTOPK_STAGE_ALL 100
-int rtopk_trace_next_encode(int stage, void *ev_begin, void *ev_end);
-
-/*
- * Test hook: the NEXT rtopk_encode issued from the calling host thread behaves
- * as if one of its two statistical shortcuts had failed, so that the exact
- * fallbacks behind them can be exercised on ordinary inputs; the request is
- * then forgotten. The results must not change, only rtopk_encode_stats.path.
- *   RTOPK_FORCE_ESTIMATE_MISS    the sampled threshold estimate keeps no
- *                                candidates: the vector itself is walked
- *   RTOPK_FORCE_KEY_WINDOW_MISS  the a-priori window around the k-th smallest
- *                                sampling key is empty: the key cut comes from
- *                                a selection over all candidates
- * Passing 0 cancels a pending request.
- */
-#define RTOPK_FORCE_ESTIMATE_MISS 1u
-#define RTOPK_FORCE_KEY_WINDOW_MISS 2u
-int rtopk_force_next_encode(unsigned flags);
 
 const char *rtopk_strerror(int code);
 

@@ -8,11 +8,12 @@ of :mod:`paper_2005_10761_amd.binding` symbols fails loudly at first use.
 """
 from .binding import (RtopkError, aggregate, aggregate_update, aggregate_update_momentum, aggregate_update_static, STATIC_SCRATCH_BYTES,
                       aggregate_update_workspace_bytes,
-                      aggregate_workspace_bytes, encode, encode_batch,
+                      aggregate_workspace_bytes, encode, encode_batch, encode_batch_device_step,
+                      diag_stream_add,
                       encode_stats, encode_workspace_bytes, library_path, load_library,
                       strerror, trace_next_encode, version, STAGES, force_next_encode,
                       FORCE_ESTIMATE_MISS, FORCE_KEY_WINDOW_MISS)
 
-__all__ = ["RtopkError", "aggregate", "aggregate_update", "aggregate_update_momentum", "aggregate_update_static", "STATIC_SCRATCH_BYTES", "aggregate_update_workspace_bytes", "aggregate_workspace_bytes", "encode", "encode_batch", "encode_stats",
+__all__ = ["RtopkError", "aggregate", "aggregate_update", "aggregate_update_momentum", "aggregate_update_static", "STATIC_SCRATCH_BYTES", "aggregate_update_workspace_bytes", "aggregate_workspace_bytes", "encode", "encode_batch", "encode_batch_device_step", "diag_stream_add", "encode_stats",
            "encode_workspace_bytes", "library_path", "load_library", "strerror", "trace_next_encode", "version", "STAGES",
            "force_next_encode", "FORCE_ESTIMATE_MISS", "FORCE_KEY_WINDOW_MISS"]

@@ -13,12 +13,15 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "librtopk.so")
 _LIB: Optional[ctypes.CDLL] = None
 
+# what include/rtopk.h declares ...
 EXPORTS = ("rtopk_encode_workspace_bytes", "rtopk_aggregate_workspace_bytes", "rtopk_encode",
-           "rtopk_encode_batch",
+           "rtopk_encode_batch", "rtopk_encode_batch_device_step",
            "rtopk_aggregate", "rtopk_aggregate_update", "rtopk_aggregate_update_workspace_bytes",
            "rtopk_aggregate_update_momentum", "rtopk_aggregate_update_static",
-           "rtopk_encode_stats", "rtopk_trace_next_encode",
-           "rtopk_force_next_encode", "rtopk_strerror", "rtopk_version")
+           "rtopk_strerror", "rtopk_version")
+# ... and include/rtopk_diag.h
+DIAG_EXPORTS = ("rtopk_encode_stats", "rtopk_trace_next_encode", "rtopk_force_next_encode",
+                "rtopk_diag_stream_add", "rtopk_debug_checks")
 
 
 class RtopkError(RuntimeError):
@@ -57,6 +60,13 @@ def load_library() -> ctypes.CDLL:
     L.rtopk_encode.restype = ctypes.c_int
     L.rtopk_encode_batch.argtypes = [u32, vp, vp, u64, u64, u64, vp, u64, vp, vp, vp, u64, vp]
     L.rtopk_encode_batch.restype = ctypes.c_int
+    L.rtopk_encode_batch_device_step.argtypes = [u32, vp, vp, u64, u64, u64, vp, vp, vp, vp, vp,
+                                                 u64, vp]
+    L.rtopk_encode_batch_device_step.restype = ctypes.c_int
+    L.rtopk_diag_stream_add.argtypes = [vp, vp, u64, vp]
+    L.rtopk_diag_stream_add.restype = ctypes.c_int
+    L.rtopk_debug_checks.argtypes = []
+    L.rtopk_debug_checks.restype = ctypes.c_int
     L.rtopk_aggregate.argtypes = [vp, vp, u32, u64, u64, vp, vp, u64, vp]
     L.rtopk_aggregate.restype = ctypes.c_int
     L.rtopk_aggregate_update_workspace_bytes.argtypes = [u64, u32, u64, ctypes.POINTER(u64)]
@@ -172,6 +182,45 @@ def encode_batch(grads, residuals, r: int, k: int, seeds, step: int, out_idx, ou
         workspace.numel() * workspace.element_size(), _stream_handle(stream))
     if rc:
         raise RtopkError(rc, "rtopk_encode_batch")
+
+
+def encode_batch_device_step(grads, residuals, r: int, k: int, seeds, step_device: torch.Tensor,
+                             out_idx, out_val, workspace: torch.Tensor, stream=None) -> None:
+    """rtopk_encode_batch_device_step: as :func:`encode_batch`, with the step
+    number read from ``step_device`` (one int64 on the GPU) when the kernels run."""
+    n = len(grads)
+    if n < 1 or not (len(residuals) == len(seeds) == len(out_idx) == len(out_val) == n):
+        raise ValueError("grads, residuals, seeds, out_idx, out_val must have the same length >= 1")
+    _need(step_device, torch.int64, "step_device")
+    d = grads[0].numel()
+    for g, m, oi, ov in zip(grads, residuals, out_idx, out_val):
+        _need(g, torch.float32, "grad")
+        _need(m, torch.float32, "residual")
+        _need(oi, torch.int32, "out_idx")
+        _need(ov, torch.float32, "out_val")
+        if g.numel() != d or m.numel() != d or oi.numel() < k or ov.numel() < k:
+            raise ValueError("every member needs d gradient and residual elements and k outputs")
+    vp_arr = ctypes.c_void_p * n
+    seeds_arr = (ctypes.c_uint64 * n)(*[s & (2**64 - 1) for s in seeds])
+    rc = load_library().rtopk_encode_batch_device_step(
+        n, vp_arr(*[_ptr(t) for t in grads]), vp_arr(*[_ptr(t) for t in residuals]), d, r, k,
+        seeds_arr, _ptr(step_device), vp_arr(*[_ptr(t) for t in out_idx]),
+        vp_arr(*[_ptr(t) for t in out_val]), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if rc:
+        raise RtopkError(rc, "rtopk_encode_batch_device_step")
+
+
+def diag_stream_add(grad: torch.Tensor, residual: torch.Tensor, stream=None) -> None:
+    """rtopk_diag_stream_add: residual += grad, streamed as the encoder's dominant kernel streams."""
+    _need(grad, torch.float32, "grad")
+    _need(residual, torch.float32, "residual")
+    if grad.numel() != residual.numel():
+        raise ValueError("grad and residual must have the same length")
+    rc = load_library().rtopk_diag_stream_add(_ptr(grad), _ptr(residual), grad.numel(),
+                                              _stream_handle(stream))
+    if rc:
+        raise RtopkError(rc, "rtopk_diag_stream_add")
 
 
 def aggregate(idx: torch.Tensor, val: torch.Tensor, n: int, k: int, out: torch.Tensor,

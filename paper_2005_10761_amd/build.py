@@ -9,6 +9,9 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "librtopk.so")
+# the same sources with RTOPK_DEBUG_CHECKS: the master entry points verify their
+# preconditions (index range, ascending slices) on the device before they launch
+DEBUG_LIB_PATH = os.path.join(HERE, "librtopk_debug.so")
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950",
@@ -22,9 +25,10 @@ def sources() -> list:
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build(verbose: bool = False) -> str:
+def build(verbose: bool = False, debug: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB_PATH] + sources()
+    out_path = DEBUG_LIB_PATH if debug else LIB_PATH
+    cmd = [hipcc] + HIPCC_FLAGS + (["-DRTOPK_DEBUG_CHECKS"] if debug else []) + ["-o", out_path] + sources()
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -35,8 +39,8 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out, flush=True)
-    return LIB_PATH
+    return out_path
 
 
 if __name__ == "__main__":
-    print(build(verbose="-q" not in sys.argv))
+    print(build(verbose="-q" not in sys.argv, debug="--debug" in sys.argv))

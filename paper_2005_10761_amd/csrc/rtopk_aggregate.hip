@@ -522,9 +522,55 @@ k_update(const u32 *__restrict__ idx, const float *__restrict__ val, u32 n, u64 
     }
 }
 
+#ifdef RTOPK_DEBUG_CHECKS
+// ---------------------------------------------------------------------------
+// Debug build only: the preconditions of the master entry points (every index
+// below d, every worker's slice ascending) are checked on the device before
+// the call's own kernels are enqueued. The check synchronises the stream, so
+// it is kept out of the release build, where the conditions stay preconditions.
+// ---------------------------------------------------------------------------
+static __device__ u32 dbg_bad_entries;
+
+__global__ void k_check_messages(const u32 *__restrict__ idx, u32 n, u64 k, u64 d, u32 *bad)
+{
+    const u64 total = (u64)n * k;
+    u32 mine = 0;
+    for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (u64)gridDim.x * blockDim.x) {
+        const u32 v = idx[i];
+        if ((u64)v >= d) ++mine;
+        else if (i % k != 0 && idx[i - 1] > v) ++mine;
+    }
+    if (mine) atomicAdd(bad, mine);
+}
+#endif
+
 }  // namespace rtopk
 
 using namespace rtopk;
+
+// Release build: nothing. Debug build (RTOPK_DEBUG_CHECKS): RTOPK_EINVAL when a
+// message breaks a precondition of the master entry points.
+static int debug_check_messages(const uint32_t *idx, uint32_t n, uint64_t k, uint64_t d,
+                                hipStream_t stream)
+{
+#ifdef RTOPK_DEBUG_CHECKS
+    u32 *bad = nullptr;
+    u32 host_bad = 0;
+    if (hipGetSymbolAddress((void **)&bad, HIP_SYMBOL(dbg_bad_entries)) != hipSuccess ||
+        hipMemcpyAsync(bad, &host_bad, sizeof host_bad, hipMemcpyHostToDevice, stream) != hipSuccess)
+        return RTOPK_EHIP;
+    k_check_messages<<<1024, 256, 0, stream>>>(idx, n, k, d, bad);
+    if (hipGetLastError() != hipSuccess ||
+        hipMemcpyAsync(&host_bad, bad, sizeof host_bad, hipMemcpyDeviceToHost, stream) != hipSuccess ||
+        hipStreamSynchronize(stream) != hipSuccess)
+        return RTOPK_EHIP;
+    if (host_bad != 0) return RTOPK_EINVAL;
+#else
+    (void)idx; (void)n; (void)k; (void)d; (void)stream;
+#endif
+    return RTOPK_OK;
+}
 
 extern "C" int rtopk_aggregate_workspace_bytes(uint64_t d, uint32_t n, uint64_t k,
                                                uint64_t *bytes)
@@ -543,6 +589,7 @@ extern "C" int rtopk_aggregate(const uint32_t *idx, const float *val, uint32_t n
         return RTOPK_EINVAL;
     if (workspace && ((uintptr_t)workspace & 255u)) return RTOPK_EWORKSPACE;
     hipStream_t stream = (hipStream_t)stream_v;
+    if (const int rc = debug_check_messages(idx, n, k, d, stream)) return rc;
     const u64 tiles = (d + kAggTile - 1) / kAggTile;
     const u32 tiles_per_wave = (u32)((tiles + kAggMaxWaves - 1) / kAggMaxWaves);
     const u64 waves = (tiles + tiles_per_wave - 1) / tiles_per_wave;
@@ -565,6 +612,7 @@ extern "C" int rtopk_aggregate_update_momentum(const uint32_t *idx, const float 
         if (w0 < v0 + d * 4 && v0 < w0 + d * 4) return RTOPK_EINVAL;
     }
     hipStream_t stream = (hipStream_t)stream_v;
+    if (const int rc = debug_check_messages(idx, n, k, d, stream)) return rc;
     const u64 tiles = (d + kAggTile - 1) / kAggTile;
     const u32 tiles_per_wave = (u32)((tiles + kAggMaxWaves - 1) / kAggMaxWaves);
     const u64 waves = (tiles + tiles_per_wave - 1) / tiles_per_wave;
@@ -592,6 +640,7 @@ extern "C" int rtopk_aggregate_update_workspace_bytes(uint64_t d, uint32_t n, ui
 static int launch_update(const uint32_t *idx, const float *val, uint32_t n, uint64_t k, uint64_t d,
                          float eta, float scale, float *omega, u32 *start, hipStream_t stream)
 {
+    if (const int rc = debug_check_messages(idx, n, k, d, stream)) return rc;
     const u64 tiles = (d + kAggTile - 1) / kAggTile;
     const dim3 sgrid((unsigned)((k + 1 + kStartThreads - 1) / kStartThreads), n);
     k_tile_starts<<<sgrid, kStartThreads, 0, stream>>>(idx, n, k, tiles, start);
@@ -678,4 +727,14 @@ extern "C" const char *rtopk_strerror(int code)
     }
 }
 
-extern "C" int rtopk_version(void) { return 100; }
+extern "C" int rtopk_version(void) { return 200; }
+
+// 1 when the library was built with RTOPK_DEBUG_CHECKS, else 0
+extern "C" int rtopk_debug_checks(void)
+{
+#ifdef RTOPK_DEBUG_CHECKS
+    return 1;
+#else
+    return 0;
+#endif
+}

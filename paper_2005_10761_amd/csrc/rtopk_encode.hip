@@ -69,6 +69,7 @@
 // rows; global atomics only go to per-chunk counters.
 #include "rtopk_common.h"
 #include "../../include/rtopk.h"
+#include "../../include/rtopk_diag.h"
 
 #include <math.h>
 #include <mutex>
@@ -1675,6 +1676,7 @@ struct Batch {
     float *out_val[kMaxBatch];
     u32 seed_lo[kMaxBatch], seed_hi[kMaxBatch];
     u32 step_lo, step_hi;
+    const u64 *step_dev;        // when not null, the step number is read from here instead
     char *ws;
     u64 ws_stride;
 };
@@ -1694,7 +1696,13 @@ struct Member {
         residual = B.residual[i];
         out_idx = B.out_idx[i];
         out_val = B.out_val[i];
-        seed = PhiloxSeed{B.seed_lo[i], B.seed_hi[i], B.step_lo, B.step_hi};
+        u32 step_lo = B.step_lo, step_hi = B.step_hi;
+        if (B.step_dev) {
+            const u64 step = *B.step_dev;
+            step_lo = (u32)step;
+            step_hi = (u32)(step >> 32);
+        }
+        seed = PhiloxSeed{B.seed_lo[i], B.seed_hi[i], step_lo, step_hi};
         ws = B.ws + (u64)i * B.ws_stride;
     }
     template <class T>
@@ -1756,6 +1764,35 @@ __global__ void __launch_bounds__(kWalkThreads) k_emit(Batch B, Geom g, EncodeLa
     const Member m(B);
     emit_body(g, m.seed, m.at<EncodeCtl>(L.ctl), m.at<u32>(L.seg_count), m.at<uint2>(L.s_ent),
               m.at<u32>(L.chunk_base), m.out_idx, m.out_val, m.residual);
+}
+
+// ---------------------------------------------------------------------------
+// Calibration (diagnostics): a = g + m into the residual buffer and nothing
+// else, over the same chunks, with the same accesses and the same grid as
+// the fused kernel: the speed of the bare read-read-write stream.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(kFusedThreads)
+k_stream_add(const float *__restrict__ grad, float *__restrict__ residual, u64 d, u32 C, u32 W)
+{
+    const u32 wave_stride = gridDim.x * kFusedWaves;
+    for (u32 w = blockIdx.x * kFusedWaves + threadIdx.x / kWave; w < W; w += wave_stride) {
+        const u64 c0 = (u64)w * C;
+        const u64 c1 = c0 + C < d ? c0 + C : d;
+        u64 base = c0;
+        for (; base + 4 * kChunkQuantum <= c1; base += 4 * kChunkQuantum) {
+            const f32x4 *g4 = reinterpret_cast<const f32x4 *>(grad + base) + lane_id();
+            f32x4 *m4 = reinterpret_cast<f32x4 *>(residual + base) + lane_id();
+            f32x4 gv[4], mv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                gv[u] = __builtin_nontemporal_load(g4 + u * kWave);
+                mv[u] = __builtin_nontemporal_load(m4 + u * kWave);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) __builtin_nontemporal_store(gv[u] + mv[u], m4 + u * kWave);
+        }
+        for (u64 i = base + lane_id(); i < c1; i += kWave) residual[i] = grad[i] + residual[i];
+    }
 }
 
 }  // namespace rtopk
@@ -1882,10 +1919,11 @@ extern "C" int rtopk_trace_next_encode(int stage, void *ev_begin, void *ev_end)
         if (hipGetLastError() != hipSuccess) return RTOPK_EHIP; \
     } while (0)
 
-extern "C" int rtopk_encode_batch(uint32_t n, const float *const *grad, float *const *residual,
-                                  uint64_t d, uint64_t r, uint64_t k, const uint64_t *seed,
-                                  uint64_t step, uint32_t *const *out_idx, float *const *out_val,
-                                  void *workspace, uint64_t workspace_bytes, void *stream_v)
+static int encode_batch_impl(uint32_t n, const float *const *grad, float *const *residual,
+                             uint64_t d, uint64_t r, uint64_t k, const uint64_t *seed,
+                             uint64_t step, const uint64_t *step_dev, uint32_t *const *out_idx,
+                             float *const *out_val, void *workspace, uint64_t workspace_bytes,
+                             void *stream_v)
 {
     if (n < 1 || !grad || !residual || !seed || !out_idx || !out_val) return RTOPK_EINVAL;
     const int rc = check_sizes(d, r, k);
@@ -1935,6 +1973,7 @@ extern "C" int rtopk_encode_batch(uint32_t n, const float *const *grad, float *c
         }
         B.step_lo = (u32)step;
         B.step_hi = (u32)(step >> 32);
+        B.step_dev = step_dev;
         B.ws = (char *)workspace + (u64)first * L.total;
         B.ws_stride = L.total;
         const dim3 fg(fgrid, 1, nb);
@@ -1987,6 +2026,28 @@ extern "C" int rtopk_encode_batch(uint32_t n, const float *const *grad, float *c
     return RTOPK_OK;
 }
 
+extern "C" int rtopk_encode_batch(uint32_t n, const float *const *grad, float *const *residual,
+                                  uint64_t d, uint64_t r, uint64_t k, const uint64_t *seed,
+                                  uint64_t step, uint32_t *const *out_idx, float *const *out_val,
+                                  void *workspace, uint64_t workspace_bytes, void *stream_v)
+{
+    return encode_batch_impl(n, grad, residual, d, r, k, seed, step, nullptr, out_idx, out_val,
+                             workspace, workspace_bytes, stream_v);
+}
+
+extern "C" int rtopk_encode_batch_device_step(uint32_t n, const float *const *grad,
+                                              float *const *residual, uint64_t d, uint64_t r,
+                                              uint64_t k, const uint64_t *seed,
+                                              const uint64_t *step_device,
+                                              uint32_t *const *out_idx, float *const *out_val,
+                                              void *workspace, uint64_t workspace_bytes,
+                                              void *stream_v)
+{
+    if (!step_device || ((uintptr_t)step_device & 7u)) return RTOPK_EINVAL;
+    return encode_batch_impl(n, grad, residual, d, r, k, seed, 0, step_device, out_idx, out_val,
+                             workspace, workspace_bytes, stream_v);
+}
+
 extern "C" int rtopk_encode(const float *grad, float *residual, uint64_t d, uint64_t r,
                             uint64_t k, uint64_t seed, uint64_t step, uint32_t *out_idx,
                             float *out_val, void *workspace, uint64_t workspace_bytes,
@@ -1994,6 +2055,23 @@ extern "C" int rtopk_encode(const float *grad, float *residual, uint64_t d, uint
 {
     return rtopk_encode_batch(1, &grad, &residual, d, r, k, &seed, step, &out_idx, &out_val,
                               workspace, workspace_bytes, stream_v);
+}
+
+extern "C" int rtopk_diag_stream_add(const float *grad, float *residual, uint64_t d,
+                                     void *stream_v)
+{
+    if (!grad || !residual || d < 1 || d > 0xFFFFFFFFull) return RTOPK_EINVAL;
+    const uintptr_t g0 = (uintptr_t)grad, m0 = (uintptr_t)residual;
+    if (((g0 | m0) & 15u) || (g0 < m0 + d * 4 && m0 < g0 + d * 4)) return RTOPK_EINVAL;
+    const Geom g = make_geom(d, d, d);                     // the chunking only
+    unsigned grid_limit = 0;
+    const int rc = fused_grid_limit(&grid_limit);
+    if (rc) return rc;
+    unsigned fgrid = (g.W + kFusedWaves - 1) / kFusedWaves;
+    if (fgrid > grid_limit) fgrid = grid_limit;
+    k_stream_add<<<fgrid, kFusedThreads, 0, (hipStream_t)stream_v>>>(grad, residual, d, g.C, g.W);
+    RTOPK_LAUNCH_CHECK();
+    return RTOPK_OK;
 }
 
 extern "C" int rtopk_encode_stats(const void *workspace, void *stream_v,

@@ -1,4 +1,4 @@
-"""The C-ABI library loads and exports every symbol include/rtopk.h declares;
+"""The C-ABI library loads and exports every symbol include/*.h declares;
 host-side argument checks (no kernel is launched, no GPU needed)."""
 import ctypes
 import os
@@ -7,13 +7,13 @@ import re
 import pytest
 
 import paper_2005_10761_amd as rt
-from paper_2005_10761_amd.binding import EXPORTS
+from paper_2005_10761_amd.binding import DIAG_EXPORTS, EXPORTS
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "rtopk.h")).read()
+def _declared_symbols(header="rtopk.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return set(re.findall(r"\b(rtopk_[a-z_0-9]+)\s*\(", text))
 
@@ -22,8 +22,11 @@ def test_library_exports_every_declared_symbol():
     lib = rt.load_library()
     declared = _declared_symbols()
     assert declared == set(EXPORTS)
-    for name in declared:
+    diag = _declared_symbols("rtopk_diag.h")
+    assert diag == set(DIAG_EXPORTS) and not (diag & declared)
+    for name in declared | diag:
         assert getattr(lib, name) is not None
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["rtopk.h", "rtopk_diag.h"]
 
 
 def test_version_and_strerror():

@@ -1108,3 +1108,147 @@ def test_step_captured_in_a_hip_graph_replays_bit_exactly():
         torch.cuda.synchronize()
         graph.replay()
         check(f"replay {rep}")
+
+
+def test_training_loop_replayed_from_one_graph_with_the_step_on_the_device():
+    """Algorithm 1's loop as ONE captured graph replayed every iteration: the
+    batched encode reads the step number from device memory
+    (rtopk_encode_batch_device_step), the master's weight step uses the entry
+    point that needs no workspace, and the last node of the graph advances the
+    step. Residuals and weights carry over from replay to replay; only the
+    gradients are refreshed (eagerly) in between. Every iteration must match
+    the oracle run with step = 5, 6, 7, 8 on its own carried residuals: a
+    graph that replayed one fixed step number would draw the same subset again
+    and fail at the second iteration."""
+    import torch
+    import paper_2005_10761_amd as rt
+    u = _u()
+    dev = u.DEV
+    n, d, first_step, iters = 3, 150_001, 5, 4
+    wl = Workload(3, d=d)
+    r, k = wl.r, wl.k
+    seeds = [philox_seed_for_worker(w) for w in range(n)]
+    stride = rt.encode_workspace_bytes(d, r, k)
+    ws = torch.empty(n * stride, dtype=torch.uint8, device=dev)
+    g = [torch.zeros(d, dtype=torch.float32, device=dev) for _ in range(n)]
+    m = [torch.zeros(d, dtype=torch.float32, device=dev) for _ in range(n)]
+    idx = torch.empty(n * k, dtype=torch.int32, device=dev)
+    val = torch.empty(n * k, dtype=torch.float32, device=dev)
+    oi = [idx[i * k:(i + 1) * k] for i in range(n)]
+    ov = [val[i * k:(i + 1) * k] for i in range(n)]
+    omega0 = np.random.default_rng(7).standard_normal(d).astype(np.float32)
+    omega = torch.from_numpy(omega0).to(dev)
+    step_dev = torch.full((1,), first_step, dtype=torch.int64, device=dev)
+    eta, scale = 0.25, float(r) / float(k)
+
+    def one_iteration():
+        rt.encode_batch_device_step(g, m, r, k, seeds, step_dev, oi, ov, ws)
+        rt.aggregate_update_static(idx, val, n, k, eta, scale, omega)
+        step_dev.add_(1)
+
+    # first use of the library's built-in scratch array outside the capture
+    # (harmless values: a zero step leaves the weights as they are)
+    rt.aggregate_update_static(torch.zeros(n * k, dtype=torch.int32, device=dev),
+                               torch.zeros(n * k, dtype=torch.float32, device=dev), n, k, 0.0, 1.0,
+                               omega.clone())
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        one_iteration()
+    # the capture enqueued nothing: state is still the initial one
+    assert int(step_dev.item()) == first_step
+
+    ref_m = [np.zeros(d, np.float32) for _ in range(n)]
+    ref_w = omega0
+    for it in range(iters):
+        t = first_step + it
+        grads = [wl.gradient(w, t) for w in range(n)]
+        for w in range(n):
+            g[w].copy_(torch.from_numpy(grads[w]))            # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        msgs_i, msgs_v = [], []
+        for w in range(n):
+            wi, wv, ref_m[w] = oracle.encode(grads[w], ref_m[w], r, k, seeds[w], t)
+            got = (oi[w].cpu().numpy().view(np.uint32), ov[w].cpu().numpy(), m[w].cpu().numpy())
+            u.assert_encode_equal(got, (wi, wv, ref_m[w]), f"iteration {it} worker {w}")
+            msgs_i.append(wi)
+            msgs_v.append(wv)
+        ref_w = oracle.aggregate_update_f32(np.concatenate(msgs_i), np.concatenate(msgs_v), n, d,
+                                            eta, scale, ref_w)
+        assert np.array_equal(u.bits(omega.cpu().numpy()), u.bits(ref_w)), it
+        assert int(step_dev.item()) == t + 1
+    # the same call issued eagerly with a 64-bit step on the device equals the by-value entry point
+    big_step = 2 ** 40 + 3
+    step_dev.fill_(big_step)
+    m2 = [torch.from_numpy(x).to(dev) for x in ref_m]
+    rt.encode_batch_device_step(g, m2, r, k, seeds, step_dev, oi, ov, ws)
+    torch.cuda.synchronize()
+    for w in range(n):
+        wi, wv, wm = oracle.encode(grads[w], ref_m[w], r, k, seeds[w], big_step)
+        got = (oi[w].cpu().numpy().view(np.uint32), ov[w].cpu().numpy(), m2[w].cpu().numpy())
+        u.assert_encode_equal(got, (wi, wv, wm), f"64-bit device step, worker {w}")
+
+
+def test_debug_build_checks_the_preconditions_of_the_master_entry_points():
+    """The library built with RTOPK_DEBUG_CHECKS refuses a message with an index
+    at or beyond d, or a slice that does not ascend, with RTOPK_EINVAL and
+    writes nothing; a valid message gives the release build's bits."""
+    import ctypes
+    import os
+    import torch
+    import paper_2005_10761_amd as rt
+    from paper_2005_10761_amd import build as hip_build
+    u = _u()
+    assert rt.load_library().rtopk_debug_checks() == 0
+    assert os.path.exists(hip_build.DEBUG_LIB_PATH), "run __graft_entry__.build() first"
+    dbg = ctypes.CDLL(hip_build.DEBUG_LIB_PATH)
+    assert dbg.rtopk_debug_checks() == 1
+    vp, u32, u64, f32 = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_float
+    dbg.rtopk_aggregate.argtypes = [vp, vp, u32, u64, u64, vp, vp, u64, vp]
+    dbg.rtopk_aggregate_update_static.argtypes = [vp, vp, u32, u64, u64, f32, f32, vp, vp]
+    dbg.rtopk_aggregate_update_momentum.argtypes = [vp, vp, u32, u64, u64, f32, f32, f32, vp, vp, vp]
+    d, n, k = 10_000, 2, 4
+    rng = np.random.default_rng(5)
+    good = np.stack([np.sort(rng.choice(d, k, replace=False)) for _ in range(n)]).astype(np.uint32)
+    val = rng.standard_normal((n, k)).astype(np.float32)
+    past_end = good.copy()
+    past_end[1, k - 1] = d
+    unsorted = good.copy()
+    unsorted[0, 1], unsorted[0, 2] = good[0, 2], good[0, 1]
+    tv = torch.from_numpy(val.reshape(-1)).to(u.DEV)
+    omega = rng.standard_normal(d).astype(np.float32)
+    for name, idx, want_rc in (("good", good, 0), ("index == d", past_end, -1),
+                               ("descending pair", unsorted, -1)):
+        ti = torch.from_numpy(idx.reshape(-1).view(np.int32)).to(u.DEV)
+        out = torch.full((d,), 7.0, dtype=torch.float32, device=u.DEV)
+        tw = torch.from_numpy(omega).to(u.DEV)
+        tvel = torch.zeros(d, dtype=torch.float32, device=u.DEV)
+        rc = dbg.rtopk_aggregate(ti.data_ptr(), tv.data_ptr(), n, k, d, out.data_ptr(), None, 0, None)
+        rc2 = dbg.rtopk_aggregate_update_static(ti.data_ptr(), tv.data_ptr(), n, k, d, 0.5, 1.0,
+                                                tw.data_ptr(), None)
+        rc3 = dbg.rtopk_aggregate_update_momentum(ti.data_ptr(), tv.data_ptr(), n, k, d, 0.5, 1.0,
+                                                  0.0, tw.clone().data_ptr(), tvel.data_ptr(), None)
+        torch.cuda.synchronize()
+        assert (rc, rc2, rc3) == (want_rc,) * 3, (name, rc, rc2, rc3)
+        if want_rc == 0:
+            assert np.array_equal(u.bits(out.cpu().numpy()), u.bits(oracle.aggregate_f32(idx, val, n, d)))
+            assert np.array_equal(u.bits(tw.cpu().numpy()),
+                                  u.bits(oracle.aggregate_update_f32(idx, val, n, d, 0.5, 1.0, omega)))
+        else:
+            assert bool((out == 7.0).all()) and np.array_equal(u.bits(tw.cpu().numpy()), u.bits(omega))
+
+
+def test_streaming_calibration_kernel_adds_in_place():
+    import torch
+    import paper_2005_10761_amd as rt
+    u = _u()
+    rng = np.random.default_rng(1)
+    for d in (1, 255, 1024, 70_001, 3_000_017):
+        g = rng.standard_normal(d).astype(np.float32)
+        m = rng.standard_normal(d).astype(np.float32)
+        tg, tm = torch.from_numpy(g).to(u.DEV), torch.from_numpy(m).to(u.DEV)
+        rt.diag_stream_add(tg, tm)
+        torch.cuda.synchronize()
+        assert np.array_equal(u.bits(tm.cpu().numpy()), u.bits(g + m)), d
