@@ -92,11 +92,12 @@ int rtopk_aggregate_workspace_bytes(uint64_t d, uint32_t n, uint64_t k, uint64_t
  *            distinct `seed`s give independent workers
  * out_idx    device, [k] uint32, the set U in strictly ascending order
  * out_val    device, [k] binary32, out_val[j] = a[out_idx[j]]
- * workspace  device, 256-byte aligned, >= rtopk_encode_workspace_bytes(d,r,k)
- *            (about 8 bytes per element plus 40 MB: every chunk of the vector
- *            owns room for all its elements as candidates, of which only the
- *            kept ones are ever written); contents on entry are irrelevant,
- *            contents on return unspecified
+ * workspace  device, 256-byte aligned, >= rtopk_encode_workspace_bytes(d,r,k):
+ *            one byte per element (every chunk of the vector owns room for an
+ *            eighth of its elements as 8-byte candidates; a chunk that keeps
+ *            more is read from the residual buffer itself) plus about 10 MB
+ *            of histograms, lists and counters; contents on entry are
+ *            irrelevant, contents on return unspecified
  * stream     hipStream_t
  */
 int rtopk_encode(const float *grad, float *residual,

@@ -21,13 +21,17 @@ extern "C" {
  */
 typedef struct rtopk_encode_stats {
     uint32_t error_flags;        /* 0 = clean; bit 1: a selection found no element of the requested
-                                    rank; bit 2: the winners did not add up to k (results invalid) */
+                                    rank; bit 2: the winners did not add up to k; bit 3: a workgroup
+                                    of the many-workgroup selection gave up waiting for the others
+                                    (any bit set: results invalid) */
     uint32_t path;               /* 0: both cut points came from the short lists; bit 0: at least one
                                     came from the slow selection over all candidates; bit 1: the
                                     sampled estimate failed and the vector itself was walked;
                                     bit 2: the threshold lies in a run of equal magnitudes too long
                                     for the short list (zeros, signs, a few quantisation levels):
-                                    its last member was located from per-chunk counts */
+                                    its last member was located from per-chunk counts; bit 3: the
+                                    selection over all candidates ran on many workgroups (vectors
+                                    of 256 chunks or more) */
     uint32_t threshold_bits;     /* magnitude pattern of the r-th largest |a_i|. With r == d no
                                     magnitude is looked at: threshold_bits and count_greater
                                     are reported as 0 and ties_taken as r */

@@ -82,7 +82,7 @@ constexpr u32 kMaxFineBins = 2048;            // linear bins over [t_lo, fine_hi
 constexpr u32 kCoarseShift = 23;              // coarse bins above them: the 8 exponent bits
 constexpr u32 kCoarseBins = 256;
 constexpr u32 kMaxBins = kMaxFineBins + kCoarseBins;
-constexpr u32 kMaxFusedBlocks = 1024;         // rows of per-workgroup histograms
+constexpr u32 kMaxFusedBlocks = 256;          // rows of per-workgroup histograms (one per compute unit)
 constexpr u32 kCoarseSpan = 64;               // bins per group: every row also carries its group sums
 constexpr u32 kMaxGroups = kMaxBins / kCoarseSpan;
 static_assert(kMaxBins % kCoarseSpan == 0 && kCoarseSpan == 64, "one lane per bin of a group");
@@ -106,7 +106,8 @@ constexpr u32 kMaxWalkBlocks = kMaxUnits / kWalkWaves;
 // next to each other, so it reads them as one 32-byte piece instead of
 // kUnitChunks separate cache lines.
 __host__ __device__ inline u32 chunk_slot(u32 s, u32 U) { return (s % U) * kUnitChunks + s / U; }
-constexpr u32 kListCap = 512;                 // short-list slots per classify workgroup
+constexpr u32 kListCap = 128;                 // short-list slots per classify workgroup
+constexpr u32 kSliceDiv = 8;                  // a chunk's slice of S holds a kSliceDiv-th of the chunk
 constexpr int kFinThreads = 1024;
 constexpr u32 kFinWaves = kFinThreads / kWave;
 constexpr u32 kSlabs = kTargetChunks / (4 * kFinThreads);  // 16-byte groups of chunk counters per thread
@@ -114,6 +115,23 @@ constexpr u32 kStageB = 2048, kStageM = 4096; // short lists that fit are select
 
 constexpr u32 kErrSelect = 2u;                // a selection found no element of the requested rank
 constexpr u32 kErrCount = 4u;                 // the winners did not add up to k
+constexpr u32 kErrBarrier = 8u;               // a workgroup gave up waiting for the others of its grid
+
+// The exact fallback over ALL candidates (or over the vector itself) runs on
+// kWideBlocks workgroups of the finalize kernel when the vector is long enough
+// to be worth it; they exchange 256-bin histograms through the workspace and
+// meet at a barrier between radix passes.
+constexpr u32 kWideBlocks = 64;
+constexpr u32 kWideMinChunks = 256;
+constexpr u32 kWidePasses = 24;               // 8 (magnitude, index) + 12 (key, index) + 2 fetches + slack
+constexpr u32 kWideSpinLimit = 1u << 20;      // polls (about a microsecond each) before giving up
+
+struct WideScratch {
+    u32 arrived;                              // workgroups that reached a barrier, over all barriers
+    u32 pad[63];
+    u32 hist[kWidePasses][256];
+    u64 found[kWidePasses][2];                // the one string left under a resolved prefix
+};
 
 // Histogram geometry chosen by the estimate kernel.
 struct Bins {
@@ -170,6 +188,8 @@ struct EncodeCtl {
 struct Geom {
     u64 d, r, k;
     u32 C;              // elements per chunk (multiple of 256, at least 1024)
+    u32 cap;            // entries a chunk's slice of S holds (C / kSliceDiv); a chunk that keeps
+                        // more is read from the vector itself by the later kernels
     u32 W;              // chunks
     u32 U;              // wavefronts of classify / emit; wavefront u walks chunks u, u + U, ...
     u32 G3;             // classify / emit workgroups
@@ -183,7 +203,7 @@ struct Geom {
 };
 
 struct EncodeLayout {
-    u64 ctl, zero_bytes, partials, group_sums;
+    u64 ctl, wide, zero_bytes, partials, group_sums;
     u64 samples, seg_count, win_cnt, bd_cnt, chunk_base, blk_sure, n_m, n_b, blk_bmin, blk_bmax;
     u64 m_key, m_idx, b_mag, b_idx;
     u64 dm_key, dm_idx, db_key, db_idx;
@@ -204,6 +224,7 @@ static Geom make_geom(u64 d, u64 r, u64 k)
     // 2560 or 8192 elements; a quarter of a kilobyte more staggers the starting points.
     if (per > kMinChunk && per % 1024 == 0 && per % 8192 != 0) per += kChunkQuantum;
     g.C = (u32)per;
+    g.cap = g.C / kSliceDiv;
     g.W = (u32)((d + per - 1) / per);
     g.U = g.W < kMaxUnits ? g.W : kMaxUnits;
     g.G3 = (g.U + kWalkWaves - 1) / kWalkWaves;
@@ -238,7 +259,8 @@ static EncodeLayout make_layout(const Geom &g)
     u64 o = 0;
     auto take = [&](u64 bytes) { u64 at = o; o = align_up(o + bytes, 256); return at; };
     L.ctl = take(sizeof(EncodeCtl));
-    L.zero_bytes = o;
+    L.wide = take(sizeof(WideScratch));
+    L.zero_bytes = o;                       // cleared at the start of every call
     L.partials = take((u64)kMaxFusedBlocks * kMaxBins * 4);
     L.group_sums = take((u64)kMaxFusedBlocks * kMaxGroups * 4);
     L.samples = take((u64)kSampleLoc * 16);
@@ -260,8 +282,7 @@ static EncodeLayout make_layout(const Geom &g)
     L.dm_idx = take(2 * slots * 4);
     L.db_key = take(slots * 8);
     L.db_idx = take(slots * 4);
-    const u64 cap = (u64)g.W * g.C;
-    L.s_ent = take(cap * 8);
+    L.s_ent = take((u64)g.W * g.cap * 8);
     L.total = o;
     return L;
 }
@@ -277,6 +298,16 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Orders one wavefront's own LDS accesses: what its lanes wrote before is what
+// its lanes read after (the hardware keeps a wavefront's LDS operations in
+// order; this keeps the compiler from moving them).
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
 }
 
 // ---------------------------------------------------------------------------
@@ -556,11 +587,17 @@ __device__ __forceinline__ u64 elem_index(u64 base, int e)
 
 template <bool kVec4>
 __device__ __forceinline__ void append_hits(const u32 (&bits)[4], const bool (&hit)[4], u64 base,
-                                            u32 &run, uint2 *__restrict__ my_ent)
+                                            u32 &run, uint2 *__restrict__ my_ent, u32 cap)
 {
     const u64 b0 = __ballot(hit[0]), b1 = __ballot(hit[1]), b2 = __ballot(hit[2]),
               b3 = __ballot(hit[3]);
     if ((b0 | b1 | b2 | b3) == 0ull) return;
+    if (run >= cap) {
+        // the slice is full: the chunk will be read from the vector itself, only its
+        // count goes on (anything above cap says so)
+        run += popc64(b0) + popc64(b1) + popc64(b2) + popc64(b3);
+        return;
+    }
     const u64 below = lanes_below();
     u32 pos[4];
     if (kVec4) {
@@ -576,7 +613,7 @@ __device__ __forceinline__ void append_hits(const u32 (&bits)[4], const bool (&h
     }
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        if (hit[e]) {
+        if (hit[e] && pos[e] < cap) {
             my_ent[pos[e]] = make_uint2((u32)elem_index<kVec4>(base, e), bits[e]);
         }
     }
@@ -600,15 +637,16 @@ constexpr u32 kFusedWaves = kFusedThreads / kWave;
 template <bool kVec4, bool kAll>
 __device__ __forceinline__ void
 fused_body(const float *__restrict__ grad, float *__restrict__ residual, Geom g, PhiloxSeed seed,
-        EncodeCtl *__restrict__ ctl, u32 *__restrict__ partials, u32 *__restrict__ group_sums,
-        u32 *__restrict__ seg_count, uint2 *__restrict__ s_ent)
+        EncodeCtl *__restrict__ ctl, u32 zero_words, u32 *__restrict__ partials,
+        u32 *__restrict__ group_sums, u32 *__restrict__ seg_count, uint2 *__restrict__ s_ent)
 {
     __shared__ u32 h[kAll ? 1 : kMaxBins];
     Bins bins{};
     u32 nbins = 0;
     if (kAll) {
+        // (the control block and what follows it up to zero_words, at the workspace's start)
         if (blockIdx.x == 0)
-            for (u32 i = threadIdx.x; i < sizeof(EncodeCtl) / 4; i += kFusedThreads)
+            for (u32 i = threadIdx.x; i < zero_words; i += kFusedThreads)
                 reinterpret_cast<u32 *>(ctl)[i] = 0u;
     } else {
         bins = ctl->bins;
@@ -621,7 +659,7 @@ fused_body(const float *__restrict__ grad, float *__restrict__ residual, Geom g,
     for (u32 w = blockIdx.x * kFusedWaves + threadIdx.x / kWave; w < g.W; w += wave_stride) {
         const u64 c0 = (u64)w * g.C;
         const u64 c1 = c0 + g.C < g.d ? c0 + g.C : g.d;
-        uint2 *my_ent = s_ent + c0;
+        uint2 *my_ent = s_ent + (u64)w * g.cap;
         u32 run = 0;
         auto keep = [&](const u32 (&bits)[4], const bool (&valid)[4], u64 base) {
             bool hit[4];
@@ -637,7 +675,7 @@ fused_body(const float *__restrict__ grad, float *__restrict__ residual, Geom g,
                     if (hit[e]) atomicAdd(&h[bin_of(bins, m)], 1u);
                 }
             }
-            append_hits<kVec4>(bits, hit, base, run, my_ent);
+            append_hits<kVec4>(bits, hit, base, run, my_ent, g.cap);
         };
         const bool all_valid[4] = {true, true, true, true};
         // NR full iterations at a time, all loads issued before the first use. Every
@@ -732,20 +770,35 @@ struct Candidates {
     const uint2 *__restrict__ s_ent;
     const float *__restrict__ a;
     u64 d;
-    u32 C, U;
-    bool dense;
+    u32 C, U, cap;
+    bool dense;         // every chunk is read from the vector (the estimate kept too little)
 
-    __device__ __forceinline__ u32 count(u32 s) const
+    __device__ __forceinline__ u32 length(u32 s) const
     {
-        if (!dense) return seg_count[chunk_slot(s, U)];
         const u64 c0 = (u64)s * C;
         return (u32)(c0 + C < d ? C : d - c0);
     }
-    __device__ __forceinline__ void entry(u32 s, u32 j, u32 *idx, u32 *bits) const
+    // entries of chunk s, and whether they are the chunk's elements themselves:
+    // a chunk that kept more than its slice holds is read from the vector (all
+    // its elements then count as entries; what lies below the candidates'
+    // lower bound is below every threshold the later kernels compare with)
+    __device__ __forceinline__ u32 count(u32 s, bool *from_vector) const
     {
-        const u64 at = (u64)s * C + j;
-        if (!dense) { const uint2 e = s_ent[at]; *idx = e.x; *bits = e.y; }
-        else { *idx = (u32)at; *bits = __float_as_uint(a[at]); }
+        const u32 kept = dense ? 0u : seg_count[chunk_slot(s, U)];
+        *from_vector = dense || kept > cap;
+        return *from_vector ? length(s) : kept;
+    }
+    __device__ __forceinline__ void entry(u32 s, u32 j, bool from_vector, u32 *idx, u32 *bits) const
+    {
+        if (!from_vector) {
+            const uint2 e = s_ent[(u64)s * cap + j];
+            *idx = e.x;
+            *bits = e.y;
+        } else {
+            const u64 at = (u64)s * C + j;
+            *idx = (u32)at;
+            *bits = __float_as_uint(a[at]);
+        }
     }
 };
 
@@ -764,6 +817,7 @@ struct Candidates {
 template <u32 kChunks>
 struct ChunkWalk {
     u32 u, stride, excl, inc, total;
+    u64 from_vector;        // bit i: the i-th chunk is read from the vector itself
 
     // chunks first, first + step, ..., at most kChunks of them and only those below n_chunks
     __device__ __forceinline__ ChunkWalk(const Candidates &cand, u32 first, u32 step, u32 n_chunks)
@@ -773,7 +827,10 @@ struct ChunkWalk {
         u = first;
         stride = step;
         const u64 s = (u64)first + (u64)lane * step;
-        const u32 cnt = (lane < kChunks && s < n_chunks) ? cand.count((u32)s) : 0u;
+        bool fv = false;
+        u32 cnt = (lane < kChunks && s < n_chunks) ? cand.count((u32)s, &fv) : 0u;
+        from_vector = __ballot(fv);
+        if (fv) cnt = 0u;           // not part of the flat sequence: see for_each_vector_row
         inc = wave_inclusive_sum(cnt);
         excl = inc - cnt;
         total = __shfl(inc, kWave - 1, kWave);
@@ -808,7 +865,7 @@ struct ChunkWalk {
             for (u32 q = 0; q < kAhead; ++q) {
                 const u32 p = p0 + q * kWave + lane;
                 locate(p, &c[q], &first[q]);
-                cand.entry(u + c[q] * stride, p - first[q], &idx[q], &bits[q]);
+                cand.entry(u + c[q] * stride, p - first[q], false, &idx[q], &bits[q]);
             }
 #pragma unroll
             for (u32 q = 0; q < kAhead; ++q) f(true, c[q], idx[q], bits[q], first[q], p0 + q * kWave);
@@ -817,13 +874,127 @@ struct ChunkWalk {
             const u32 p = p0 + lane;
             u32 c, first, idx = 0, bits = 0;
             locate(p, &c, &first);
-            if (p < total) cand.entry(u + c * stride, p - first, &idx, &bits);
+            if (p < total) cand.entry(u + c * stride, p - first, false, &idx, &bits);
             f(p < total, c, idx, bits, first, p0);
         }
     }
+
+    // The wavefront's chunks that are read from the vector itself (they kept more
+    // candidates than their slice of S holds, or the whole vector is walked), one
+    // after the other in rows of 256 elements, four rows fetched together: lane l
+    // holds the four elements idx0 .. idx0 + 3, idx0 = row start + 4 l, with 16-byte
+    // loads where the vector's alignment allows. g(i, idx0, patterns, valid) is called
+    // by all lanes together, rows of one chunk in index order; i is the chunk's
+    // ordinal among the wavefront's chunks.
+    template <class G>
+    __device__ __forceinline__ void for_each_vector_row(const Candidates &cand, G &&g) const
+    {
+        const u32 lane = lane_id();
+        const bool vec16 = (reinterpret_cast<uintptr_t>(cand.a) & 15u) == 0;
+        for (u64 rest = from_vector; rest; rest &= rest - 1ull) {
+            const u32 i = (u32)__ffsll((unsigned long long)rest) - 1u;
+            const u32 s = u + i * stride;
+            const u64 c0 = (u64)s * cand.C;
+            const u32 len = cand.length(s);
+            for (u32 r0 = 0; r0 < len; r0 += 4 * kChunkQuantum) {
+                u32 bits[4][4];
+                bool valid[4][4];
+#pragma unroll
+                for (u32 q = 0; q < 4; ++q) {
+                    const u32 row = r0 + q * kChunkQuantum;
+                    const u32 off = row + 4u * lane;
+                    if (vec16 && row + kChunkQuantum <= len) {
+                        const f32x4 v = *reinterpret_cast<const f32x4 *>(cand.a + c0 + off);
+                        bits[q][0] = __float_as_uint(v.x); bits[q][1] = __float_as_uint(v.y);
+                        bits[q][2] = __float_as_uint(v.z); bits[q][3] = __float_as_uint(v.w);
+#pragma unroll
+                        for (u32 e = 0; e < 4; ++e) valid[q][e] = true;
+                    } else {
+#pragma unroll
+                        for (u32 e = 0; e < 4; ++e) {
+                            valid[q][e] = off + e < len;
+                            bits[q][e] = valid[q][e] ? __float_as_uint(cand.a[c0 + off + e]) : 0u;
+                        }
+                    }
+                }
+#pragma unroll
+                for (u32 q = 0; q < 4; ++q)
+                    if (r0 + q * kChunkQuantum < len)
+                        g(i, (u32)(c0 + r0 + q * kChunkQuantum) + 4u * lane, bits[q], valid[q]);
+            }
+        }
+    }
+
+    // The same chunks with the elements that keep(pattern) lets through gathered
+    // first, so that the work per entry (a sampling key costs a hundred
+    // instructions) is done on full wavefronts: the rows' survivors are appended
+    // to a queue in LDS in index order (buf: kRowQueue entries owned by this
+    // wavefront) and taken from its front 64 at a time; what is left of a chunk
+    // is flushed before the next one starts. f(valid, i, index, pattern) is called
+    // by all lanes together, entries of one chunk in index order.
+    template <class Keep, class F>
+    __device__ __forceinline__ void for_each_vector_entry(const Candidates &cand, uint2 *buf,
+                                                          Keep &&keep, F &&f) const
+    {
+        const u32 lane = lane_id();
+        const u64 below = lanes_below();
+        u32 pending = 0, cur = 0;
+        auto drain = [&](u32 i, bool all) {
+            u32 done = 0;
+            while (done < pending && (all || pending - done >= (u32)kWave)) {
+                const u32 j = done + lane;
+                const bool v = j < pending;
+                const uint2 e = v ? buf[j] : make_uint2(0u, 0u);
+                f(v, i, e.x, e.y);
+                done += kWave;
+            }
+            if (all) {
+                pending = 0;
+            } else if (done > 0) {
+                const u32 rest = pending - done;           // fewer than 64: to the front
+                uint2 e = make_uint2(0u, 0u);
+                if (lane < rest) e = buf[done + lane];
+                wave_lds_fence();
+                if (lane < rest) buf[lane] = e;
+                pending = rest;
+            }
+            wave_lds_fence();
+        };
+        for_each_vector_row(cand, [&](u32 i, u32 idx0, const u32 (&bits)[4], const bool (&valid)[4]) {
+            if (i != cur) { drain(cur, true); cur = i; }
+            bool hit[4];
+            u64 b[4];
+#pragma unroll
+            for (u32 e = 0; e < 4; ++e) {
+                hit[e] = valid[e] && keep(bits[e]);
+                b[e] = __ballot(hit[e]);
+            }
+            if ((b[0] | b[1] | b[2] | b[3]) == 0ull) return;
+            u32 p = pending + popc64(b[0] & below) + popc64(b[1] & below) + popc64(b[2] & below) +
+                    popc64(b[3] & below);
+#pragma unroll
+            for (u32 e = 0; e < 4; ++e)
+                if (hit[e]) buf[p++] = make_uint2(idx0 + e, bits[e]);
+            pending += popc64(b[0]) + popc64(b[1]) + popc64(b[2]) + popc64(b[3]);
+            wave_lds_fence();
+            drain(i, false);
+        });
+        drain(cur, true);
+    }
 };
+constexpr u32 kRowQueue = 320;               // 63 entries carried over + one row of 256
 
 using UnitWalk = ChunkWalk<kUnitChunks>;     // classify / emit: chunks u, u + U, u + 2U, ...
+
+// per-element form of a row callback: f(valid, i, index, pattern) four times
+template <class F>
+__device__ __forceinline__ auto each_of_row(F &&f)
+{
+    return [&f](u32 i, u32 idx0, const u32 (&bits)[4], const bool (&valid)[4]) {
+#pragma unroll
+        for (u32 e = 0; e < 4; ++e) f(valid[e], i, idx0 + e, bits[e]);
+    };
+}
 
 // ---------------------------------------------------------------------------
 // pick: one workgroup finds the bin that holds the r-th largest magnitude
@@ -956,8 +1127,8 @@ pick_body(const u32 *__restrict__ partials, const u32 *__restrict__ group_sums, 
 // a known rank in index order, which those counts locate.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ void
-classify_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ seg_count,
-           const uint2 *__restrict__ s_ent,
+classify_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__ a,
+           const u32 *__restrict__ seg_count, const uint2 *__restrict__ s_ent,
            u32 *__restrict__ win_cnt, u32 *__restrict__ bd_cnt, u32 *__restrict__ blk_sure,
            u32 *__restrict__ n_m, u32 *__restrict__ n_b, u32 *__restrict__ blk_bmin,
            u32 *__restrict__ blk_bmax, u64 *__restrict__ m_key, u32 *__restrict__ m_idx,
@@ -966,6 +1137,7 @@ classify_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ s
     __shared__ u32 cnt_m, cnt_b, cnt_sure, bmin_s, bmax_s;
     __shared__ u32 per_chunk[kWalkWaves][kUnitChunks];
     __shared__ u32 per_chunk_b[kWalkWaves][kUnitChunks];
+    __shared__ uint2 row_queue[kWalkWaves][kRowQueue];
     const u32 wave = threadIdx.x / kWave, lane = lane_id();
     const u32 u = blockIdx.x * kWalkWaves + wave;
     const bool dense = ctl->dense != 0u;
@@ -977,7 +1149,7 @@ classify_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ s
         }
         return;
     }
-    const Candidates cand{seg_count, s_ent, nullptr, g.d, g.C, g.U, false};
+    const Candidates cand{seg_count, s_ent, a, g.d, g.C, g.U, g.cap, false};
     const UnitWalk walk(cand, u < g.U ? u : g.W, g.U, g.W);
     if (threadIdx.x == 0) { cnt_m = 0u; cnt_b = 0u; cnt_sure = 0u; bmin_s = 0xFFFFFFFFu; bmax_s = 0u; }
     if (lane < kUnitChunks) { per_chunk[wave][lane] = 0u; per_chunk_b[wave][lane] = 0u; }
@@ -988,7 +1160,7 @@ classify_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ s
     // finalize kernel reads entry p of all workgroups with one coalesced load
     auto slot = [&](u32 p) { return (u64)p * g.G3 + blockIdx.x; };
     const u64 below = lanes_below();
-    walk.for_each(cand, [&](bool valid, u32 i, u32 idx, u32 bits, u32, u32) {
+    auto per_entry = [&](bool valid, u32 i, u32 idx, u32 bits) {
         const u32 m = mag_of(bits);
         const bool member = valid && (g.all_members != 0u || m > bd_hi);
         const bool in_bin = valid && !member && m >= bd_lo;
@@ -1018,7 +1190,13 @@ classify_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const u32 *__restrict__ s
             if (m < lane_bmin) { lane_bmin = m; atomicMin(&bmin_s, m); }
             if (m > lane_bmax) { lane_bmax = m; atomicMax(&bmax_s, m); }
         }
+    };
+    walk.for_each(cand, [&](bool valid, u32 i, u32 idx, u32 bits, u32, u32) {
+        per_entry(valid, i, idx, bits);
     });
+    walk.for_each_vector_entry(cand, row_queue[wave],
+                               [&](u32 bits) { return g.all_members != 0u || mag_of(bits) >= bd_lo; },
+                               per_entry);
     __builtin_amdgcn_wave_barrier();
     // certain winners, and entries of the deciding bin, of each of the wavefront's chunks
     u32 mine = 0;
@@ -1153,11 +1331,146 @@ __device__ __forceinline__ bool pair_le(u64 hi, u32 lo, const Pair96 &p)
 }
 
 // ---------------------------------------------------------------------------
-// finalize: one workgroup turns the short lists into the two cut points and
-// the output offset of every chunk.
+// The same selection spread over the workgroups of one grid (the finalize
+// kernel's, at most kWideBlocks, which are resident together). Each workgroup
+// histograms its share of the strings in LDS, adds its non-empty bins to the
+// pass's 256-bin histogram in the workspace (device-scope atomics), and all
+// meet at a barrier; every workgroup then reads the same totals and derives
+// the same digit. The barrier is a counter that only grows; a workgroup that
+// polls it kWideSpinLimit times in vain gives up, which ends the kernel with
+// an error flag instead of a hang (the others give up in turn).
+// ---------------------------------------------------------------------------
+struct Wide {
+    WideScratch *ws;
+    u32 nblocks;
+    u32 epoch;          // barriers passed
+    u32 pass;           // histogram / fetch slots used
+    bool alive;         // false once a barrier timed out
+};
+
+__device__ __forceinline__ bool grid_barrier(Wide &w, u32 *lds_flag)
+{
+    if (!w.alive) return false;
+    __threadfence();                               // what this thread wrote is visible device-wide
+    __syncthreads();
+    ++w.epoch;
+    if (threadIdx.x == 0) {
+        __hip_atomic_fetch_add(&w.ws->arrived, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        const u32 target = w.epoch * w.nblocks;
+        u32 polls = 0;
+        bool ok = true;
+        while (__hip_atomic_load(&w.ws->arrived, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+            __builtin_amdgcn_s_sleep(32);
+            if (++polls > kWideSpinLimit) { ok = false; break; }
+        }
+        *lds_flag = ok ? 1u : 0u;
+    }
+    __syncthreads();
+    __threadfence();                               // what the others wrote is read from memory
+    w.alive = *lds_flag != 0u;
+    __syncthreads();
+    return w.alive;
+}
+
+// for_each(f) calls f(valid, hi, lo) for every string of this workgroup's
+// share, ALL lanes of a wavefront together (valid says whether the lane holds
+// one). *less_hi receives the number of strings whose high 64 bits are below
+// the result's. h: 4 x 256 words of LDS.
+template <class ForEach>
+__device__ __forceinline__ Pair96 grid_select96(ForEach &&for_each, u64 rank, int first_byte, Wide &w,
+                                                u32 (*h)[256], u64 *less_hi, bool *ok)
+{
+    u64 phi = 0;
+    u32 plo = 0;
+    u64 need = rank;
+    int j = first_byte;
+    const u32 lane = lane_id();
+    *ok = true;
+    *less_hi = 0;
+    for (; j < 12; ++j) {
+        for (u32 b = threadIdx.x; b < 256u; b += blockDim.x) h[0][b] = 0u;
+        lds_barrier();
+        for_each([&](bool valid, u64 hi, u32 lo) {
+            const bool on = valid && pair_matches(hi, lo, phi, plo, j);
+            const u32 digit = pair_byte(hi, lo, j);
+            // neighbouring strings often share the digit (runs of equal magnitudes): when all
+            // of a wavefront's do, one addition serves them
+            const u64 m = __ballot(on);
+            if (m == 0ull) return;
+            const int src = __ffsll((unsigned long long)m) - 1;
+            const u32 first = (u32)__builtin_amdgcn_readlane((int)digit, src);
+            if (__ballot(on && digit == first) == m) {
+                if ((int)lane == src) atomicAdd(&h[0][first], popc64(m));
+            } else if (on) {
+                atomicAdd(&h[0][digit], 1u);
+            }
+        });
+        lds_barrier();
+        if (w.pass >= kWidePasses) { *ok = false; return Pair96{0, 0}; }
+        u32 *gh = w.ws->hist[w.pass];
+        for (u32 b = threadIdx.x; b < 256u; b += blockDim.x)
+            if (h[0][b]) atomicAdd(&gh[b], h[0][b]);
+        if (!grid_barrier(w, &h[3][4])) { *ok = false; return Pair96{0, 0}; }
+        if (threadIdx.x < kWave) {
+            u32 c[4];
+            u32 mine = 0;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                c[q] = __hip_atomic_load(&gh[4 * lane + q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                mine += c[q];
+            }
+            const u32 inc = wave_inclusive_sum(mine);
+            u32 run = inc - mine;
+            const bool mine_it = (u64)run < need && need <= (u64)inc;
+            const u64 owner = __ballot(mine_it);
+            if (owner == 0ull && lane == 0) h[3][3] = 0u;
+            if (mine_it) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if ((u64)run < need && need <= (u64)run + c[q]) {
+                        h[3][0] = 4 * lane + q;
+                        h[3][1] = c[q];
+                        h[3][2] = run;
+                        h[3][3] = 1u;
+                    }
+                    run += c[q];
+                }
+            }
+        }
+        lds_barrier();
+        ++w.pass;
+        if (h[3][3] == 0u) { *ok = false; return Pair96{0, 0}; }
+        const u32 bin = h[3][0], in_bin = h[3][1], before = h[3][2];
+        lds_barrier();
+        need -= before;
+        if (j < 8) { phi |= (u64)bin << (56 - 8 * j); *less_hi += before; }
+        else plo |= bin << (24 - 8 * (j - 8));
+        if (in_bin == 1u) { ++j; break; }
+    }
+    if (j < 12) {
+        // exactly one string starts with the resolved bytes: whoever holds it leaves it for all
+        if (w.pass >= kWidePasses) { *ok = false; return Pair96{0, 0}; }
+        u64 *slot = w.ws->found[w.pass];
+        for_each([&](bool valid, u64 hi, u32 lo) {
+            if (valid && pair_matches(hi, lo, phi, plo, j)) { slot[0] = hi; slot[1] = (u64)lo; }
+        });
+        if (!grid_barrier(w, &h[3][4])) { *ok = false; return Pair96{0, 0}; }
+        phi = __hip_atomic_load(&slot[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        plo = (u32)__hip_atomic_load(&slot[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        ++w.pass;
+    }
+    return Pair96{phi, plo};
+}
+
+// ---------------------------------------------------------------------------
+// finalize: turns the short lists into the two cut points and the output
+// offset of every chunk (workgroup 0; the others leave at once), or, when the
+// counts left by classify show that the lists cannot decide and the vector is
+// long, runs the exact selection over all candidates on all its workgroups.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ void
-finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__ a,
+finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, WideScratch *wide_ws,
+           const float *__restrict__ a,
            const u32 *__restrict__ seg_count, const uint2 *__restrict__ s_ent,
            u32 *win_cnt, const u32 *__restrict__ bd_cnt, const u32 *__restrict__ blk_sure,
            const u32 *__restrict__ n_m, const u32 *__restrict__ n_b,
@@ -1182,7 +1495,7 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
     const u32 tid = threadIdx.x;
     const u32 wave = tid / kWave, lane = lane_id();
     const bool dense = ctl->dense != 0u;
-    Candidates cand{seg_count, s_ent, a, g.d, g.C, g.U, dense};
+    Candidates cand{seg_count, s_ent, a, g.d, g.C, g.U, g.cap, dense};
     // every candidate, split wavefront by chunk; f(index, pattern, chunk)
     auto each_s = [&](auto &&f) {
         // kWave consecutive chunks per wavefront at a time: their sizes in one round of
@@ -1192,6 +1505,10 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
             walk.for_each(cand, [&](bool valid, u32 i, u32 idx, u32 bits, u32, u32) {
                 if (valid) f(idx, bits, first + i);
             });
+            auto of_row = [&](bool valid, u32 i, u32 idx, u32 bits) {
+                if (valid) f(idx, bits, first + i);
+            };
+            walk.for_each_vector_row(cand, each_of_row(of_row));
         }
     };
 
@@ -1203,11 +1520,20 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
     const u64 c_def = ctl->c_def;
     const bool overflow = ctl->overflow != 0u, overflow_m = ctl->overflow_m != 0u;
     if (tid == 0) { extra_m = 0u; sure_extra = 0u; gt_extra = 0ull; run_found = 0u; }
-    const u32 em = block_exclusive_sum(vm, scan32);
-    const u32 n_m0 = scan32[kFinWaves];
-    const u32 eb = block_exclusive_sum(vb, scan32);
-    const u32 n_bd = scan32[kFinWaves];
-    const u64 sure_walk = block_sum(vs, scan32);
+    // the three totals with one barrier (every workgroup of the grid needs them to
+    // decide whether it stays; the prefix sums follow for the one that does)
+    u32 n_m0, n_bd;
+    u64 sure_walk;
+    {
+        const u32 wm = wave_sum(vm), wb = wave_sum(vb), wsure = wave_sum(vs);
+        if (lane == 0) { scan32[wave] = wm; scan32[kFinWaves + wave] = wb; scan32[2 * kFinWaves + wave] = wsure; }
+        static_assert(3 * kFinWaves <= kSlabs * kFinWaves + 1, "room for three partial sums per wavefront");
+        lds_barrier();
+        n_m0 = wave_sum(lane < kFinWaves ? scan32[lane] : 0u);
+        n_bd = wave_sum(lane < kFinWaves ? scan32[kFinWaves + lane] : 0u);
+        sure_walk = wave_sum(lane < kFinWaves ? scan32[2 * kFinWaves + lane] : 0u);
+        lds_barrier();
+    }
 
     const u64 need2 = g.r - c_def;
     u32 err = 0, path = 0;
@@ -1235,6 +1561,141 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
         lds_barrier();
         tie_run = all_lo == all_hi;
         if (tie_run) T = all_lo;
+    }
+    // ---- many workgroups or one? Every workgroup of the grid decides alike,
+    //      from what classify and pick left: the lists cannot give the
+    //      threshold (the estimate kept too little; the deciding bin crowded by
+    //      several magnitudes), or the key window certainly missed.
+    bool wide = false;
+    if (gridDim.x > 1u) {
+        const bool slow_t = !g.all_members && !lists && !tie_run;
+        bool slow_k = false;
+        if (!g.take_all && !tie_run) {
+            const u64 from_b = (g.all_members || !lists) ? 0ull : (need2 < n_bd ? need2 : (u64)n_bd);
+            slow_k = dense || overflow_m || (g.all_members && overflow) || sure_walk >= g.k ||
+                     sure_walk + n_m0 + from_b < g.k;
+        }
+        wide = slow_t || slow_k;
+        if (!wide && blockIdx.x != 0u) return;
+    }
+    if (__builtin_expect(wide, 0)) {
+        // ---- exact selection over all candidates, on all workgroups of the grid
+        Wide w{wide_ws, gridDim.x, 0u, 0u, true};
+        // r == d: S only holds the coordinates inside the key window, which
+        // missed: the vector itself is walked, here and by the emit kernel
+        if (g.all_members) cand.dense = true;
+        const bool vec16 = (reinterpret_cast<uintptr_t>(a) & 15u) == 0;
+        const u32 n_waves = gridDim.x * kFinWaves;
+        // f(valid, index, pattern) for every entry of this workgroup's chunks, all lanes
+        // together; done(s) after the last entry of chunk s. Wavefront v of the grid takes
+        // chunks v, v + n_waves, ...; a chunk read from the vector is streamed with
+        // 16-byte loads, four rows in flight.
+        auto wide_each = [&](auto &&f, auto &&done) {
+            for (u32 sc = blockIdx.x * kFinWaves + wave; sc < g.W; sc += n_waves) {
+                bool fv = false;
+                const u32 n_e = cand.count(sc, &fv);
+                if (!fv) {
+                    for (u32 j0 = 0; j0 < n_e; j0 += kWave) {
+                        const u32 j = j0 + lane;
+                        u32 idx = 0, bits = 0;
+                        if (j < n_e) cand.entry(sc, j, false, &idx, &bits);
+                        f(j < n_e, idx, bits);
+                    }
+                } else {
+                    const u64 c0 = (u64)sc * g.C;
+                    u32 j0 = 0;
+                    if (vec16) {
+                        for (; j0 + 4 * kChunkQuantum <= n_e; j0 += 4 * kChunkQuantum) {
+                            const f32x4 *p4 = reinterpret_cast<const f32x4 *>(a + c0 + j0) + lane;
+                            f32x4 v[4];
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) v[q] = p4[q * kWave];
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) {
+                                const u32 i0 = (u32)(c0 + j0) + (u32)q * kChunkQuantum + 4u * lane;
+                                f(true, i0, __float_as_uint(v[q].x));
+                                f(true, i0 + 1u, __float_as_uint(v[q].y));
+                                f(true, i0 + 2u, __float_as_uint(v[q].z));
+                                f(true, i0 + 3u, __float_as_uint(v[q].w));
+                            }
+                        }
+                    }
+                    for (; j0 < n_e; j0 += kWave) {
+                        const u32 j = j0 + lane;
+                        const u32 bits = j < n_e ? __float_as_uint(a[c0 + j]) : 0u;
+                        f(j < n_e, (u32)(c0 + j), bits);
+                    }
+                }
+                done(sc);
+            }
+        };
+        auto nothing = [](u32) {};
+        path = 1u | 8u;
+        if (!g.all_members) {
+            // the r-th (magnitude desc, index asc): inside the deciding bin when pick found
+            // one, over the whole vector when the estimate had kept too little
+            const bool in_bin_only = !cand.dense;
+            const u32 top = in_bin_only ? bd_hi : 0x7FFFFFFFu;
+            auto each_mag = [&](auto &&f2) {
+                wide_each([&](bool valid, u32 idx, u32 bits) {
+                    const u32 m = mag_of(bits);
+                    const bool on = valid && (!in_bin_only || (m >= bd_lo && m <= bd_hi));
+                    f2(on, (u64)(top - (on ? m : top)), idx);
+                }, nothing);
+            };
+            u64 less = 0;
+            const Pair96 tb = grid_select96(each_mag, in_bin_only ? need2 : g.r,
+                                            in_bin_only ? (64 - (int)bd_bits) / 8 : 4, w, h, &less, &ok);
+            if (!ok) err |= kErrSelect;
+            T = top - (u32)tb.hi;
+            I_star = tb.lo;
+            count_greater = (in_bin_only ? c_def : 0ull) + less;
+        }
+        auto is_member_w = [&](u32 idx, u32 bits) {
+            const u32 m = mag_of(bits);
+            return g.all_members != 0u || m > T || (m == T && idx <= I_star);
+        };
+        if (!g.take_all && w.alive) {
+            auto each_key = [&](auto &&f2) {
+                wide_each([&](bool valid, u32 idx, u32 bits) {
+                    const bool on = valid && is_member_w(idx, bits);
+                    f2(on, on ? sample_key(idx, seed) : 0ull, idx);
+                }, nothing);
+            };
+            u64 less = 0;
+            bool ok_k = true;
+            const Pair96 kb = grid_select96(each_key, g.k, 0, w, h, &less, &ok_k);
+            if (!ok_k) err |= kErrSelect;
+            K_star = kb.hi;
+            J_star = kb.lo;
+        }
+        // winners per chunk (every chunk's counter is written: what classify left is stale)
+        if (w.alive) {
+            const Pair96 kcut{K_star, J_star};
+            u32 mine = 0;
+            wide_each([&](bool valid, u32 idx, u32 bits) {
+                if (valid && is_member_w(idx, bits) &&
+                    (g.take_all != 0u || pair_le(sample_key(idx, seed), idx, kcut)))
+                    ++mine;
+            }, [&](u32 sc) {
+                const u32 total = wave_sum(mine);
+                if (lane == 0) win_cnt[sc] = total;
+                mine = 0;
+            });
+            grid_barrier(w, &h[3][4]);
+        }
+        if (!w.alive) err |= kErrBarrier;
+        if (blockIdx.x != 0u) return;
+        have_t = true;
+        have_k = true;
+        if (g.all_members && tid == 0) ctl->dense = 1u;
+    }
+
+    // where this thread's classify workgroup's entries start in the lists
+    u32 em = 0, eb = 0;
+    if (!wide && (lists || tie_run)) {
+        em = block_exclusive_sum(vm, scan32);
+        eb = block_exclusive_sum(vb, scan32);
     }
     // The short-list path. It is compiled twice: once with both lists in LDS
     // (the usual case; the compiler then knows the address space of every list
@@ -1353,14 +1814,15 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
                 // ---- the entry of that rank inside the chunk, 1024 entries a round
                 const u32 sc = run_chunk;
                 const u32 want = (u32)(need2 - run_before);      // 1-based, among the chunk's
-                const u32 n_e = cand.count(sc);
+                bool sc_vec = false;
+                const u32 n_e = cand.count(sc, &sc_vec);
                 lds_barrier();
                 if (tid == 0) run_found = 0u;
                 u32 seen = 0;
                 for (u32 j0 = 0; j0 < n_e && seen < want; j0 += kFinThreads) {
                     const u32 j = j0 + tid;
                     u32 idx = 0, bits = 0;
-                    if (j < n_e) cand.entry(sc, j, &idx, &bits);
+                    if (j < n_e) cand.entry(sc, j, sc_vec, &idx, &bits);
                     const u32 m = mag_of(bits);
                     const u32 flag = (j < n_e && m >= bd_lo && m <= bd_hi) ? 1u : 0u;
                     const u32 excl = block_exclusive_sum(flag, scan32);
@@ -1417,11 +1879,15 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
                     if (lane < kUnitChunks) run_sure[wave][lane] = 0u;
                     __builtin_amdgcn_wave_barrier();
                     const UnitWalk walk(cand, first, 1u, s_end);
-                    walk.for_each(cand, [&](bool valid, u32 i, u32 idx, u32 bits, u32, u32) {
+                    auto run_member = [&](bool valid, u32 i, u32 idx, u32 bits) {
                         const u32 m = mag_of(bits);
                         if (valid && m >= bd_lo && m <= bd_hi && idx <= I_star)
                             join(idx, [&] { atomicAdd(&run_sure[wave][i], 1u); ++my_sure; });
+                    };
+                    walk.for_each(cand, [&](bool valid, u32 i, u32 idx, u32 bits, u32, u32) {
+                        run_member(valid, i, idx, bits);
                     });
+                    walk.for_each_vector_row(cand, each_of_row(run_member));
                     __builtin_amdgcn_wave_barrier();
                     if (lane < kUnitChunks && first + lane < s_end && run_sure[wave][lane])
                         atomicAdd(&win_cnt[first + lane], run_sure[wave][lane]);
@@ -1478,7 +1944,7 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
             }
         }
     };
-    if (lists || tie_run) {
+    if (!wide && (lists || tie_run)) {
         const u32 n_b_use = lists ? n_bd : 0u;
         const bool b_lds = n_b_use <= kStageB;
         // (a run of equal magnitudes may add any number of keys: the large array then)
@@ -1621,10 +2087,11 @@ emit_body(Geom g, PhiloxSeed seed, const EncodeCtl *__restrict__ ctl,
        const u32 *__restrict__ chunk_base,
        u32 *__restrict__ out_idx, float *__restrict__ out_val, float *residual)
 {
+    __shared__ uint2 row_queue[kWalkWaves][kRowQueue];
     const u32 u = blockIdx.x * kWalkWaves + threadIdx.x / kWave;
     if (u >= g.U) return;
     const u32 lane = lane_id();
-    const Candidates cand{seg_count, s_ent, residual, g.d, g.C, g.U, ctl->dense != 0u};
+    const Candidates cand{seg_count, s_ent, residual, g.d, g.C, g.U, g.cap, ctl->dense != 0u};
     const UnitWalk walk(cand, u < g.U ? u : g.W, g.U, g.W);
     const u32 my_chunk = u + lane * g.U;
     const u32 my_base = (lane < kUnitChunks && my_chunk < g.W) ? chunk_base[my_chunk] : 0u;
@@ -1633,29 +2100,47 @@ emit_body(Geom g, PhiloxSeed seed, const EncodeCtl *__restrict__ ctl,
     const u64 below = lanes_below();
     u32 run = 0;          // winners at flat positions before this iteration
     u32 carry = 0;        // winners before the first entry of the chunk that runs into this iteration
-    walk.for_each(cand, [&](bool valid, u32 i, u32 idx, u32 bits, u32 first, u32 p0) {
+    auto wins = [&](bool valid, u32 idx, u32 bits) {
         bool win = false;
         if (valid) {
             const u32 m = mag_of(bits);
             win = m > T || (m == T && idx <= I_star);
             if (win && !g.take_all) win = pair_le(sample_key(idx, seed), idx, kcut);
         }
+        return win;
+    };
+    auto send = [&](u64 pos, u32 idx, u32 bits) {
+        if (pos < g.k) {
+            const float v = __uint_as_float(bits);
+            out_idx[pos] = idx;
+            out_val[pos] = v;
+            residual[idx] = v - v;
+        }
+    };
+    walk.for_each(cand, [&](bool valid, u32 i, u32 idx, u32 bits, u32 first, u32 p0) {
+        const bool win = wins(valid, idx, bits);
         const u64 mask = __ballot(win);
         // winners before the first entry of this lane's chunk
         const u32 at_start =
             first >= p0 ? run + popc64(mask & ((1ull << (first - p0)) - 1ull)) : carry;
         const u32 base_c = __shfl(my_base, i, kWave);
-        if (win) {
-            const u64 pos = (u64)base_c + (run + popc64(mask & below) - at_start);
-            if (pos < g.k) {
-                const float v = __uint_as_float(bits);
-                out_idx[pos] = idx;
-                out_val[pos] = v;
-                residual[idx] = v - v;
-            }
-        }
+        if (win) send((u64)base_c + (run + popc64(mask & below) - at_start), idx, bits);
         carry = __shfl(at_start, kWave - 1, kWave);
         run += popc64(mask);
+    });
+    // chunks read from the vector itself: what can be a member is gathered first,
+    // then taken 64 at a time in index order; seen counts the chunk's winners so far
+    u32 row_chunk = 0xFFFFFFFFu, seen = 0;
+    walk.for_each_vector_entry(cand, row_queue[threadIdx.x / kWave],
+                               [&](u32 bits) { return mag_of(bits) >= T; },
+                               [&](bool valid, u32 i, u32 idx, u32 bits) {
+        if (i != row_chunk) { row_chunk = i; seen = 0; }
+        const bool win = wins(valid, idx, bits);
+        const u64 mask = __ballot(win);
+        if (mask == 0ull) return;
+        const u32 base_c = __shfl(my_base, i, kWave);
+        if (win) send((u64)base_c + seen + popc64(mask & below), idx, bits);
+        seen += popc64(mask);
     });
 }
 
@@ -1727,7 +2212,7 @@ __global__ void __launch_bounds__(kFusedThreads) k_fused(Batch B, Geom g, Encode
 {
     const Member m(B);
     fused_body<kVec4, kAll>(m.grad, m.residual, g, m.seed, m.at<EncodeCtl>(L.ctl),
-                            m.at<u32>(L.partials), m.at<u32>(L.group_sums), m.at<u32>(L.seg_count),
+                            (u32)(L.zero_bytes / 4), m.at<u32>(L.partials), m.at<u32>(L.group_sums), m.at<u32>(L.seg_count),
                             m.at<uint2>(L.s_ent));
 }
 
@@ -1740,7 +2225,7 @@ __global__ void __launch_bounds__(kPickThreads) k_pick(Batch B, u32 n_rows, Geom
 __global__ void __launch_bounds__(kWalkThreads) k_classify(Batch B, Geom g, EncodeLayout L)
 {
     const Member m(B);
-    classify_body(g, m.seed, m.at<EncodeCtl>(L.ctl), m.at<u32>(L.seg_count),
+    classify_body(g, m.seed, m.at<EncodeCtl>(L.ctl), m.residual, m.at<u32>(L.seg_count),
                   m.at<uint2>(L.s_ent), m.at<u32>(L.win_cnt), m.at<u32>(L.bd_cnt),
                   m.at<u32>(L.blk_sure), m.at<u32>(L.n_m), m.at<u32>(L.n_b), m.at<u32>(L.blk_bmin),
                   m.at<u32>(L.blk_bmax), m.at<u64>(L.m_key), m.at<u32>(L.m_idx),
@@ -1750,7 +2235,8 @@ __global__ void __launch_bounds__(kWalkThreads) k_classify(Batch B, Geom g, Enco
 __global__ void __launch_bounds__(kFinThreads) k_finalize(Batch B, Geom g, EncodeLayout L)
 {
     const Member m(B);
-    finalize_body(g, m.seed, m.at<EncodeCtl>(L.ctl), m.residual, m.at<u32>(L.seg_count),
+    finalize_body(g, m.seed, m.at<EncodeCtl>(L.ctl), m.at<WideScratch>(L.wide), m.residual,
+                  m.at<u32>(L.seg_count),
                   m.at<uint2>(L.s_ent), m.at<u32>(L.win_cnt), m.at<u32>(L.bd_cnt),
                   m.at<u32>(L.blk_sure), m.at<u32>(L.n_m), m.at<u32>(L.n_b),
                   m.at<u32>(L.blk_bmin), m.at<u32>(L.blk_bmax), m.at<u64>(L.m_key),
@@ -2014,7 +2500,15 @@ static int encode_batch_impl(uint32_t n, const float *const *grad, float *const 
         }
         {
             StageScope sc(trace, RTOPK_STAGE_FINALIZE, stream);
-            k_finalize<<<dim3(1, 1, nb), kFinThreads, 0, stream>>>(B, g, L);
+            // long vectors: enough workgroups for the exact fallback over all candidates
+            // (all but the first leave at once when the short lists decide)
+            // (the kernel's workgroups are resident one per compute unit: a batch shares them)
+            unsigned fin_grid = 1u;
+            if (g.W >= kWideMinChunks) {
+                fin_grid = 256u / nb;
+                fin_grid = fin_grid > kWideBlocks ? kWideBlocks : (fin_grid < 16u ? 16u : fin_grid);
+            }
+            k_finalize<<<dim3(fin_grid, 1, nb), kFinThreads, 0, stream>>>(B, g, L);
             RTOPK_LAUNCH_CHECK();
         }
         {

@@ -236,7 +236,8 @@ def test_seed_and_step_use_all_64_bits():
 # --------------------------------------------------------------------------
 # the exact fallbacks behind the two statistical shortcuts
 # --------------------------------------------------------------------------
-@pytest.mark.parametrize("d,offset", [(5_000, 0), (70_001, 1), (300_000, 0)])
+@pytest.mark.parametrize("d,offset", [(5_000, 0), (70_001, 1), (300_000, 0), (300_001, 1),
+                                      (3_000_017, 0)])
 def test_fallback_paths_give_the_same_message(d, offset):
     """Ordinary input, but the sampled threshold estimate and/or the key window
     are made to miss: the message and the residual must not change, only the
@@ -250,11 +251,14 @@ def test_fallback_paths_give_the_same_message(d, offset):
     plain = u.gpu_encode_once(g, m, wl.r, wl.k, 99, 7, offset=offset)
     u.assert_encode_equal(plain, want, "no fallback")
     assert plain[3]["path"] == 0
+    # from 256 chunks of 1024 elements on, the exact selection over all candidates runs on
+    # many workgroups (path bit 3); shorter vectors leave it to one
+    wide = 8 if (d + 1023) // 1024 >= 256 else 0
     for force, bits in ((rt.FORCE_ESTIMATE_MISS, 3), (rt.FORCE_KEY_WINDOW_MISS, 1),
                         (rt.FORCE_ESTIMATE_MISS | rt.FORCE_KEY_WINDOW_MISS, 3)):
         got = u.gpu_encode_once(g, m, wl.r, wl.k, 99, 7, offset=offset, force=force)
         u.assert_encode_equal(got, want, f"force={force}")
-        assert got[3]["path"] == bits, got[3]
+        assert got[3]["path"] == bits | wide, got[3]
     # the request is consumed by one call
     again = u.gpu_encode_once(g, m, wl.r, wl.k, 99, 7, offset=offset)
     assert again[3]["path"] == 0
@@ -270,6 +274,117 @@ def test_fallback_paths_with_ties_and_special_cases():
         for force in (rt.FORCE_ESTIMATE_MISS, rt.FORCE_KEY_WINDOW_MISS):
             got = _u().gpu_encode_once(g, m, r, k, 5, 5, force=force)
             _u().assert_encode_equal(got, oracle.encode(g, m, r, k, 5, 5), f"r={r} k={k} f={force}")
+
+
+def test_exact_fallbacks_on_many_workgroups_long_vectors():
+    """Inputs that the statistical shortcuts cannot decide, at lengths where the
+    exact selection over all candidates is spread over the finalize kernel's
+    workgroups (path bit 3): two neighbouring magnitudes filling the vector
+    (the deciding bin holds millions of entries of two values), a few levels
+    with noise in the last bits, a vector with a period close to the sampling
+    strata; each also with the threshold estimate and the key window made to
+    miss, with r = k (no keys) and r = d (no magnitudes), misaligned, and with
+    error feedback over two steps."""
+    import paper_2005_10761_amd as rt
+    u = _u()
+    rng = np.random.default_rng(31)
+    d = 2_500_003
+    one = np.float32(1.0)
+    two = np.where(rng.random(d) < 0.5, one, np.nextafter(one, np.float32(2.0))).astype(np.float32)
+    two *= rng.choice(np.array([-1.0, 1.0], np.float32), d)
+    levels = (rng.integers(1, 4, d).astype(np.float32)
+              * (1.0 + rng.integers(0, 64, d).astype(np.float32) * np.float32(2.0 ** -23)))
+    periodic = (np.sin(np.arange(d, dtype=np.float64) * (2 * np.pi / 152.6)) ** 7).astype(np.float32)
+    cases = [("two magnitudes", two, 900_000, 100_000, 0, 0, 9),
+             ("two magnitudes, misaligned", two, 900_000, 100_000, 0, 1, 9),
+             ("two magnitudes, top-k", two, 1_300_000, 1_300_000, 0, 0, 9),
+             ("levels with noise", levels, 1_000_000, 50_000, 0, 0, None),
+             ("periodic", periodic, 25_000, 2_500, 0, 0, None),
+             ("periodic, estimate miss", periodic, 25_000, 2_500, rt.FORCE_ESTIMATE_MISS, 0, 11),
+             # (a window miss is certain before the short lists are read when k exceeds what
+             # they can add; otherwise one workgroup finds out and finishes alone: bit 0 only)
+             ("periodic, window miss", periodic, 250_000, 100_000, rt.FORCE_KEY_WINDOW_MISS, 3, 9),
+             ("periodic, window miss, small k", periodic, 25_000, 2_500, rt.FORCE_KEY_WINDOW_MISS, 0, None),
+             ("random-k, window miss", two, d, 40_000, rt.FORCE_KEY_WINDOW_MISS, 0, 11)]
+    for name, g, r, k, force, offset, want_path in cases:
+        print(f"wide: {name} d={d} r={r} k={k}", flush=True)
+        w = u.GpuWorker(d, r, k, offset=offset)
+        res = np.zeros(d, np.float32)
+        for t in range(2):
+            got = w.encode(g, 77, t, force=force)
+            oi, ov, res = oracle.encode(g, res, r, k, 77, t)
+            u.assert_encode_equal(got, (oi, ov, res), f"{name} step {t}")
+            if want_path is not None and t == 0:
+                assert w.stats["path"] == want_path, (name, w.stats)
+        del w
+
+
+def test_chunks_that_keep_more_than_their_slice_are_read_from_the_vector():
+    """A chunk of the vector owns a slice of the candidate buffer an eighth of
+    its own length; where more of its elements are candidates (a layer that
+    holds most of the top r) the later kernels read the chunk from the vector
+    itself. Regions dense in candidates next to sparse ones, ties inside the
+    dense region, a dense region at the ragged end; the ordinary path decides
+    (path 0) and the message is the oracle's."""
+    u = _u()
+    rng = np.random.default_rng(32)
+    for d, lo, hi, r, k in ((400_003, 100_000, 140_000, 50_000, 5_000),
+                            (400_003, 390_000, 400_003, 12_000, 12_000),
+                            (1_000_000, 0, 300_000, 250_000, 1_000),
+                            (70_000, 1_000, 3_000, 2_500, 300)):
+        g = (rng.standard_normal(d) * 1e-3).astype(np.float32)
+        g[lo:hi] = (rng.standard_normal(hi - lo) * 5.0).astype(np.float32)      # the hot layer
+        g[lo:hi:7] = np.float32(3.0)                                            # ties inside it
+        res = np.zeros(d, np.float32)
+        w = u.GpuWorker(d, r, k)
+        for t in range(2):
+            print(f"hot layer d={d} [{lo},{hi}) r={r} k={k} step {t}", flush=True)
+            got = w.encode(g, 5, t)
+            oi, ov, res = oracle.encode(g, res, r, k, 5, t)
+            u.assert_encode_equal(got, (oi, ov, res), f"hot layer d={d} step {t}")
+            # (in the last case all members sit in two chunks: their keys inside the window
+            # overflow one classify workgroup's list, and the one-workgroup selection decides)
+            if t == 0 and d > 100_000:
+                assert w.stats["path"] == 0, w.stats
+        del w
+
+
+def test_batch_of_members_that_all_need_the_exact_fallback():
+    """Several members of one batched call run the many-workgroup selection at
+    the same time (each on its own part of the workspace), next to members on
+    the ordinary path."""
+    import torch
+    u = _u()
+    rt = u.rt
+    dev = u.DEV
+    d, r, k = 1_200_000, 300_000, 30_000
+    rng = np.random.default_rng(33)
+    one = np.float32(1.0)
+    gs = []
+    for i in range(5):
+        if i == 2:
+            gs.append(Workload(3, d=d, r=r, k=k).gradient(0, 0))
+        else:
+            v = np.where(rng.random(d) < 0.3 + 0.1 * i, one, np.nextafter(one, np.float32(2.0)))
+            gs.append((v * rng.choice(np.array([-1.0, 1.0]), d)).astype(np.float32))
+    n = len(gs)
+    stride = rt.encode_workspace_bytes(d, r, k)
+    ws = torch.empty(n * stride, dtype=torch.uint8, device=dev)
+    ws.fill_(0xC3)
+    grads = [torch.from_numpy(g).to(dev) for g in gs]
+    resid = [torch.zeros(d, dtype=torch.float32, device=dev) for _ in range(n)]
+    out_i = [torch.full((k,), -1, dtype=torch.int32, device=dev) for _ in range(n)]
+    out_v = [torch.full((k,), float("nan"), dtype=torch.float32, device=dev) for _ in range(n)]
+    seeds = [200 + i for i in range(n)]
+    rt.encode_batch(grads, resid, r, k, seeds, 3, out_i, out_v, ws)
+    torch.cuda.synchronize()
+    for i in range(n):
+        st = rt.encode_stats(ws[i * stride:(i + 1) * stride])
+        assert st["error_flags"] == 0, (i, st)
+        assert st["path"] == (0 if i == 2 else 9), (i, st)
+        want = oracle.encode(gs[i], np.zeros(d, np.float32), r, k, seeds[i], 3)
+        got = (out_i[i].cpu().numpy().view(np.uint32), out_v[i].cpu().numpy(), resid[i].cpu().numpy())
+        u.assert_encode_equal(got, want, f"member {i}")
 
 
 # --------------------------------------------------------------------------
