@@ -818,6 +818,7 @@ template <u32 kChunks>
 struct ChunkWalk {
     u32 u, stride, excl, inc, total;
     u64 from_vector;        // bit i: the i-th chunk is read from the vector itself
+    static constexpr u32 kRowQueueSize = 512; // a power of two >= 63 entries waiting + one row of 256
 
     // chunks first, first + step, ..., at most kChunks of them and only those below n_chunks
     __device__ __forceinline__ ChunkWalk(const Candidates &cand, u32 first, u32 step, u32 n_chunks)
@@ -879,120 +880,142 @@ struct ChunkWalk {
         }
     }
 
-    // The wavefront's chunks that are read from the vector itself (they kept more
-    // candidates than their slice of S holds, or the whole vector is walked), one
-    // after the other in rows of 256 elements, four rows fetched together: lane l
-    // holds the four elements idx0 .. idx0 + 3, idx0 = row start + 4 l, with 16-byte
-    // loads where the vector's alignment allows. g(i, idx0, patterns, valid) is called
-    // by all lanes together, rows of one chunk in index order; i is the chunk's
-    // ordinal among the wavefront's chunks.
+    // Cursor over the rows of 256 elements of the wavefront's chunks that are read
+    // from the vector itself (they kept more candidates than their slice of S
+    // holds, or the whole vector is walked): lane l of a row holds the four
+    // elements idx0 .. idx0 + 3, idx0 = row start + 4 l, loaded with one 16-byte
+    // access where the vector's alignment allows.
+    struct RowCursor {
+        u64 rest;           // chunks still to come
+        u64 c0;             // first element of the current chunk
+        u32 i, len, r0;     // its ordinal among the wavefront's chunks, its length, the next row
+        bool open;
+    };
+    __device__ __forceinline__ RowCursor rows() const { return RowCursor{from_vector, 0ull, 0u, 0u, 0u, false}; }
+    // moves to the next chunk if the current one is used up; false when no chunk is left
+    __device__ __forceinline__ bool next_chunk(const Candidates &cand, RowCursor &rc) const
+    {
+        if (rc.rest == 0ull) return false;
+        rc.i = (u32)__ffsll((unsigned long long)rc.rest) - 1u;
+        rc.rest &= rc.rest - 1ull;
+        const u32 s = u + rc.i * stride;
+        rc.c0 = (u64)s * cand.C;
+        rc.len = cand.length(s);
+        rc.r0 = 0;
+        rc.open = true;
+        return true;
+    }
+    // loads the current chunk's next row (the chunk must have one left)
+    __device__ __forceinline__ void load_row(const Candidates &cand, RowCursor &rc, u32 *idx0,
+                                             u32 (&bits)[4], bool (&valid)[4]) const
+    {
+        const u32 off = rc.r0 + 4u * lane_id();
+        const bool vec16 = (reinterpret_cast<uintptr_t>(cand.a) & 15u) == 0;
+        if (vec16 && rc.r0 + kChunkQuantum <= rc.len) {
+            const f32x4 v = *reinterpret_cast<const f32x4 *>(cand.a + rc.c0 + off);
+            bits[0] = __float_as_uint(v.x); bits[1] = __float_as_uint(v.y);
+            bits[2] = __float_as_uint(v.z); bits[3] = __float_as_uint(v.w);
+#pragma unroll
+            for (u32 e = 0; e < 4; ++e) valid[e] = true;
+        } else {
+#pragma unroll
+            for (u32 e = 0; e < 4; ++e) {
+                valid[e] = off + e < rc.len;
+                bits[e] = valid[e] ? __float_as_uint(cand.a[rc.c0 + off + e]) : 0u;
+            }
+        }
+        *idx0 = (u32)rc.c0 + off;
+        rc.r0 += kChunkQuantum;
+        if (rc.r0 >= rc.len) rc.open = false;
+    }
+
+    // g(i, idx0, patterns, valid) for every such row, all lanes together, rows of one
+    // chunk in index order (rare paths: one row in flight)
     template <class G>
     __device__ __forceinline__ void for_each_vector_row(const Candidates &cand, G &&g) const
     {
-        const u32 lane = lane_id();
-        const bool vec16 = (reinterpret_cast<uintptr_t>(cand.a) & 15u) == 0;
-        for (u64 rest = from_vector; rest; rest &= rest - 1ull) {
-            const u32 i = (u32)__ffsll((unsigned long long)rest) - 1u;
-            const u32 s = u + i * stride;
-            const u64 c0 = (u64)s * cand.C;
-            const u32 len = cand.length(s);
-            for (u32 r0 = 0; r0 < len; r0 += 4 * kChunkQuantum) {
-                u32 bits[4][4];
-                bool valid[4][4];
-#pragma unroll
-                for (u32 q = 0; q < 4; ++q) {
-                    const u32 row = r0 + q * kChunkQuantum;
-                    const u32 off = row + 4u * lane;
-                    if (vec16 && row + kChunkQuantum <= len) {
-                        const f32x4 v = *reinterpret_cast<const f32x4 *>(cand.a + c0 + off);
-                        bits[q][0] = __float_as_uint(v.x); bits[q][1] = __float_as_uint(v.y);
-                        bits[q][2] = __float_as_uint(v.z); bits[q][3] = __float_as_uint(v.w);
-#pragma unroll
-                        for (u32 e = 0; e < 4; ++e) valid[q][e] = true;
-                    } else {
-#pragma unroll
-                        for (u32 e = 0; e < 4; ++e) {
-                            valid[q][e] = off + e < len;
-                            bits[q][e] = valid[q][e] ? __float_as_uint(cand.a[c0 + off + e]) : 0u;
-                        }
-                    }
-                }
-#pragma unroll
-                for (u32 q = 0; q < 4; ++q)
-                    if (r0 + q * kChunkQuantum < len)
-                        g(i, (u32)(c0 + r0 + q * kChunkQuantum) + 4u * lane, bits[q], valid[q]);
-            }
+        RowCursor rc = rows();
+        for (;;) {
+            if (!rc.open && !next_chunk(cand, rc)) break;
+            u32 idx0, bits[4];
+            bool valid[4];
+            load_row(cand, rc, &idx0, bits, valid);
+            g(rc.i, idx0, bits, valid);
         }
     }
 
     // The same chunks with the elements that keep(pattern) lets through gathered
     // first, so that the work per entry (a sampling key costs a hundred
-    // instructions) is done on full wavefronts: the rows' survivors are appended
-    // to a queue in LDS in index order (buf: kRowQueue entries owned by this
-    // wavefront) and taken from its front 64 at a time; what is left of a chunk
-    // is flushed before the next one starts. f(valid, i, index, pattern) is called
-    // by all lanes together, entries of one chunk in index order.
+    // instructions) is done on full wavefronts: a row's survivors are appended in
+    // index order to a ring in LDS (buf: kRowQueue entries owned by this
+    // wavefront) and taken from its front 64 at a time; what is left of a chunk is
+    // taken before the next chunk starts, so the ring only ever holds one chunk's
+    // entries. f(valid, i, index, pattern) is called by all lanes together (from
+    // one place: its code exists once), entries of one chunk in index order.
     template <class Keep, class F>
     __device__ __forceinline__ void for_each_vector_entry(const Candidates &cand, uint2 *buf,
                                                           Keep &&keep, F &&f) const
     {
         const u32 lane = lane_id();
         const u64 below = lanes_below();
-        u32 pending = 0, cur = 0;
-        auto drain = [&](u32 i, bool all) {
-            u32 done = 0;
-            while (done < pending && (all || pending - done >= (u32)kWave)) {
-                const u32 j = done + lane;
-                const bool v = j < pending;
-                const uint2 e = v ? buf[j] : make_uint2(0u, 0u);
-                f(v, i, e.x, e.y);
-                done += kWave;
-            }
-            if (all) {
-                pending = 0;
-            } else if (done > 0) {
-                const u32 rest = pending - done;           // fewer than 64: to the front
-                uint2 e = make_uint2(0u, 0u);
-                if (lane < rest) e = buf[done + lane];
-                wave_lds_fence();
-                if (lane < rest) buf[lane] = e;
-                pending = rest;
-            }
-            wave_lds_fence();
-        };
-        for_each_vector_row(cand, [&](u32 i, u32 idx0, const u32 (&bits)[4], const bool (&valid)[4]) {
-            if (i != cur) { drain(cur, true); cur = i; }
-            bool hit[4];
-            u64 b[4];
+        RowCursor rc = rows();
+        u32 head = 0, pending = 0, cur = 0;
+        bool flushing = false;        // the chunk has ended: empty the ring before the next one
+        for (;;) {
+            while (pending < (u32)kWave && !flushing) {
+                if (!rc.open) {
+                    if (pending != 0u) { flushing = true; break; }
+                    if (!next_chunk(cand, rc)) break;
+                    cur = rc.i;
+                }
+                u32 idx0, bits[4];
+                bool valid[4], hit[4];
+                load_row(cand, rc, &idx0, bits, valid);
+                u64 b[4];
 #pragma unroll
-            for (u32 e = 0; e < 4; ++e) {
-                hit[e] = valid[e] && keep(bits[e]);
-                b[e] = __ballot(hit[e]);
-            }
-            if ((b[0] | b[1] | b[2] | b[3]) == 0ull) return;
-            u32 p = pending + popc64(b[0] & below) + popc64(b[1] & below) + popc64(b[2] & below) +
-                    popc64(b[3] & below);
+                for (u32 e = 0; e < 4; ++e) {
+                    hit[e] = valid[e] && keep(bits[e]);
+                    b[e] = __ballot(hit[e]);
+                }
+                if ((b[0] | b[1] | b[2] | b[3]) != 0ull) {
+                    u32 p = head + pending + popc64(b[0] & below) + popc64(b[1] & below) +
+                            popc64(b[2] & below) + popc64(b[3] & below);
 #pragma unroll
-            for (u32 e = 0; e < 4; ++e)
-                if (hit[e]) buf[p++] = make_uint2(idx0 + e, bits[e]);
-            pending += popc64(b[0]) + popc64(b[1]) + popc64(b[2]) + popc64(b[3]);
+                    for (u32 e = 0; e < 4; ++e) {
+                        if (hit[e]) { buf[p & (kRowQueueSize - 1u)] = make_uint2(idx0 + e, bits[e]); ++p; }
+                    }
+                    pending += popc64(b[0]) + popc64(b[1]) + popc64(b[2]) + popc64(b[3]);
+                    wave_lds_fence();
+                }
+            }
+            if (pending == 0u) break;             // no chunk left and nothing waiting
+            const u32 take = pending < (u32)kWave ? pending : (u32)kWave;
+            const bool v = lane < take;
+            const uint2 e = v ? buf[(head + lane) & (kRowQueueSize - 1u)] : make_uint2(0u, 0u);
+            f(v, cur, e.x, e.y);
+            head = (head + take) & (kRowQueueSize - 1u);
+            pending -= take;
+            if (pending == 0u) flushing = false;
             wave_lds_fence();
-            drain(i, false);
-        });
-        drain(cur, true);
+        }
     }
 };
-constexpr u32 kRowQueue = 320;               // 63 entries carried over + one row of 256
+constexpr u32 kRowQueue = 512;               // ring of one wavefront (ChunkWalk::kRowQueueSize entries)
 
 using UnitWalk = ChunkWalk<kUnitChunks>;     // classify / emit: chunks u, u + U, u + 2U, ...
 
-// per-element form of a row callback: f(valid, i, index, pattern) four times
+// per-element form of a row callback: f(valid, i, index, pattern) for the four
+// elements of a lane, from one call site (the loop is kept rolled)
 template <class F>
 __device__ __forceinline__ auto each_of_row(F &&f)
 {
     return [&f](u32 i, u32 idx0, const u32 (&bits)[4], const bool (&valid)[4]) {
-#pragma unroll
-        for (u32 e = 0; e < 4; ++e) f(valid[e], i, idx0 + e, bits[e]);
+#pragma unroll 1
+        for (u32 e = 0; e < 4; ++e) {
+            const u32 b = e == 0 ? bits[0] : e == 1 ? bits[1] : e == 2 ? bits[2] : bits[3];
+            const bool v = e == 0 ? valid[0] : e == 1 ? valid[1] : e == 2 ? valid[2] : valid[3];
+            f(v, i, idx0 + e, b);
+        }
     };
 }
 
