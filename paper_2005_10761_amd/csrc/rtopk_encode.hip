@@ -121,14 +121,18 @@ constexpr u32 kErrBarrier = 8u;               // a workgroup gave up waiting for
 // kWideBlocks workgroups of the finalize kernel when the vector is long enough
 // to be worth it; they exchange 256-bin histograms through the workspace and
 // meet at a barrier between radix passes.
-constexpr u32 kWideBlocks = 64;
+constexpr u32 kWideBlocks = 256;              // one per compute unit, shared by the members of a batch
 constexpr u32 kWideMinChunks = 256;
-constexpr u32 kWidePasses = 24;               // 8 (magnitude, index) + 12 (key, index) + 2 fetches + slack
+constexpr u32 kWidePasses = 24;               // 8 (magnitude, index) + 12 (key, index) + slack; the last two
+                                              // `found` slots hold the two selected strings
 constexpr u32 kWideSpinLimit = 1u << 20;      // polls (about a microsecond each) before giving up
+constexpr u32 kWideCheckInLimit = 1u << 14;   // ... while the workgroups gather for the first time
+constexpr u32 kWideGo = 1u, kWideAbort = 2u;
 
 struct WideScratch {
     u32 arrived;                              // workgroups that reached a barrier, over all barriers
-    u32 pad[63];
+    u32 decision;                             // 0, kWideGo (all are resident) or kWideAbort
+    u32 pad[62];
     u32 hist[kWidePasses][256];
     u64 found[kWidePasses][2];                // the one string left under a resolved prefix
 };
@@ -1371,14 +1375,22 @@ struct Wide {
     bool alive;         // false once a barrier timed out
 };
 
+// Everything the workgroups exchange goes through device-scope atomic
+// operations (additions to the histograms, atomic stores of the few words
+// workgroup 0 reads at the end, atomic loads on the reading side), which are
+// carried out where all compute units see them. The barrier therefore only has
+// to order them: every thread waits until its own operations are acknowledged
+// (a workgroup-scope release does that) before its workgroup checks in. A
+// device-scope fence per thread, which writes back and invalidates the L2 of
+// the XCD, made a barrier of 256 workgroups cost ~100 us.
 __device__ __forceinline__ bool grid_barrier(Wide &w, u32 *lds_flag)
 {
     if (!w.alive) return false;
-    __threadfence();                               // what this thread wrote is visible device-wide
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
     ++w.epoch;
     if (threadIdx.x == 0) {
-        __hip_atomic_fetch_add(&w.ws->arrived, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add(&w.ws->arrived, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const u32 target = w.epoch * w.nblocks;
         u32 polls = 0;
         bool ok = true;
@@ -1389,10 +1401,67 @@ __device__ __forceinline__ bool grid_barrier(Wide &w, u32 *lds_flag)
         *lds_flag = ok ? 1u : 0u;
     }
     __syncthreads();
-    __threadfence();                               // what the others wrote is read from memory
     w.alive = *lds_flag != 0u;
     __syncthreads();
     return w.alive;
+}
+
+// What the selection over the grid settles: the first `bytes` bytes of the
+// rank-th smallest string (the rest of hi:lo is zero). With bytes < 12 exactly
+// ONE string starts with them, so "at or below the selected string" is the
+// same as "at or below these bytes followed by ones" (bound()), and nobody has
+// to go and fetch the rest before the next pass can start; is() recognises the
+// selected string itself when a later pass comes across it.
+struct Selected {
+    u64 hi;
+    u32 lo;
+    int bytes;
+    __device__ __forceinline__ Pair96 bound() const
+    {
+        if (bytes >= 12) return Pair96{hi, lo};
+        if (bytes > 8) return Pair96{hi, lo | ((1u << (32 - 8 * (bytes - 8))) - 1u)};
+        if (bytes == 8) return Pair96{hi, 0xFFFFFFFFu};
+        return Pair96{hi | ((1ull << (64 - 8 * bytes)) - 1ull), 0xFFFFFFFFu};
+    }
+    __device__ __forceinline__ bool is(u64 shi, u32 slo) const { return pair_matches(shi, slo, hi, lo, bytes); }
+};
+
+// Before the first barrier the workgroups of the grid make sure that ALL of
+// them are resident: every workgroup checks in; the last to arrive decides
+// "go", a workgroup that has polled kWideCheckInLimit times in vain decides
+// "abort" (compare-and-swap: one decision stands), and everybody waits for the
+// decision. After "go" every workgroup is running, so the later barriers
+// cannot wait for one that was never scheduled (two grids of two streams, each
+// holding half of the compute units, would otherwise wait for each other until
+// the poll limit). After "abort" nothing has been computed yet: the caller
+// falls back to the selection by one workgroup. Counts as the first barrier.
+__device__ __forceinline__ bool grid_check_in(Wide &w, u32 *lds_flag)
+{
+    __syncthreads();
+    ++w.epoch;
+    if (threadIdx.x == 0) {
+        const u32 mine = __hip_atomic_fetch_add(&w.ws->arrived, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
+        u32 expected = 0u;
+        if (mine == w.nblocks)
+            __hip_atomic_compare_exchange_strong(&w.ws->decision, &expected, kWideGo, __ATOMIC_RELAXED,
+                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        u32 polls = 0, d = 0;
+        while ((d = __hip_atomic_load(&w.ws->decision, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) == 0u) {
+            __builtin_amdgcn_s_sleep(32);
+            if (++polls == kWideCheckInLimit) {
+                expected = 0u;
+                __hip_atomic_compare_exchange_strong(&w.ws->decision, &expected, kWideAbort,
+                                                     __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                     __HIP_MEMORY_SCOPE_AGENT);
+            }
+            if (polls > kWideSpinLimit) { d = kWideAbort; break; }   // (cannot happen: somebody decides)
+        }
+        *lds_flag = d == kWideGo ? 1u : 0u;
+    }
+    __syncthreads();
+    const bool go = *lds_flag != 0u;
+    __syncthreads();
+    return go;
 }
 
 // for_each(f) calls f(valid, hi, lo) for every string of this workgroup's
@@ -1400,8 +1469,8 @@ __device__ __forceinline__ bool grid_barrier(Wide &w, u32 *lds_flag)
 // one). *less_hi receives the number of strings whose high 64 bits are below
 // the result's. h: 4 x 256 words of LDS.
 template <class ForEach>
-__device__ __forceinline__ Pair96 grid_select96(ForEach &&for_each, u64 rank, int first_byte, Wide &w,
-                                                u32 (*h)[256], u64 *less_hi, bool *ok)
+__device__ __forceinline__ Selected grid_select96(ForEach &&for_each, u64 rank, int first_byte, Wide &w,
+                                                  u32 (*h)[256], u64 *less_hi, bool *ok)
 {
     u64 phi = 0;
     u32 plo = 0;
@@ -1429,11 +1498,11 @@ __device__ __forceinline__ Pair96 grid_select96(ForEach &&for_each, u64 rank, in
             }
         });
         lds_barrier();
-        if (w.pass >= kWidePasses) { *ok = false; return Pair96{0, 0}; }
+        if (w.pass >= kWidePasses) { *ok = false; return Selected{0, 0, 12}; }
         u32 *gh = w.ws->hist[w.pass];
         for (u32 b = threadIdx.x; b < 256u; b += blockDim.x)
             if (h[0][b]) atomicAdd(&gh[b], h[0][b]);
-        if (!grid_barrier(w, &h[3][4])) { *ok = false; return Pair96{0, 0}; }
+        if (!grid_barrier(w, &h[3][4])) { *ok = false; return Selected{0, 0, 12}; }
         if (threadIdx.x < kWave) {
             u32 c[4];
             u32 mine = 0;
@@ -1462,7 +1531,7 @@ __device__ __forceinline__ Pair96 grid_select96(ForEach &&for_each, u64 rank, in
         }
         lds_barrier();
         ++w.pass;
-        if (h[3][3] == 0u) { *ok = false; return Pair96{0, 0}; }
+        if (h[3][3] == 0u) { *ok = false; return Selected{0, 0, 12}; }
         const u32 bin = h[3][0], in_bin = h[3][1], before = h[3][2];
         lds_barrier();
         need -= before;
@@ -1470,19 +1539,7 @@ __device__ __forceinline__ Pair96 grid_select96(ForEach &&for_each, u64 rank, in
         else plo |= bin << (24 - 8 * (j - 8));
         if (in_bin == 1u) { ++j; break; }
     }
-    if (j < 12) {
-        // exactly one string starts with the resolved bytes: whoever holds it leaves it for all
-        if (w.pass >= kWidePasses) { *ok = false; return Pair96{0, 0}; }
-        u64 *slot = w.ws->found[w.pass];
-        for_each([&](bool valid, u64 hi, u32 lo) {
-            if (valid && pair_matches(hi, lo, phi, plo, j)) { slot[0] = hi; slot[1] = (u64)lo; }
-        });
-        if (!grid_barrier(w, &h[3][4])) { *ok = false; return Pair96{0, 0}; }
-        phi = __hip_atomic_load(&slot[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        plo = (u32)__hip_atomic_load(&slot[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        ++w.pass;
-    }
-    return Pair96{phi, plo};
+    return Selected{phi, plo, j};
 }
 
 // ---------------------------------------------------------------------------
@@ -1604,6 +1661,16 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, WideScratch *wide_ws,
     if (__builtin_expect(wide, 0)) {
         // ---- exact selection over all candidates, on all workgroups of the grid
         Wide w{wide_ws, gridDim.x, 0u, 0u, true};
+        if (!grid_check_in(w, &h[3][4])) {
+            // the grid's workgroups cannot be resident together right now (another
+            // stream's grid holds compute units and waits as well): nothing has been
+            // done yet, workgroup 0 runs the selection alone below
+            if (blockIdx.x != 0u) return;
+            wide = false;
+        }
+    }
+    if (__builtin_expect(wide, 0)) {
+        Wide w{wide_ws, gridDim.x, 1u, 0u, true};
         // r == d: S only holds the coordinates inside the key window, which
         // missed: the vector itself is walked, here and by the emit kernel
         if (g.all_members) cand.dense = true;
@@ -1654,11 +1721,15 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, WideScratch *wide_ws,
         };
         auto nothing = [](u32) {};
         path = 1u | 8u;
+        // where whoever comes across a selected string in a later pass leaves it whole
+        u64 *found_t = w.ws->found[kWidePasses - 2], *found_k = w.ws->found[kWidePasses - 1];
+        const bool in_bin_only = !g.all_members && !cand.dense;
+        const u32 top = in_bin_only ? bd_hi : 0x7FFFFFFFu;
+        Selected sel_t{0ull, 0u, 12}, sel_k{0ull, 0u, 12};
+        Pair96 tbound{~0ull, 0xFFFFFFFFu}, kbound{~0ull, 0xFFFFFFFFu};
         if (!g.all_members) {
             // the r-th (magnitude desc, index asc): inside the deciding bin when pick found
             // one, over the whole vector when the estimate had kept too little
-            const bool in_bin_only = !cand.dense;
-            const u32 top = in_bin_only ? bd_hi : 0x7FFFFFFFu;
             auto each_mag = [&](auto &&f2) {
                 wide_each([&](bool valid, u32 idx, u32 bits) {
                     const u32 m = mag_of(bits);
@@ -1667,16 +1738,20 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, WideScratch *wide_ws,
                 }, nothing);
             };
             u64 less = 0;
-            const Pair96 tb = grid_select96(each_mag, in_bin_only ? need2 : g.r,
-                                            in_bin_only ? (64 - (int)bd_bits) / 8 : 4, w, h, &less, &ok);
+            sel_t = grid_select96(each_mag, in_bin_only ? need2 : g.r,
+                                  in_bin_only ? (64 - (int)bd_bits) / 8 : 4, w, h, &less, &ok);
             if (!ok) err |= kErrSelect;
-            T = top - (u32)tb.hi;
-            I_star = tb.lo;
+            tbound = sel_t.bound();
             count_greater = (in_bin_only ? c_def : 0ull) + less;
         }
+        // members: above the deciding bin, or at or below the selected string in
+        // (magnitude desc, index asc) order
         auto is_member_w = [&](u32 idx, u32 bits) {
+            if (g.all_members != 0u) return true;
             const u32 m = mag_of(bits);
-            return g.all_members != 0u || m > T || (m == T && idx <= I_star);
+            if (m > top) return true;
+            if (in_bin_only && m < bd_lo) return false;
+            return pair_le((u64)(top - m), idx, tbound);
         };
         if (!g.take_all && w.alive) {
             auto each_key = [&](auto &&f2) {
@@ -1687,25 +1762,49 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, WideScratch *wide_ws,
             };
             u64 less = 0;
             bool ok_k = true;
-            const Pair96 kb = grid_select96(each_key, g.k, 0, w, h, &less, &ok_k);
+            sel_k = grid_select96(each_key, g.k, 0, w, h, &less, &ok_k);
             if (!ok_k) err |= kErrSelect;
-            K_star = kb.hi;
-            J_star = kb.lo;
+            kbound = sel_k.bound();
         }
-        // winners per chunk (every chunk's counter is written: what classify left is stale)
+        // winners per chunk (every chunk's counter is written: what classify left is
+        // stale); the same pass leaves the two selected strings whole for workgroup 0
         if (w.alive) {
-            const Pair96 kcut{K_star, J_star};
             u32 mine = 0;
             wide_each([&](bool valid, u32 idx, u32 bits) {
-                if (valid && is_member_w(idx, bits) &&
-                    (g.take_all != 0u || pair_le(sample_key(idx, seed), idx, kcut)))
-                    ++mine;
+                if (!valid || !is_member_w(idx, bits)) return;
+                const u32 m = mag_of(bits);
+                if (sel_t.bytes < 12 && m <= top && sel_t.is((u64)(top - m), idx)) {
+                    __hip_atomic_store(&found_t[0], (u64)(top - m), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(&found_t[1], (u64)idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                if (g.take_all != 0u) { ++mine; return; }
+                const u64 key = sample_key(idx, seed);
+                if (!pair_le(key, idx, kbound)) return;
+                ++mine;
+                if (sel_k.bytes < 12 && sel_k.is(key, idx)) {
+                    __hip_atomic_store(&found_k[0], key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(&found_k[1], (u64)idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
             }, [&](u32 sc) {
                 const u32 total = wave_sum(mine);
-                if (lane == 0) win_cnt[sc] = total;
+                if (lane == 0)
+                    __hip_atomic_store(&win_cnt[sc], total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 mine = 0;
             });
             grid_barrier(w, &h[3][4]);
+        }
+        if (w.alive && blockIdx.x == 0u) {
+            Pair96 ts{sel_t.hi, sel_t.lo}, ks{sel_k.hi, sel_k.lo};
+            if (sel_t.bytes < 12) {
+                ts.hi = __hip_atomic_load(&found_t[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ts.lo = (u32)__hip_atomic_load(&found_t[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            if (sel_k.bytes < 12) {
+                ks.hi = __hip_atomic_load(&found_k[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ks.lo = (u32)__hip_atomic_load(&found_k[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            if (!g.all_members) { T = top - (u32)ts.hi; I_star = ts.lo; }
+            if (!g.take_all) { K_star = ks.hi; J_star = ks.lo; }
         }
         if (!w.alive) err |= kErrBarrier;
         if (blockIdx.x != 0u) return;
@@ -2042,7 +2141,17 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, WideScratch *wide_ws,
     for (u32 q = 0; q < kSlabs; ++q) {
         const u32 s = 4u * (q * kFinThreads + tid);
         uint4 v = make_uint4(0u, 0u, 0u, 0u);
-        if (s < g.W) v = reinterpret_cast<const uint4 *>(win_cnt)[q * kFinThreads + tid];
+        if (s < g.W) {
+            if (__builtin_expect(wide, 0)) {
+                // written by other workgroups of this grid: read where they were written
+                v.x = __hip_atomic_load(&win_cnt[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                v.y = __hip_atomic_load(&win_cnt[s + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                v.z = __hip_atomic_load(&win_cnt[s + 2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                v.w = __hip_atomic_load(&win_cnt[s + 3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else {
+                v = reinterpret_cast<const uint4 *>(win_cnt)[q * kFinThreads + tid];
+            }
+        }
         c[q][0] = v.x;
         c[q][1] = s + 1 < g.W ? v.y : 0u;
         c[q][2] = s + 2 < g.W ? v.z : 0u;
