@@ -1221,9 +1221,10 @@ classify_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
     walk.for_each(cand, [&](bool valid, u32 i, u32 idx, u32 bits, u32, u32) {
         per_entry(valid, i, idx, bits);
     });
-    walk.for_each_vector_entry(cand, row_queue[wave],
-                               [&](u32 bits) { return g.all_members != 0u || mag_of(bits) >= bd_lo; },
-                               per_entry);
+    if (__builtin_expect(walk.from_vector != 0ull, 0))
+        walk.for_each_vector_entry(cand, row_queue[wave],
+                                   [&](u32 bits) { return g.all_members != 0u || mag_of(bits) >= bd_lo; },
+                                   per_entry);
     __builtin_amdgcn_wave_barrier();
     // certain winners, and entries of the deciding bin, of each of the wavefront's chunks
     u32 mine = 0;
@@ -2263,6 +2264,7 @@ emit_body(Geom g, PhiloxSeed seed, const EncodeCtl *__restrict__ ctl,
     // chunks read from the vector itself: what can be a member is gathered first,
     // then taken 64 at a time in index order; seen counts the chunk's winners so far
     u32 row_chunk = 0xFFFFFFFFu, seen = 0;
+    if (__builtin_expect(walk.from_vector != 0ull, 0))
     walk.for_each_vector_entry(cand, row_queue[threadIdx.x / kWave],
                                [&](u32 bits) { return mag_of(bits) >= T; },
                                [&](bool valid, u32 i, u32 idx, u32 bits) {
