@@ -211,6 +211,18 @@ def measure_config(rt, torch, dev, stream, ev, wl, r, k, n, grads, steps, warmup
     ms_step, fused = timed_loop(job, torch, ev, [grads], steps)
     enc, agg, _ = split_loop(job, torch, [grads], min(steps, 5))
     st = job.check_stats(f"{wl.config.name} r={r} k={k}")
+    # the bare read-read-write stream over the same buffers, for this size's ceiling
+    rounds = 3
+    for w in range(n):
+        rt.diag_stream_add(grads[w], job.residual[w], stream)
+    a0, a1 = (torch.cuda.Event(enable_timing=True) for _ in range(2))
+    a0.record(stream)
+    for _ in range(rounds):
+        for w in range(n):
+            rt.diag_stream_add(grads[w], job.residual[w], stream)
+    a1.record(stream)
+    torch.cuda.synchronize()
+    add_ms = a0.elapsed_time(a1) / (rounds * n)
     fused_ms = mean(fused)
     res = {"d": d, "r": r, "k": k, "workers": n, "steps": steps,
            "ms_per_step": round(ms_step, 4),
@@ -219,6 +231,7 @@ def measure_config(rt, torch, dev, stream, ev, wl, r, k, n, grads, steps, warmup
            "encode_pct_hbm_peak_at_12d": round(100.0 * 12.0 * d / (enc * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2),
            "k_fused_ms": round(fused_ms, 5),
            "k_fused_frac": round(n * 12.0 * d / (fused_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+           "stream_add_frac": round(12.0 * d / (add_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
            "aggregate_us": round(agg * 1e3, 2),
            "aggregate_GBps": round(4.0 * d / (agg * 1e-3) / 1e9, 1),
            "path": st["path"], "candidates_per_vector": st["superset_size"]}

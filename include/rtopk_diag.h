@@ -69,10 +69,25 @@ int rtopk_trace_next_encode(int stage, void *ev_begin, void *ev_end);
  *   RTOPK_FORCE_KEY_WINDOW_MISS  the a-priori window around the k-th smallest
  *                                sampling key is empty: the key cut comes from
  *                                a selection over all candidates
+ *   RTOPK_FORCE_CHECK_IN_ABORT   when the exact selection over all candidates
+ *                                is about to run on many workgroups, they
+ *                                decide at check-in that they are not all
+ *                                resident (as when another stream's grid holds
+ *                                compute units and waits too): one workgroup
+ *                                runs the selection alone. Only has an effect
+ *                                together with a condition that needs the
+ *                                selection.
+ *   RTOPK_FORCE_BRACKET_LOW      the estimate's upper bound is put at its lower
+ *                                bound, as if the sample had underestimated
+ *                                the r-th largest magnitude: the threshold
+ *                                then lies above the finely binned range, in
+ *                                the one bin that holds everything above it
  * Passing 0 cancels a pending request.
  */
 #define RTOPK_FORCE_ESTIMATE_MISS 1u
 #define RTOPK_FORCE_KEY_WINDOW_MISS 2u
+#define RTOPK_FORCE_CHECK_IN_ABORT 4u
+#define RTOPK_FORCE_BRACKET_LOW 8u
 int rtopk_force_next_encode(unsigned flags);
 
 /*

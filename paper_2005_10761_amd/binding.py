@@ -315,6 +315,8 @@ def trace_next_encode(stage: int, ev_begin: int, ev_end: int) -> None:
 
 FORCE_ESTIMATE_MISS = 1
 FORCE_KEY_WINDOW_MISS = 2
+FORCE_CHECK_IN_ABORT = 4
+FORCE_BRACKET_LOW = 8
 
 
 def force_next_encode(flags: int) -> None:

@@ -22,7 +22,7 @@
 //   fused      a = g + m, stored into the residual buffer (12d bytes, the
 //              dominant kernel); entries with magnitude >= t_lo -> S, and
 //              into the workgroup's own histogram row: up to 2048 linear bins
-//              over the fine range, 256 exponent bins above it
+//              over the fine range and one bin for everything above it
 //              (every row also carries the sums over groups of 64 bins)
 //   pick       one workgroup: the group sums of all rows -> the group that
 //              holds the r-th largest magnitude; that group's bins of all
@@ -79,8 +79,8 @@
 namespace rtopk {
 
 constexpr u32 kMaxFineBins = 2048;            // linear bins over [t_lo, fine_hi]: 64 .. 2048, by r
-constexpr u32 kCoarseShift = 23;              // coarse bins above them: the 8 exponent bits
-constexpr u32 kCoarseBins = 256;
+constexpr u32 kCoarseBins = 64;               // one more group of bins, of which only the first is used:
+                                              // everything above the linear bins
 constexpr u32 kMaxBins = kMaxFineBins + kCoarseBins;
 constexpr u32 kMaxFusedBlocks = 256;          // rows of per-workgroup histograms (one per compute unit)
 constexpr u32 kCoarseSpan = 64;               // bins per group: every row also carries its group sums
@@ -147,7 +147,7 @@ struct Bins {
 
 __device__ __forceinline__ u32 bin_of(const Bins &b, u32 m)
 {
-    return m <= b.fine_hi ? (m - b.t_lo) >> b.shift : b.nfine + (m >> kCoarseShift);
+    return m <= b.fine_hi ? (m - b.t_lo) >> b.shift : b.nfine;
 }
 
 __device__ __forceinline__ void bin_range(const Bins &b, u32 bin, u32 *lo, u32 *hi)
@@ -157,10 +157,9 @@ __device__ __forceinline__ void bin_range(const Bins &b, u32 bin, u32 *lo, u32 *
         const u32 h = *lo + ((1u << b.shift) - 1u);
         *hi = h < b.fine_hi ? h : b.fine_hi;
     } else {
-        const u32 c = bin - b.nfine;
-        const u32 l = c << kCoarseShift;
-        *lo = l > b.fine_hi ? l : b.fine_hi + 1u;
-        *hi = l | ((1u << kCoarseShift) - 1u);
+        // the one bin above the linear ones
+        *lo = b.fine_hi + 1u;
+        *hi = 0x7FFFFFFFu;
     }
 }
 
@@ -200,6 +199,9 @@ struct Geom {
     u32 L;              // sampled locations
     u32 nfine;          // linear histogram bins
     u32 force_dense;    // diagnostics: make the estimate keep nothing, as if the sample had misled it
+    u32 force_abort;    // diagnostics: the workgroups of the wide selection decide "abort" at check-in
+    u32 force_low;      // diagnostics: the bracket's upper end is put at its lower end, as if the sample
+                        // had underestimated the r-th largest magnitude: it then lies above the linear bins
     u32 take_all;       // k == r: every member is sent, keys are never looked at
     u32 all_members;    // r == d: every coordinate is a member, magnitudes are never looked at
     u32 k_nlz;          // leading zeros of K_hi - K_lo
@@ -562,6 +564,7 @@ estimate_body(const u32 *__restrict__ samples, Geom g, EncodeCtl *ctl)
         u32 t_lo = lo_all ? 0u : (bin_s[0] << 19);
         u32 t_hi = (bin_s[1] << 19) | 0x7FFFFu;
         if (g.force_dense) t_lo = 0x7FFFFFFFu;
+        if (g.force_low) t_hi = t_lo;
         if (t_hi < t_lo) t_hi = t_lo;
         u32 shift = 0;
         while (((t_hi - t_lo) >> shift) >= g.nfine) ++shift;
@@ -660,6 +663,7 @@ fused_body(const float *__restrict__ grad, float *__restrict__ residual, Geom g,
     }
 
     const u32 wave_stride = gridDim.x * kFusedWaves;
+    u32 n_above = 0;        // this wavefront's candidates above the linear bins
     for (u32 w = blockIdx.x * kFusedWaves + threadIdx.x / kWave; w < g.W; w += wave_stride) {
         const u64 c0 = (u64)w * g.C;
         const u64 c1 = c0 + g.C < g.d ? c0 + g.C : g.d;
@@ -676,7 +680,12 @@ fused_body(const float *__restrict__ grad, float *__restrict__ residual, Geom g,
                 } else {
                     const u32 m = mag_of(bits[e]);
                     hit[e] = valid[e] && m >= bins.t_lo;
-                    if (hit[e]) atomicAdd(&h[bin_of(bins, m)], 1u);
+                    // candidates inside the bracket are counted bin by bin; the ones above it
+                    // (certain members, often most of the candidates and crowded in a few
+                    // exponents) only need their number: a popcount instead of LDS additions
+                    const bool fine = hit[e] && m <= bins.fine_hi;
+                    if (fine) atomicAdd(&h[(m - bins.t_lo) >> bins.shift], 1u);
+                    n_above += popc64(__ballot(hit[e] && !fine));
                 }
             }
             append_hits<kVec4>(bits, hit, base, run, my_ent, g.cap);
@@ -748,6 +757,7 @@ fused_body(const float *__restrict__ grad, float *__restrict__ residual, Geom g,
         if (lane_id() == 0) seg_count[chunk_slot(w, g.U)] = run;
     }
     if (kAll) return;
+    if (lane_id() == 0 && n_above != 0u) atomicAdd(&h[bins.nfine], n_above);
     __syncthreads();
     // The workgroup's histogram goes out as one dense row with plain stores:
     // device-wide atomics here, however few, slow the whole stream down. With
@@ -1662,7 +1672,7 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, WideScratch *wide_ws,
     if (__builtin_expect(wide, 0)) {
         // ---- exact selection over all candidates, on all workgroups of the grid
         Wide w{wide_ws, gridDim.x, 0u, 0u, true};
-        if (!grid_check_in(w, &h[3][4])) {
+        if (g.force_abort != 0u || !grid_check_in(w, &h[3][4])) {
             // the grid's workgroups cannot be resident together right now (another
             // stream's grid holds compute units and waits as well): nothing has been
             // done yet, workgroup 0 runs the selection alone below
@@ -2167,13 +2177,17 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, WideScratch *wide_ws,
     }
     __syncthreads();
     {
-        constexpr u32 n = kSlabs * kFinWaves;          // 128 partial sums, two per lane of wave 0
-        static_assert(n == 2 * kWave, "two partial sums per lane");
+        constexpr u32 n = kSlabs * kFinWaves;          // partial sums, a few per lane of wave 0
+        constexpr u32 kEach = n / kWave;
+        static_assert(n % kWave == 0 && kEach >= 1, "whole partial sums per lane");
         if (wave == 0) {
-            const u32 a0 = scan32[2 * lane], a1 = scan32[2 * lane + 1];
-            const u32 xi = wave_inclusive_sum(a0 + a1);
-            scan32[2 * lane] = xi - (a0 + a1);
-            scan32[2 * lane + 1] = xi - a1;
+            u32 part[kEach], sum = 0;
+#pragma unroll
+            for (u32 j = 0; j < kEach; ++j) { part[j] = scan32[kEach * lane + j]; sum += part[j]; }
+            const u32 xi = wave_inclusive_sum(sum);
+            u32 running = xi - sum;
+#pragma unroll
+            for (u32 j = 0; j < kEach; ++j) { scan32[kEach * lane + j] = running; running += part[j]; }
             if (lane == kWave - 1) scan32[n] = xi;
         }
     }
@@ -2519,7 +2533,8 @@ int fused_grid_limit(unsigned *out)
 
 extern "C" int rtopk_force_next_encode(unsigned flags)
 {
-    if (flags & ~(unsigned)(RTOPK_FORCE_ESTIMATE_MISS | RTOPK_FORCE_KEY_WINDOW_MISS))
+    if (flags & ~(unsigned)(RTOPK_FORCE_ESTIMATE_MISS | RTOPK_FORCE_KEY_WINDOW_MISS |
+                            RTOPK_FORCE_CHECK_IN_ABORT | RTOPK_FORCE_BRACKET_LOW))
         return RTOPK_EINVAL;
     g_force = flags;
     return RTOPK_OK;
@@ -2565,6 +2580,8 @@ static int encode_batch_impl(uint32_t n, const float *const *grad, float *const 
     // honoured on the r == d path too (it then walks the vector itself)
     if (force & RTOPK_FORCE_ESTIMATE_MISS) g.all_members = 0u;
     if (force & RTOPK_FORCE_ESTIMATE_MISS) g.force_dense = 1u;
+    if (force & RTOPK_FORCE_CHECK_IN_ABORT) g.force_abort = 1u;
+    if (force & RTOPK_FORCE_BRACKET_LOW) g.force_low = 1u;
     if ((force & RTOPK_FORCE_KEY_WINDOW_MISS) && !g.take_all) {
         g.K_lo = g.K_hi = 0;       // a window that holds no key: the exact selection must run
         g.k_nlz = 63u;

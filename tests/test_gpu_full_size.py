@@ -267,6 +267,28 @@ def test_full_size_run_of_equal_magnitudes_at_the_threshold():
         del w
 
 
+def test_periodic_vector_does_not_mislead_the_sampled_estimate():
+    """d = 2^24 with a period close to the length of the sampling strata (1024
+    elements): the sample's offsets inside the strata are hashed from (stratum,
+    seed, step), so a periodic layout is sampled fairly: the ordinary path
+    decides (path 0) for every worker and step, and the message is the oracle's."""
+    u = _u()
+    d = 1 << 24
+    r, k = 100_000, 10_000
+    i = np.arange(d, dtype=np.float64)
+    g = (np.sin(i * (2 * np.pi / 1024.0)) ** 9 + 0.05 * np.sin(i * (2 * np.pi / 37.0))).astype(np.float32)
+    for seed in (1, 2):
+        w = u.GpuWorker(d, r, k)
+        res = np.zeros(d, np.float32)
+        for t in range(2):
+            print(f"periodic d={d} seed={seed} step={t}", flush=True)
+            got = w.encode(g, seed, t)
+            oi, ov, res = oracle.encode(g, res, r, k, seed, t)
+            u.assert_encode_equal(got, (oi, ov, res), f"periodic seed {seed} step {t}")
+            assert w.stats["path"] == 0, w.stats
+        del w
+
+
 def test_largest_vector_the_index_type_allows():
     """d = 2^32 - 1, the largest length a 32-bit index addresses (chunks of
     131072 elements, 51 GB streamed). Inputs are drawn on the device; what the

@@ -259,6 +259,9 @@ def test_fallback_paths_give_the_same_message(d, offset):
         got = u.gpu_encode_once(g, m, wl.r, wl.k, 99, 7, offset=offset, force=force)
         u.assert_encode_equal(got, want, f"force={force}")
         assert got[3]["path"] == bits | wide, got[3]
+    # the bracket ends below the threshold: exact by whichever path the sizes take
+    got = u.gpu_encode_once(g, m, wl.r, wl.k, 99, 7, offset=offset, force=rt.FORCE_BRACKET_LOW)
+    u.assert_encode_equal(got, want, "bracket too low")
     # the request is consumed by one call
     again = u.gpu_encode_once(g, m, wl.r, wl.k, 99, 7, offset=offset)
     assert again[3]["path"] == 0
@@ -305,7 +308,18 @@ def test_exact_fallbacks_on_many_workgroups_long_vectors():
              # they can add; otherwise one workgroup finds out and finishes alone: bit 0 only)
              ("periodic, window miss", periodic, 250_000, 100_000, rt.FORCE_KEY_WINDOW_MISS, 3, 9),
              ("periodic, window miss, small k", periodic, 25_000, 2_500, rt.FORCE_KEY_WINDOW_MISS, 0, None),
-             ("random-k, window miss", two, d, 40_000, rt.FORCE_KEY_WINDOW_MISS, 0, 11)]
+             ("random-k, window miss", two, d, 40_000, rt.FORCE_KEY_WINDOW_MISS, 0, 11),
+             # the workgroups decide at check-in that they are not all resident: one of
+             # them runs the selection alone (bit 0 without bit 3)
+             ("estimate miss, check-in aborted", periodic, 25_000, 2_500,
+              rt.FORCE_ESTIMATE_MISS | rt.FORCE_CHECK_IN_ABORT, 0, 3),
+             ("window miss, check-in aborted", periodic, 250_000, 100_000,
+              rt.FORCE_KEY_WINDOW_MISS | rt.FORCE_CHECK_IN_ABORT, 0, 1),
+             # the bracket ends below the r-th largest magnitude: it lies in the one bin
+             # that holds everything above the linear bins
+             ("bracket too low", levels, 1_000_000, 50_000, rt.FORCE_BRACKET_LOW, 0, None),
+             ("bracket too low, periodic", periodic, 250_000, 100_000, rt.FORCE_BRACKET_LOW, 1, 9),
+             ("bracket too low, top-k", periodic, 30_000, 30_000, rt.FORCE_BRACKET_LOW, 0, 9)]
     for name, g, r, k, force, offset, want_path in cases:
         print(f"wide: {name} d={d} r={r} k={k}", flush=True)
         w = u.GpuWorker(d, r, k, offset=offset)
