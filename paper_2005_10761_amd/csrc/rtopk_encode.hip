@@ -4,11 +4,13 @@
 // (12d bytes). All cross-kernel state lives in the caller's workspace.
 //
 // The vector is cut into W short contiguous chunks, and every chunk owns a
-// slice of the candidate buffer S as long as the chunk itself. The wavefront
-// that streams a chunk appends the entries it keeps to the chunk's slice in
-// index order and finally stores how many it kept. S is therefore ordered by
-// index without any cross-workgroup scan, ticket or fence, and a slice can
-// never overflow. Later kernels walk S chunk by chunk; each of their
+// slice of the candidate buffer S an eighth as long as the chunk (one byte of
+// workspace per element). The wavefront that streams a chunk appends the
+// entries it keeps to the chunk's slice in index order and finally stores how
+// many it kept. S is therefore ordered by index without any cross-workgroup
+// scan, ticket or fence. A chunk that keeps more than its slice holds only
+// counts on; the later kernels read such a chunk from the residual buffer,
+// which holds a by then. Later kernels walk S chunk by chunk; each of their
 // wavefronts takes every U-th chunk, so that a region of the vector that is
 // dense in candidates is shared by all wavefronts.
 //
@@ -42,7 +44,8 @@
 //              rank in index order and is located from the per-chunk counts.
 //              When a short list overflowed otherwise or the key window
 //              missed, the same quantities are found by radix selection over
-//              all of S instead (slow, exact)
+//              all of S instead (exact; on all workgroups of the kernel's
+//              grid when the vector is long, see grid_select96)
 //   emit       entries of S that are members and winners -> the message in
 //              index order, starting at the chunk's prefix; residual at the
 //              sent positions <- a - a
@@ -63,10 +66,12 @@
 // What the hardware punishes shaped this: a device-scope fence inside a
 // kernel costs tens of microseconds once a few hundred workgroups execute
 // one, atomics on a single address retire at about one per 12 ns, and
-// atomics on one 64-byte line queue behind each other too. So no kernel here
-// uses a fence, a ticket or a "last workgroup out" protocol; workgroups never
-// wait for each other; histograms are accumulated in LDS and stored as plain
-// rows; global atomics only go to per-chunk counters.
+// atomics on one 64-byte line queue behind each other too. So on the ordinary
+// path no kernel uses a fence, a ticket or a "last workgroup out" protocol and
+// workgroups never wait for each other; histograms are accumulated in LDS and
+// stored as plain rows; global atomics only go to per-chunk counters. Only the
+// rare exact selection over all candidates lets the workgroups of one grid
+// meet at barriers, and those have no device-scope fence (grid_barrier).
 #include "rtopk_common.h"
 #include "../../include/rtopk.h"
 #include "../../include/rtopk_diag.h"
