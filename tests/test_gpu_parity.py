@@ -1127,6 +1127,43 @@ def test_two_streams_with_their_own_workspaces_do_not_disturb_each_other():
             ms[w] = want[2]
 
 
+def test_exact_fallbacks_of_three_streams_at_once():
+    """Three streams force the selection over all candidates at the same time.
+    Each call's finalize grid wants every compute unit; the grids first agree
+    among their own workgroups whether all of them are running, and a grid that
+    cannot get there falls back to one workgroup. Whichever way each call goes,
+    its message is the oracle's."""
+    import torch
+    u = _u()
+    rt = u.rt
+    dev = u.DEV
+    d = 1_500_000
+    wl = Workload(3, d=d)
+    r, k = wl.r, wl.k
+    n = 3
+    streams = [torch.cuda.Stream(device=dev) for _ in range(n)]
+    gs = [wl.gradient(w, 0) for w in range(n)]
+    ms = [np.zeros(d, np.float32) for _ in range(n)]
+    grads = [torch.from_numpy(g).to(dev) for g in gs]
+    resid = [torch.zeros(d, dtype=torch.float32, device=dev) for _ in range(n)]
+    ws = [torch.empty(rt.encode_workspace_bytes(d, r, k), dtype=torch.uint8, device=dev) for _ in range(n)]
+    oi = [torch.empty(k, dtype=torch.int32, device=dev) for _ in range(n)]
+    ov = [torch.empty(k, dtype=torch.float32, device=dev) for _ in range(n)]
+    torch.cuda.synchronize()
+    for t, force in enumerate((rt.FORCE_KEY_WINDOW_MISS, rt.FORCE_ESTIMATE_MISS)):
+        for w in range(n):                                   # enqueue all before any finishes
+            rt.force_next_encode(force)
+            rt.encode(grads[w], resid[w], r, k, 7 + w, t, oi[w], ov[w], ws[w], stream=streams[w])
+        torch.cuda.synchronize()
+        for w in range(n):
+            st = rt.encode_stats(ws[w])
+            assert st["error_flags"] == 0 and st["path"] & 1, st
+            want = oracle.encode(gs[w], ms[w], r, k, 7 + w, t)
+            got = (oi[w].cpu().numpy().view(np.uint32), ov[w].cpu().numpy(), resid[w].cpu().numpy())
+            u.assert_encode_equal(got, want, f"step {t} stream {w} path {st['path']}")
+            ms[w] = want[2]
+
+
 def test_test_hooks_belong_to_the_calling_host_thread():
     """rtopk_force_next_encode (like rtopk_trace_next_encode) is remembered per
     host thread: a request made on one thread must not reach another thread's
