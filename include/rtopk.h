@@ -97,7 +97,15 @@ int rtopk_aggregate_workspace_bytes(uint64_t d, uint32_t n, uint64_t k, uint64_t
  *            eighth of its elements as 8-byte candidates; a chunk that keeps
  *            more is read from the residual buffer itself) plus about 10 MB
  *            of histograms, lists and counters; contents on entry are
- *            irrelevant, contents on return unspecified
+ *            irrelevant, contents on return unspecified but for its first
+ *            32-bit word: once the call's kernels have run it holds the
+ *            call's error flags, 0 when the message is valid, non-zero when
+ *            an internal consistency check failed (a selection found no
+ *            element of its rank, the winners did not add up to k, a bounded
+ *            wait inside a kernel ran out) and the outputs must be discarded.
+ *            A caller that wants to know without stopping the stream copies
+ *            that word asynchronously; no input in the domain above is known
+ *            to set it
  * stream     hipStream_t
  */
 int rtopk_encode(const float *grad, float *residual,
@@ -121,8 +129,9 @@ int rtopk_encode(const float *grad, float *residual,
  *            members may share or overlap a residual or an output buffer.
  * seed       HOST array of n seeds
  * workspace  device, 256-byte aligned, >= n * rtopk_encode_workspace_bytes(d,r,k);
- *            member i uses the i-th slice of that size, and rtopk_encode_stats
- *            on the slice's address reports on member i
+ *            member i uses the i-th slice of that size (its first word holds
+ *            member i's error flags), and rtopk_encode_stats on the slice's
+ *            address reports on member i
  */
 int rtopk_encode_batch(uint32_t n,
                        const float *const *grad, float *const *residual,

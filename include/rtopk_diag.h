@@ -63,7 +63,8 @@ int rtopk_trace_next_encode(int stage, void *ev_begin, void *ev_end);
  * Test hook: the NEXT rtopk_encode issued from the calling host thread behaves
  * as if one of its two statistical shortcuts had failed, so that the exact
  * fallbacks behind them can be exercised on ordinary inputs; the request is
- * then forgotten. The results must not change, only rtopk_encode_stats.path.
+ * then forgotten. The results must not change, only rtopk_encode_stats.path
+ * (RTOPK_FORCE_BARRIER_TIMEOUT excepted, see there).
  *   RTOPK_FORCE_ESTIMATE_MISS    the sampled threshold estimate keeps no
  *                                candidates: the vector itself is walked
  *   RTOPK_FORCE_KEY_WINDOW_MISS  the a-priori window around the k-th smallest
@@ -82,12 +83,21 @@ int rtopk_trace_next_encode(int stage, void *ev_begin, void *ev_end);
  *                                the r-th largest magnitude: the threshold
  *                                then lies above the finely binned range, in
  *                                the one bin that holds everything above it
+ *   RTOPK_FORCE_BARRIER_TIMEOUT  (an error path, not a fallback) the bounded
+ *                                waits between the workgroups of the
+ *                                many-workgroup selection give up at their
+ *                                first poll: every kernel still ends normally,
+ *                                error_flags reports bit 3, and the outputs of
+ *                                that call are invalid. Only has an effect
+ *                                together with a condition that needs the
+ *                                selection on a vector of 256 chunks or more.
  * Passing 0 cancels a pending request.
  */
 #define RTOPK_FORCE_ESTIMATE_MISS 1u
 #define RTOPK_FORCE_KEY_WINDOW_MISS 2u
 #define RTOPK_FORCE_CHECK_IN_ABORT 4u
 #define RTOPK_FORCE_BRACKET_LOW 8u
+#define RTOPK_FORCE_BARRIER_TIMEOUT 16u
 int rtopk_force_next_encode(unsigned flags);
 
 /*

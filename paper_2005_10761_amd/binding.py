@@ -317,6 +317,7 @@ FORCE_ESTIMATE_MISS = 1
 FORCE_KEY_WINDOW_MISS = 2
 FORCE_CHECK_IN_ABORT = 4
 FORCE_BRACKET_LOW = 8
+FORCE_BARRIER_TIMEOUT = 16
 
 
 def force_next_encode(flags: int) -> None:

@@ -77,6 +77,7 @@
 #include "../../include/rtopk_diag.h"
 
 #include <math.h>
+#include <cstddef>
 #include <mutex>
 #include <type_traits>
 #include <vector>
@@ -192,6 +193,9 @@ struct EncodeCtl {
     u64 count_greater, ties;
 };
 
+// (the error word is the first word of the workspace: callers may read it there)
+static_assert(offsetof(EncodeCtl, err) == 0, "the error flags lead the control block");
+
 // Geometry and sampling window: a pure function of (d, r, k), computed on the host.
 struct Geom {
     u64 d, r, k;
@@ -205,6 +209,7 @@ struct Geom {
     u32 nfine;          // linear histogram bins
     u32 force_dense;    // diagnostics: make the estimate keep nothing, as if the sample had misled it
     u32 force_abort;    // diagnostics: the workgroups of the wide selection decide "abort" at check-in
+    u32 force_timeout;  // diagnostics: the barriers of the wide selection give up at their first poll
     u32 force_low;      // diagnostics: the bracket's upper end is put at its lower end, as if the sample
                         // had underestimated the r-th largest magnitude: it then lies above the linear bins
     u32 take_all;       // k == r: every member is sent, keys are never looked at
@@ -1394,6 +1399,7 @@ struct Wide {
     u32 epoch;          // barriers passed
     u32 pass;           // histogram / fetch slots used
     bool alive;         // false once a barrier timed out
+    u32 spin_limit;     // polls before a workgroup gives up at a barrier
 };
 
 // Everything the workgroups exchange goes through device-scope atomic
@@ -1417,7 +1423,7 @@ __device__ __forceinline__ bool grid_barrier(Wide &w, u32 *lds_flag)
         bool ok = true;
         while (__hip_atomic_load(&w.ws->arrived, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
             __builtin_amdgcn_s_sleep(32);
-            if (++polls > kWideSpinLimit) { ok = false; break; }
+            if (++polls > w.spin_limit) { ok = false; break; }
         }
         *lds_flag = ok ? 1u : 0u;
     }
@@ -1681,7 +1687,7 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, WideScratch *wide_ws,
     }
     if (__builtin_expect(wide, 0)) {
         // ---- exact selection over all candidates, on all workgroups of the grid
-        Wide w{wide_ws, gridDim.x, 0u, 0u, true};
+        Wide w{wide_ws, gridDim.x, 0u, 0u, true, kWideSpinLimit};
         if (g.force_abort != 0u || !grid_check_in(w, &h[3][4])) {
             // the grid's workgroups cannot be resident together right now (another
             // stream's grid holds compute units and waits as well): nothing has been
@@ -1691,7 +1697,9 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, WideScratch *wide_ws,
         }
     }
     if (__builtin_expect(wide, 0)) {
-        Wide w{wide_ws, gridDim.x, 1u, 0u, true};
+        // (diagnostics: with no patience at all the barriers time out, the kernel ends
+        // with the error flag set and every workgroup still leaves normally)
+        Wide w{wide_ws, gridDim.x, 1u, 0u, true, g.force_timeout != 0u ? 0u : kWideSpinLimit};
         // r == d: S only holds the coordinates inside the key window, which
         // missed: the vector itself is walked, here and by the emit kernel
         if (g.all_members) cand.dense = true;
@@ -2545,7 +2553,8 @@ int fused_grid_limit(unsigned *out)
 extern "C" int rtopk_force_next_encode(unsigned flags)
 {
     if (flags & ~(unsigned)(RTOPK_FORCE_ESTIMATE_MISS | RTOPK_FORCE_KEY_WINDOW_MISS |
-                            RTOPK_FORCE_CHECK_IN_ABORT | RTOPK_FORCE_BRACKET_LOW))
+                            RTOPK_FORCE_CHECK_IN_ABORT | RTOPK_FORCE_BRACKET_LOW |
+                            RTOPK_FORCE_BARRIER_TIMEOUT))
         return RTOPK_EINVAL;
     g_force = flags;
     return RTOPK_OK;
@@ -2593,6 +2602,7 @@ static int encode_batch_impl(uint32_t n, const float *const *grad, float *const 
     if (force & RTOPK_FORCE_ESTIMATE_MISS) g.force_dense = 1u;
     if (force & RTOPK_FORCE_CHECK_IN_ABORT) g.force_abort = 1u;
     if (force & RTOPK_FORCE_BRACKET_LOW) g.force_low = 1u;
+    if (force & RTOPK_FORCE_BARRIER_TIMEOUT) g.force_timeout = 1u;
     if ((force & RTOPK_FORCE_KEY_WINDOW_MISS) && !g.take_all) {
         g.K_lo = g.K_hi = 0;       // a window that holds no key: the exact selection must run
         g.k_nlz = 63u;

@@ -44,6 +44,8 @@ class GpuWorker:
             rt.force_next_encode(force)
         rt.encode(self.grad, self.residual, r, k, seed, step, self.idx, self.val, self.ws)
         st = rt.encode_stats(self.ws)
+        # the error flags are also the first word of the workspace
+        assert int(self.ws[:4].view(torch.int32).item()) == st["error_flags"], st
         if check_stats:
             assert st["error_flags"] == 0, st
         self.stats = st

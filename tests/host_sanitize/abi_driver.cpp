@@ -99,7 +99,7 @@ int main()
     EXPECT(rtopk_diag_stream_add(fake, fake, 100, nullptr) == RTOPK_EINVAL);
     EXPECT(rtopk_diag_stream_add(fake, reinterpret_cast<float *>(0x100004), 100, nullptr) == RTOPK_EINVAL);
     EXPECT(rtopk_force_next_encode(64u) == RTOPK_EINVAL);
-    EXPECT(rtopk_force_next_encode(RTOPK_FORCE_BRACKET_LOW) == RTOPK_OK);
+    EXPECT(rtopk_force_next_encode(RTOPK_FORCE_BRACKET_LOW | RTOPK_FORCE_BARRIER_TIMEOUT) == RTOPK_OK);
     EXPECT(rtopk_force_next_encode(RTOPK_FORCE_CHECK_IN_ABORT | RTOPK_FORCE_ESTIMATE_MISS) == RTOPK_OK);
     EXPECT(rtopk_force_next_encode(RTOPK_FORCE_KEY_WINDOW_MISS) == RTOPK_OK);
     EXPECT(rtopk_force_next_encode(0) == RTOPK_OK);

@@ -1164,6 +1164,28 @@ def test_exact_fallbacks_of_three_streams_at_once():
             ms[w] = want[2]
 
 
+def test_a_barrier_that_gives_up_ends_the_call_with_the_error_flag():
+    """Failure handling of the many-workgroup selection, forced from the host:
+    its bounded waits give up at once. Every kernel still ends, the error flag
+    says that the outputs are invalid (in the statistics and in the first word
+    of the workspace), and the next call on the same buffers is clean again."""
+    u = _u()
+    rt = u.rt
+    d = 1_500_000
+    wl = Workload(3, d=d)
+    g = wl.gradient(0, 0)
+    w = u.GpuWorker(d, wl.r, wl.k)
+    w.encode(g, 5, 0, check_stats=False,
+             force=rt.FORCE_KEY_WINDOW_MISS | rt.FORCE_BARRIER_TIMEOUT)
+    assert w.stats["error_flags"] & 8, w.stats
+    # a fresh residual (the failed call's is invalid), the same workspace
+    w.residual.zero_()
+    got = w.encode(g, 5, 0)
+    want = oracle.encode(g, np.zeros(d, np.float32), wl.r, wl.k, 5, 0)
+    u.assert_encode_equal(got, want, "after a failed call")
+    assert w.stats["error_flags"] == 0 and w.stats["path"] == 0, w.stats
+
+
 def test_test_hooks_belong_to_the_calling_host_thread():
     """rtopk_force_next_encode (like rtopk_trace_next_encode) is remembered per
     host thread: a request made on one thread must not reach another thread's
