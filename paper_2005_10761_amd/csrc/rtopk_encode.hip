@@ -1627,18 +1627,25 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, WideScratch *wide_ws,
     const u64 c_def = ctl->c_def;
     const bool overflow = ctl->overflow != 0u, overflow_m = ctl->overflow_m != 0u;
     if (tid == 0) { extra_m = 0u; sure_extra = 0u; gt_extra = 0ull; run_found = 0u; }
-    // the three totals with one barrier (every workgroup of the grid needs them to
-    // decide whether it stays; the prefix sums follow for the one that does)
-    u32 n_m0, n_bd;
+    // The three totals (every workgroup of the grid needs them to decide whether
+    // it stays) and, from the same partial sums, where this thread's classify
+    // workgroup's entries start in the two lists: one exchange, every wavefront
+    // adds up the sixteen partial sums for itself.
+    u32 n_m0, n_bd, em, eb;
     u64 sure_walk;
     {
-        const u32 wm = wave_sum(vm), wb = wave_sum(vb), wsure = wave_sum(vs);
-        if (lane == 0) { scan32[wave] = wm; scan32[kFinWaves + wave] = wb; scan32[2 * kFinWaves + wave] = wsure; }
+        const u32 im = wave_inclusive_sum(vm), ib = wave_inclusive_sum(vb), wsure = wave_sum(vs);
+        if (lane == kWave - 1) { scan32[wave] = im; scan32[kFinWaves + wave] = ib; scan32[2 * kFinWaves + wave] = wsure; }
         static_assert(3 * kFinWaves <= kSlabs * kFinWaves + 1, "room for three partial sums per wavefront");
+        static_assert(kFinWaves <= kWave, "one lane per wavefront's partial sum");
         lds_barrier();
-        n_m0 = wave_sum(lane < kFinWaves ? scan32[lane] : 0u);
-        n_bd = wave_sum(lane < kFinWaves ? scan32[kFinWaves + lane] : 0u);
+        const u32 pm = lane < kFinWaves ? scan32[lane] : 0u;
+        const u32 pb = lane < kFinWaves ? scan32[kFinWaves + lane] : 0u;
+        n_m0 = wave_sum(pm);
+        n_bd = wave_sum(pb);
         sure_walk = wave_sum(lane < kFinWaves ? scan32[2 * kFinWaves + lane] : 0u);
+        em = wave_sum(lane < wave ? pm : 0u) + im - vm;
+        eb = wave_sum(lane < wave ? pb : 0u) + ib - vb;
         lds_barrier();
     }
 
@@ -1842,12 +1849,6 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, WideScratch *wide_ws,
         if (g.all_members && tid == 0) ctl->dense = 1u;
     }
 
-    // where this thread's classify workgroup's entries start in the lists
-    u32 em = 0, eb = 0;
-    if (!wide && (lists || tie_run)) {
-        em = block_exclusive_sum(vm, scan32);
-        eb = block_exclusive_sum(vb, scan32);
-    }
     // The short-list path. It is compiled twice: once with both lists in LDS
     // (the usual case; the compiler then knows the address space of every list
     // access and overlaps the loads that fill the lists) and once with the
