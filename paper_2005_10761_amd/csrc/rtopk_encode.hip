@@ -101,17 +101,25 @@ constexpr u32 kNoSample = 0xFFFFFFFFu;
 constexpr u32 kChunkQuantum = 256;            // one wavefront iteration: 64 lanes x 4 elements
 constexpr u32 kMinChunk = 4 * kChunkQuantum;  // short vectors: chunks of four iterations
 constexpr u32 kTargetChunks = 32768;          // short chunks, dealt round-robin to the wavefronts
-constexpr u32 kMaxUnits = 4096;               // wavefronts of classify / emit
+constexpr u32 kMaxUnits = 4096;               // wavefronts of classify / emit (per vector)
 constexpr u32 kUnitChunks = kTargetChunks / kMaxUnits;   // chunks one of them walks, at most
+// In a batch of several vectors the two walking kernels are bound by the
+// instructions they issue, a good part of them per wavefront rather than per
+// entry: half as many wavefronts then walk twice as many chunks each (eight
+// vectors of 25.6 M elements: 23.5 and 20.9 instead of 28 and 23.5 us; one
+// vector alone would pay a microsecond in each kernel).
+constexpr u32 kBatchUnits = 2048;
+constexpr u32 kBatchMembers = 4;              // ... from this many members per launch on
+constexpr u32 kUnitChunksMax = kTargetChunks / kBatchUnits;
 constexpr u32 kWalkThreads = 256;             // fused / classify / emit workgroups: 4 wavefronts
 constexpr u32 kWalkWaves = kWalkThreads / kWave;
 constexpr u32 kMaxWalkBlocks = kMaxUnits / kWalkWaves;
 
-// The numbers of candidates kept per chunk are stored unit by unit: the
-// kUnitChunks chunks u, u + U, u + 2U, ... that one walking wavefront takes lie
-// next to each other, so it reads them as one 32-byte piece instead of
-// kUnitChunks separate cache lines.
-__host__ __device__ inline u32 chunk_slot(u32 s, u32 U) { return (s % U) * kUnitChunks + s / U; }
+// The numbers of candidates kept per chunk are stored unit by unit: the UC
+// chunks u, u + U, u + 2U, ... that one walking wavefront takes lie next to
+// each other, so it reads them as one 32- or 64-byte piece instead of UC
+// separate cache lines.
+__host__ __device__ inline u32 chunk_slot(u32 s, u32 U, u32 UC) { return (s % U) * UC + s / U; }
 constexpr u32 kListCap = 128;                 // short-list slots per classify workgroup
 constexpr u32 kSliceDiv = 8;                  // a chunk's slice of S holds a kSliceDiv-th of the chunk
 constexpr int kFinThreads = 1024;
@@ -189,7 +197,7 @@ struct EncodeCtl {
     u64 K_star;         // last winner in (key asc, index asc) order
     u32 J_star;
     u32 n_b, n_m;
-    u32 W;              // number of chunks, for the host-side statistics
+    u32 W, U, UC;       // chunks and their share-out, for the host-side statistics
     u64 count_greater, ties;
 };
 
@@ -204,6 +212,7 @@ struct Geom {
                         // more is read from the vector itself by the later kernels
     u32 W;              // chunks
     u32 U;              // wavefronts of classify / emit; wavefront u walks chunks u, u + U, ...
+    u32 UC;             // ... at most this many of them (W <= U * UC)
     u32 G3;             // classify / emit workgroups
     u32 L;              // sampled locations
     u32 nfine;          // linear histogram bins
@@ -243,7 +252,8 @@ static Geom make_geom(u64 d, u64 r, u64 k)
     g.cap = g.C / kSliceDiv;
     g.W = (u32)((d + per - 1) / per);
     g.U = g.W < kMaxUnits ? g.W : kMaxUnits;
-    g.G3 = (g.U + kWalkWaves - 1) / kWalkWaves;
+    g.UC = kUnitChunks;
+    g.G3 = (g.U + kWalkWaves - 1) / kWalkWaves;       // (the layout is sized for this many)
     const u64 loc = (d + 3) / 4;
     g.L = (u32)(loc < kSampleLoc ? loc : kSampleLoc);
     // Every workgroup of the streaming kernel stores its whole histogram: few
@@ -267,6 +277,15 @@ static Geom make_geom(u64 d, u64 r, u64 k)
     const u64 width = g.K_hi - g.K_lo;
     g.k_nlz = width ? (u32)__builtin_clzll(width) : 63u;
     return g;
+}
+
+// the walking kernels' share-out for a launch that serves nb vectors (see kBatchUnits)
+static void set_units(Geom &g, unsigned nb)
+{
+    const u32 units = nb >= kBatchMembers ? kBatchUnits : kMaxUnits;
+    g.U = g.W < units ? g.W : units;
+    g.UC = nb >= kBatchMembers ? kUnitChunksMax : kUnitChunks;
+    g.G3 = (g.U + kWalkWaves - 1) / kWalkWaves;
 }
 
 static EncodeLayout make_layout(const Geom &g)
@@ -769,7 +788,7 @@ fused_body(const float *__restrict__ grad, float *__restrict__ residual, Geom g,
             }
             keep(bits, valid, base);
         }
-        if (lane_id() == 0) seg_count[chunk_slot(w, g.U)] = run;
+        if (lane_id() == 0) seg_count[chunk_slot(w, g.U, g.UC)] = run;
     }
     if (kAll) return;
     if (lane_id() == 0 && n_above != 0u) atomicAdd(&h[bins.nfine], n_above);
@@ -799,7 +818,7 @@ struct Candidates {
     const uint2 *__restrict__ s_ent;
     const float *__restrict__ a;
     u64 d;
-    u32 C, U, cap;
+    u32 C, U, UC, cap;
     bool dense;         // every chunk is read from the vector (the estimate kept too little)
 
     __device__ __forceinline__ u32 length(u32 s) const
@@ -813,7 +832,7 @@ struct Candidates {
     // lower bound is below every threshold the later kernels compare with)
     __device__ __forceinline__ u32 count(u32 s, bool *from_vector) const
     {
-        const u32 kept = dense ? 0u : seg_count[chunk_slot(s, U)];
+        const u32 kept = dense ? 0u : seg_count[chunk_slot(s, U, UC)];
         *from_vector = dense || kept > cap;
         return *from_vector ? length(s) : kept;
     }
@@ -1031,7 +1050,7 @@ struct ChunkWalk {
 };
 constexpr u32 kRowQueue = 512;               // ring of one wavefront (ChunkWalk::kRowQueueSize entries)
 
-using UnitWalk = ChunkWalk<kUnitChunks>;     // classify / emit: chunks u, u + U, u + 2U, ...
+using UnitWalk = ChunkWalk<kUnitChunksMax>;  // classify / emit: chunks u, u + U, u + 2U, ...
 
 // per-element form of a row callback: f(valid, i, index, pattern) for the four
 // elements of a lane, from one call site (the loop is kept rolled)
@@ -1187,8 +1206,8 @@ classify_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
            u32 *__restrict__ b_mag, u32 *__restrict__ b_idx)
 {
     __shared__ u32 cnt_m, cnt_b, cnt_sure, bmin_s, bmax_s;
-    __shared__ u32 per_chunk[kWalkWaves][kUnitChunks];
-    __shared__ u32 per_chunk_b[kWalkWaves][kUnitChunks];
+    __shared__ u32 per_chunk[kWalkWaves][kUnitChunksMax];
+    __shared__ u32 per_chunk_b[kWalkWaves][kUnitChunksMax];
     __shared__ uint2 row_queue[kWalkWaves][kRowQueue];
     const u32 wave = threadIdx.x / kWave, lane = lane_id();
     const u32 u = blockIdx.x * kWalkWaves + wave;
@@ -1201,10 +1220,10 @@ classify_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
         }
         return;
     }
-    const Candidates cand{seg_count, s_ent, a, g.d, g.C, g.U, g.cap, false};
+    const Candidates cand{seg_count, s_ent, a, g.d, g.C, g.U, g.UC, g.cap, false};
     const UnitWalk walk(cand, u < g.U ? u : g.W, g.U, g.W);
     if (threadIdx.x == 0) { cnt_m = 0u; cnt_b = 0u; cnt_sure = 0u; bmin_s = 0xFFFFFFFFu; bmax_s = 0u; }
-    if (lane < kUnitChunks) { per_chunk[wave][lane] = 0u; per_chunk_b[wave][lane] = 0u; }
+    if (lane < kUnitChunksMax) { per_chunk[wave][lane] = 0u; per_chunk_b[wave][lane] = 0u; }
     __syncthreads();
     u32 lane_bmin = 0xFFFFFFFFu, lane_bmax = 0u;      // what this lane has already reported
 
@@ -1253,7 +1272,7 @@ classify_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, const float *__restrict__
     __builtin_amdgcn_wave_barrier();
     // certain winners, and entries of the deciding bin, of each of the wavefront's chunks
     u32 mine = 0;
-    if (u < g.U && lane < kUnitChunks) {
+    if (u < g.U && lane < g.UC) {
         const u32 s = u + lane * g.U;
         if (s < g.W) {
             mine = per_chunk[wave][lane];
@@ -1597,12 +1616,12 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, WideScratch *wide_ws,
     __shared__ u32 extra_m, sure_extra;
     __shared__ unsigned long long gt_extra;
     __shared__ u32 run_chunk, run_before, run_index, run_found;
-    __shared__ u32 run_sure[kFinWaves][kUnitChunks];
+    __shared__ u32 run_sure[kFinWaves][kUnitChunksMax];
 
     const u32 tid = threadIdx.x;
     const u32 wave = tid / kWave, lane = lane_id();
     const bool dense = ctl->dense != 0u;
-    Candidates cand{seg_count, s_ent, a, g.d, g.C, g.U, g.cap, dense};
+    Candidates cand{seg_count, s_ent, a, g.d, g.C, g.U, g.UC, g.cap, dense};
     // every candidate, split wavefront by chunk; f(index, pattern, chunk)
     auto each_s = [&](auto &&f) {
         // kWave consecutive chunks per wavefront at a time: their sizes in one round of
@@ -2027,8 +2046,8 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, WideScratch *wide_ws,
                 // and reach the chunk's counter as one addition.
                 const u32 s_end = run_chunk + 1u;
                 u32 my_sure = 0;
-                for (u32 first = wave * kUnitChunks; first < s_end; first += kFinWaves * kUnitChunks) {
-                    if (lane < kUnitChunks) run_sure[wave][lane] = 0u;
+                for (u32 first = wave * kUnitChunksMax; first < s_end; first += kFinWaves * kUnitChunksMax) {
+                    if (lane < kUnitChunksMax) run_sure[wave][lane] = 0u;
                     __builtin_amdgcn_wave_barrier();
                     const UnitWalk walk(cand, first, 1u, s_end);
                     auto run_member = [&](bool valid, u32 i, u32 idx, u32 bits) {
@@ -2041,7 +2060,7 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, WideScratch *wide_ws,
                     });
                     walk.for_each_vector_row(cand, each_of_row(run_member));
                     __builtin_amdgcn_wave_barrier();
-                    if (lane < kUnitChunks && first + lane < s_end && run_sure[wave][lane])
+                    if (lane < kUnitChunksMax && first + lane < s_end && run_sure[wave][lane])
                         atomicAdd(&win_cnt[first + lane], run_sure[wave][lane]);
                     __builtin_amdgcn_wave_barrier();
                 }
@@ -2235,6 +2254,8 @@ finalize_body(Geom g, PhiloxSeed seed, EncodeCtl *ctl, WideScratch *wide_ws,
         ctl->n_b = n_bd;
         ctl->n_m = n_mm;
         ctl->W = g.W;
+        ctl->U = g.U;
+        ctl->UC = g.UC;
         ctl->count_greater = count_greater;
         ctl->ties = g.r - count_greater;
     }
@@ -2257,10 +2278,10 @@ emit_body(Geom g, PhiloxSeed seed, const EncodeCtl *__restrict__ ctl,
     const u32 u = blockIdx.x * kWalkWaves + threadIdx.x / kWave;
     if (u >= g.U) return;
     const u32 lane = lane_id();
-    const Candidates cand{seg_count, s_ent, residual, g.d, g.C, g.U, g.cap, ctl->dense != 0u};
+    const Candidates cand{seg_count, s_ent, residual, g.d, g.C, g.U, g.UC, g.cap, ctl->dense != 0u};
     const UnitWalk walk(cand, u < g.U ? u : g.W, g.U, g.W);
     const u32 my_chunk = u + lane * g.U;
-    const u32 my_base = (lane < kUnitChunks && my_chunk < g.W) ? chunk_base[my_chunk] : 0u;
+    const u32 my_base = (lane < g.UC && my_chunk < g.W) ? chunk_base[my_chunk] : 0u;
     const u32 T = ctl->T, I_star = ctl->I_star;
     const Pair96 kcut{ctl->K_star, ctl->J_star};
     const u64 below = lanes_below();
@@ -2621,6 +2642,8 @@ static int encode_batch_impl(uint32_t n, const float *const *grad, float *const 
 
     for (uint32_t first = 0; first < n; first += kMaxBatch) {
         const unsigned nb = n - first < kMaxBatch ? n - first : kMaxBatch;
+        Geom gg = g;                    // this launch group's share-out of the walking kernels
+        set_units(gg, nb);
         Batch B{};
         for (unsigned i = 0; i < nb; ++i) {
             B.grad[i] = grad[first + i];
@@ -2640,35 +2663,35 @@ static int encode_batch_impl(uint32_t n, const float *const *grad, float *const 
             // r == d (random-k): no estimate, no histogram, no threshold
             StageScope sc(trace, RTOPK_STAGE_FUSED, stream);
             if (vec4)
-                k_fused<true, true><<<fg, kFusedThreads, kFusedLdsClaim, stream>>>(B, g, L);
+                k_fused<true, true><<<fg, kFusedThreads, kFusedLdsClaim, stream>>>(B, gg, L);
             else
-                k_fused<false, true><<<fg, kFusedThreads, kFusedLdsClaim, stream>>>(B, g, L);
+                k_fused<false, true><<<fg, kFusedThreads, kFusedLdsClaim, stream>>>(B, gg, L);
             RTOPK_LAUNCH_CHECK();
         } else {
             {
                 StageScope sc(trace, RTOPK_STAGE_PREPARE, stream);
                 k_sample<<<dim3(kSampleLoc / kSampleThreads, 1, nb), kSampleThreads, 0, stream>>>(
-                    B, g, L);
+                    B, gg, L);
                 RTOPK_LAUNCH_CHECK();
-                k_estimate<<<dim3(1, 1, nb), kEstThreads, 0, stream>>>(B, g, L);
+                k_estimate<<<dim3(1, 1, nb), kEstThreads, 0, stream>>>(B, gg, L);
                 RTOPK_LAUNCH_CHECK();
             }
             {
                 StageScope sc(trace, RTOPK_STAGE_FUSED, stream);
                 if (vec4)
-                    k_fused<true, false><<<fg, kFusedThreads, kFusedLdsClaim, stream>>>(B, g, L);
+                    k_fused<true, false><<<fg, kFusedThreads, kFusedLdsClaim, stream>>>(B, gg, L);
                 else
-                    k_fused<false, false><<<fg, kFusedThreads, kFusedLdsClaim, stream>>>(B, g, L);
+                    k_fused<false, false><<<fg, kFusedThreads, kFusedLdsClaim, stream>>>(B, gg, L);
                 RTOPK_LAUNCH_CHECK();
             }
         }
         {
             StageScope sc(trace, RTOPK_STAGE_CLASSIFY, stream);
             if (!g.all_members) {
-                k_pick<<<dim3(1, 1, nb), kPickThreads, 0, stream>>>(B, fgrid, g, L);
+                k_pick<<<dim3(1, 1, nb), kPickThreads, 0, stream>>>(B, fgrid, gg, L);
                 RTOPK_LAUNCH_CHECK();
             }
-            k_classify<<<dim3(g.G3, 1, nb), kWalkThreads, 0, stream>>>(B, g, L);
+            k_classify<<<dim3(gg.G3, 1, nb), kWalkThreads, 0, stream>>>(B, gg, L);
             RTOPK_LAUNCH_CHECK();
         }
         {
@@ -2681,12 +2704,12 @@ static int encode_batch_impl(uint32_t n, const float *const *grad, float *const 
                 fin_grid = 256u / nb;
                 fin_grid = fin_grid > kWideBlocks ? kWideBlocks : (fin_grid < 16u ? 16u : fin_grid);
             }
-            k_finalize<<<dim3(fin_grid, 1, nb), kFinThreads, 0, stream>>>(B, g, L);
+            k_finalize<<<dim3(fin_grid, 1, nb), kFinThreads, 0, stream>>>(B, gg, L);
             RTOPK_LAUNCH_CHECK();
         }
         {
             StageScope sc(trace, RTOPK_STAGE_EMIT, stream);
-            k_emit<<<dim3(g.G3, 1, nb), kWalkThreads, 0, stream>>>(B, g, L);
+            k_emit<<<dim3(gg.G3, 1, nb), kWalkThreads, 0, stream>>>(B, gg, L);
             RTOPK_LAUNCH_CHECK();
         }
     }
@@ -2752,14 +2775,14 @@ extern "C" int rtopk_encode_stats(const void *workspace, void *stream_v,
         return RTOPK_EHIP;
     // candidates kept by the streaming kernel: the chunk sizes, added up here
     uint64_t superset = 0;
-    if (c.W > 0 && c.W <= kTargetChunks) {
+    if (c.W > 0 && c.W <= kTargetChunks && c.U > 0 && c.UC > 0 && (u64)c.U * c.UC <= kTargetChunks &&
+        c.W <= c.U * c.UC) {
         const EncodeLayout L = make_layout(Geom{});   // the offset of seg_count is fixed
         std::vector<u32> counts(kTargetChunks);
         if (hipMemcpy(counts.data(), (const char *)workspace + L.seg_count,
                       (size_t)kTargetChunks * 4, hipMemcpyDeviceToHost) != hipSuccess)
             return RTOPK_EHIP;
-        const u32 U = c.W < kMaxUnits ? c.W : kMaxUnits;
-        for (u32 s2 = 0; s2 < c.W; ++s2) superset += counts[chunk_slot(s2, U)];
+        for (u32 s2 = 0; s2 < c.W; ++s2) superset += counts[chunk_slot(s2, c.U, c.UC)];
     }
     host_out->error_flags = c.err;
     host_out->path = c.path | (c.dense ? 2u : 0u);
