@@ -751,7 +751,11 @@ def rt_ws(u, d, r, k):
 # several vectors in one call: every member exactly as if encoded alone
 # --------------------------------------------------------------------------
 @pytest.mark.parametrize("n,d,misalign", [(3, 150_001, None), (8, 70_000, None), (17, 20_011, None),
-                                          (4, 90_004, 2)])
+                                          (4, 90_004, 2),
+                                          # chunk counts around the walking kernels' share-out of a
+                                          # batch (2048 wavefronts of up to 16 chunks): 2,930 and 5,860
+                                          # chunks, and 20 members in launches of 16 + 4
+                                          (4, 3_000_003, None), (5, 6_000_001, 1), (20, 2_200_000, None)])
 def test_batch_members_match_the_oracle_one_by_one(n, d, misalign):
     import torch
     u = _u()
