@@ -15,10 +15,14 @@ Order of the run (default flags):
   warm-up      W steps
   steady loop  ``--steady-steps`` further steps (at least 100 ms of device
                time), timed as a whole and with the dominant kernel of every
-               step bracketed: the device is at its steady clocks afterwards,
-               and the line shows the kernel's mean over the first and the
-               last tenth of the loop
-  timed region EXACTLY K steps between two synchronisations -> ``value``
+               ``--trace-every``-th step bracketed by HIP events: the device
+               is at its steady clocks afterwards, and the line shows the
+               kernel's mean over the first and the last tenth of the loop
+  timed region EXACTLY K steps between two synchronisations -> ``value``;
+               the dominant kernel of every ``--trace-every``-th of them is
+               bracketed in the same way -> ``roofline`` (a bracket holds the
+               stream up for ~5 us on either side of the kernel, which is why
+               not every step carries one)
   legs         (outside the timed region) the encode / aggregate split of a
                step, one ``rtopk_encode`` call per worker (``per_call``), the
                fused master updates, a bare streaming add over the same
@@ -161,11 +165,13 @@ class Job:
         return last
 
 
-def timed_loop(job, torch, ev, grad_sets, steps, as_batch=True, trace_all=True):
+def timed_loop(job, torch, ev, grad_sets, steps, as_batch=True, trace_all=True, trace_every=1):
     """``steps`` steps on job.stream between two events; returns (ms per step,
-    list of per-step durations of the dominant kernel in ms)."""
+    list of durations of the dominant kernel in ms, one per bracketed step).
+    Every ``trace_every``-th step has its dominant kernel bracketed by HIP
+    events: each bracket costs the stream ~5 us on either side of the kernel."""
     n = job.n
-    pairs = [ev.pair() if trace_all else None for _ in range(steps)]
+    pairs = [ev.pair() if trace_all and s % trace_every == 0 else None for s in range(steps)]
     t0 = torch.cuda.Event(enable_timing=True)
     t1 = torch.cuda.Event(enable_timing=True)
     t0.record(job.stream)
@@ -321,6 +327,9 @@ def main() -> int:
     ap.add_argument("--workers", type=int, default=0, help="override the workload's worker count")
     ap.add_argument("--steady-steps", type=int, default=240, metavar="S",
                     help="steps of the steady loop that precedes the timed region (0 = none)")
+    ap.add_argument("--trace-every", type=int, default=4, metavar="N",
+                    help="bracket the dominant kernel with HIP events on every N-th step of the steady "
+                         "loop and the timed region (each bracket costs the stream ~10 us)")
     ap.add_argument("--grad-sets", type=int, default=6, metavar="G",
                     help="distinct gradient sets resident in HBM; step s uses set s mod G")
     ap.add_argument("--sequential", action="store_true",
@@ -358,6 +367,7 @@ def main() -> int:
     d, r, k = wl.d, wl.r, wl.k
     n = args.workers or wl.n_workers
     K, W = args.steps, args.warmup
+    TE = max(1, min(args.trace_every, K))
     batched = not args.sequential
 
     # ---- inputs: G gradient sets resident in HBM, cycled ------------------
@@ -376,8 +386,8 @@ def main() -> int:
     steady = None
     if args.steady_steps > 0:
         S = args.steady_steps
-        ms_s, fused_s = timed_loop(job, torch, ev, grad_sets, S, batched)
-        tenth = max(1, S // 10)
+        ms_s, fused_s = timed_loop(job, torch, ev, grad_sets, S, batched, trace_every=TE)
+        tenth = max(1, len(fused_s) // 10)
         steady = {"steps": S, "ms_per_step": round(ms_s, 4), "region_ms": round(ms_s * S, 1),
                   "value": round(n * 4.0 * d / (ms_s * 1e-3) / 1e9, 2), "unit": "GB/s",
                   "k_fused_ms_first_tenth": round(mean(fused_s[:tenth]), 5),
@@ -388,7 +398,7 @@ def main() -> int:
     # ---- timed region: EXACTLY K steps between two synchronisations --------
     torch.cuda.synchronize()
     t_wall0 = time.perf_counter()
-    ms_per_step, fused_ms = timed_loop(job, torch, ev, grad_sets, K, batched)
+    ms_per_step, fused_ms = timed_loop(job, torch, ev, grad_sets, K, batched, trace_every=TE)
     t_wall1 = time.perf_counter()
     stats = job.check_stats("timed region")
     vectors_per_launch = n if batched else 1
@@ -523,6 +533,7 @@ def main() -> int:
             "vectors_per_launch": vectors_per_launch,
             "avg_launch_ms": round(fused_ms_avg, 5),
             "launches": len(fused_ms),
+            "launches_bracketed": f"every {TE}th step of the timed region" if TE > 1 else "every step of the timed region",
             "stream_add_calibration": stream_add,
         },
     }
