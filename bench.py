@@ -214,7 +214,7 @@ def measure_config(rt, torch, dev, stream, ev, wl, r, k, n, grads, steps, warmup
     for _ in range(warmup):
         job.step(grads)
     torch.cuda.synchronize()
-    ms_step, fused = timed_loop(job, torch, ev, [grads], steps)
+    ms_step, fused = timed_loop(job, torch, ev, [grads], steps, trace_every=max(1, min(4, steps // 2)))
     enc, agg, _ = split_loop(job, torch, [grads], min(steps, 5))
     st = job.check_stats(f"{wl.config.name} r={r} k={k}")
     # the bare read-read-write stream over the same buffers, for this size's ceiling
